@@ -1,0 +1,208 @@
+/*
+ * CPU oracle for the AdaTopK compress / decompress path.
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE.  It is the slow, plain statement of what the
+ * path computes, used only by the tests, the smoke check and the benchmark's CPU
+ * baseline leg.  The product library never links, loads or calls it, and it shares
+ * no code with the HIP kernels.
+ *
+ * What it computes (paper Sec. 5.1, caption of the Top-K sparsification figure:
+ * of a d-vector the k entries of largest absolute value are communicated as
+ * (index, value) pairs and every other entry is zero after decompression;
+ * Sec. 5.2, Eq. "adacompress": the per-link ratio rule):
+ *
+ *   1. key_i  = bit pattern of x_i with the sign bit cleared, read as an unsigned
+ *               integer (31 bits for fp32, 15 bits for bf16).  Ordering keys is
+ *               ordering |x| for every finite value, and extends it to Inf / NaN.
+ *   2. sort all (key_i, i) by key descending, then index ascending  (full sort).
+ *   3. the first k pairs are the selected set.
+ *   4. sort the selected set by index ascending; emit idx[j] and val[j] = the
+ *      untouched bits of x[idx[j]].
+ *   5. err = (float) sqrt( sum over the non-selected i of (double)x_i^2 ),
+ *      summed in index order in fp64.
+ *   6. decompress: y = n entries of +0.0, then y[idx[j]] = val[j].
+ *
+ * Readings where the paper is silent: ties at the threshold go to the lowest
+ * index; output is in ascending index order; indices are 32-bit; the error norm
+ * is the L2 norm of the residual x - decompress(compress(x)).
+ *
+ * Pins (tests, CPU only): brute-force repeated arg-max and exhaustive subsets on
+ * tiny inputs, selection invariants, agreement with numpy lexsort / torch.topk on
+ * distinct magnitudes, closed forms (all-equal, k = n, k = 1, pre-sorted input),
+ * err^2 = |x|^2 - |val|^2, the Gaussian closed form of the relative error, the
+ * paper's wire-size arithmetic and a hand-worked example of Eq. "adacompress".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct {
+    uint32_t key;
+    int32_t idx;
+} oracle_pair;
+
+static int cmp_key_desc_idx_asc(const void *pa, const void *pb) {
+    const oracle_pair *a = (const oracle_pair *)pa;
+    const oracle_pair *b = (const oracle_pair *)pb;
+    if (a->key != b->key) return (a->key > b->key) ? -1 : 1;
+    if (a->idx != b->idx) return (a->idx < b->idx) ? -1 : 1;
+    return 0;
+}
+
+static int cmp_idx_asc(const void *pa, const void *pb) {
+    const int32_t a = *(const int32_t *)pa, b = *(const int32_t *)pb;
+    return (a > b) - (a < b);
+}
+
+static float bf16_to_f32(uint16_t h) {
+    uint32_t u = ((uint32_t)h) << 16; /* exact widening */
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+/* Steps 1-4: fills idx[k] (ascending).  keys[] holds key_i for all i.  The caller
+ * owns every buffer.  Returns 0, or -1 on bad arguments / out of memory. */
+static int select_topk(const uint32_t *keys, int64_t n, int64_t k, int32_t *idx) {
+    if (n < 0 || k < 0 || k > n || n > INT32_MAX) return -1;
+    if (k == 0) return 0;
+    oracle_pair *p = (oracle_pair *)malloc((size_t)n * sizeof *p);
+    if (!p) return -1;
+    for (int64_t i = 0; i < n; ++i) {
+        p[i].key = keys[i];
+        p[i].idx = (int32_t)i;
+    }
+    qsort(p, (size_t)n, sizeof *p, cmp_key_desc_idx_asc);
+    for (int64_t j = 0; j < k; ++j) idx[j] = p[j].idx;
+    free(p);
+    qsort(idx, (size_t)k, sizeof *idx, cmp_idx_asc);
+    return 0;
+}
+
+int oracle_compress_f32(const float *x, int64_t n, int64_t k, int32_t *idx, float *val, float *err) {
+    if (n < 0 || k < 0 || k > n || n > INT32_MAX) return -1;
+    uint32_t *keys = (uint32_t *)malloc((size_t)(n > 0 ? n : 1) * sizeof *keys);
+    uint8_t *sel = (uint8_t *)calloc((size_t)(n > 0 ? n : 1), 1);
+    if (!keys || !sel) { free(keys); free(sel); return -1; }
+    for (int64_t i = 0; i < n; ++i) {
+        uint32_t u;
+        memcpy(&u, &x[i], sizeof u);
+        keys[i] = u & 0x7FFFFFFFu;
+    }
+    int rc = select_topk(keys, n, k, idx);
+    if (rc == 0) {
+        for (int64_t j = 0; j < k; ++j) {
+            memcpy(&val[j], &x[idx[j]], sizeof(float)); /* bits, not a float move */
+            sel[idx[j]] = 1;
+        }
+        if (err) {
+            double s = 0.0;
+            for (int64_t i = 0; i < n; ++i)
+                if (!sel[i]) s += (double)x[i] * (double)x[i];
+            *err = (float)sqrt(s);
+        }
+    }
+    free(keys);
+    free(sel);
+    return rc;
+}
+
+int oracle_compress_bf16(const uint16_t *x, int64_t n, int64_t k, int32_t *idx, uint16_t *val, float *err) {
+    if (n < 0 || k < 0 || k > n || n > INT32_MAX) return -1;
+    uint32_t *keys = (uint32_t *)malloc((size_t)(n > 0 ? n : 1) * sizeof *keys);
+    uint8_t *sel = (uint8_t *)calloc((size_t)(n > 0 ? n : 1), 1);
+    if (!keys || !sel) { free(keys); free(sel); return -1; }
+    for (int64_t i = 0; i < n; ++i) keys[i] = (uint32_t)(x[i] & 0x7FFFu);
+    int rc = select_topk(keys, n, k, idx);
+    if (rc == 0) {
+        for (int64_t j = 0; j < k; ++j) {
+            val[j] = x[idx[j]];
+            sel[idx[j]] = 1;
+        }
+        if (err) {
+            double s = 0.0;
+            for (int64_t i = 0; i < n; ++i)
+                if (!sel[i]) {
+                    double v = (double)bf16_to_f32(x[i]);
+                    s += v * v;
+                }
+            *err = (float)sqrt(s);
+        }
+    }
+    free(keys);
+    free(sel);
+    return rc;
+}
+
+/* Step 6.  Indices must be unique and inside [0, n); anything else is an error. */
+int oracle_decompress_f32(const int32_t *idx, const float *val, int64_t k, float *y, int64_t n) {
+    if (n < 0 || k < 0) return -1;
+    memset(y, 0, (size_t)n * sizeof *y);
+    for (int64_t j = 0; j < k; ++j) {
+        if (idx[j] < 0 || (int64_t)idx[j] >= n) return -1;
+        memcpy(&y[idx[j]], &val[j], sizeof(float));
+    }
+    return 0;
+}
+
+int oracle_decompress_bf16(const int32_t *idx, const uint16_t *val, int64_t k, uint16_t *y, int64_t n) {
+    if (n < 0 || k < 0) return -1;
+    memset(y, 0, (size_t)n * sizeof *y);
+    for (int64_t j = 0; j < k; ++j) {
+        if (idx[j] < 0 || (int64_t)idx[j] >= n) return -1;
+        y[idx[j]] = val[j];
+    }
+    return 0;
+}
+
+/* Segmented variant: the single-tensor routine once per tensor.  x is the
+ * concatenation of the S tensors; tensor s starts at in_offset[s] (S+1 entries) and
+ * its outputs start at out_offset[s] (S+1 entries, the exclusive scan of k). */
+int oracle_compress_segmented_f32(const float *x, const int64_t *in_offset, const int64_t *k, int32_t S,
+                                  int32_t *idx, float *val, const int64_t *out_offset, float *err) {
+    for (int32_t s = 0; s < S; ++s) {
+        int rc = oracle_compress_f32(x + in_offset[s], in_offset[s + 1] - in_offset[s], k[s],
+                                     idx + out_offset[s], val + out_offset[s], err ? err + s : NULL);
+        if (rc) return rc;
+    }
+    return 0;
+}
+
+int oracle_compress_segmented_bf16(const uint16_t *x, const int64_t *in_offset, const int64_t *k, int32_t S,
+                                   int32_t *idx, uint16_t *val, const int64_t *out_offset, float *err) {
+    for (int32_t s = 0; s < S; ++s) {
+        int rc = oracle_compress_bf16(x + in_offset[s], in_offset[s + 1] - in_offset[s], k[s],
+                                      idx + out_offset[s], val + out_offset[s], err ? err + s : NULL);
+        if (rc) return rc;
+    }
+    return 0;
+}
+
+/* Sec. 5.2, Eq. "adacompress": r_i = max(1, coeff * r * R_i / max_p R_p); the paper's
+ * coefficient is 3 (fp32 value + int64 index).  R are the estimated uncompressed
+ * communication times of the m links. */
+int oracle_adaptive_ratios(const double *R, int32_t m, double r, double coeff, double *r_out) {
+    if (m <= 0 || !(r > 0.0) || !(coeff > 0.0)) return -1;
+    double Rmax = R[0];
+    for (int32_t i = 0; i < m; ++i) {
+        if (!(R[i] >= 0.0)) return -1;
+        if (R[i] > Rmax) Rmax = R[i];
+    }
+    if (!(Rmax > 0.0)) return -1;
+    for (int32_t i = 0; i < m; ++i) {
+        double v = coeff * r * R[i] / Rmax;
+        r_out[i] = v > 1.0 ? v : 1.0;
+    }
+    return 0;
+}
+
+/* A ratio r_i keeps one element in r_i: k = max(1, floor(n / r_i)), at most n. */
+int64_t oracle_k_for_ratio(int64_t n, double r_i) {
+    if (n <= 0 || !(r_i >= 1.0)) return n <= 0 ? 0 : -1;
+    double q = floor((double)n / r_i);
+    int64_t k = (int64_t)q;
+    if (k < 1) k = 1;
+    if (k > n) k = n;
+    return k;
+}

@@ -1,0 +1,287 @@
+"""Pins of the CPU oracle against things other than itself (CPU only).
+
+The paper prints no worked numeric example of the Top-K step (its illustration is a
+figure), so the selection is pinned by the definition in Sec. 5.1 (the k entries of
+largest absolute value are sent as (index, value) pairs, the rest decompress to 0):
+brute force, exhaustive subsets, invariants, library special cases and closed forms.
+The error norm is pinned by an fp64 identity and by the Gaussian closed form; the ratio
+rule by Eq. "adacompress" (Sec. 5.2) worked by hand, and by the wire-size arithmetic the
+paper prints (tests/golden/).
+"""
+import itertools
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import adatopk_oracle as orc
+from paper_2410_12707_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------------------- helpers
+def magnitudes(x):
+    """|x| as float64 for finite inputs (fp32 array, or uint16 bf16 bit patterns)."""
+    if x.dtype == np.uint16:
+        x = wl.bf16_bits_to_f32(x)
+    return np.abs(x.astype(np.float64))
+
+
+def brute_force_topk(mag, k):
+    """k rounds of: scan for the largest magnitude, first occurrence wins, remove it."""
+    mag = list(mag)
+    taken = []
+    alive = [True] * len(mag)
+    for _ in range(k):
+        best = -1
+        for i, m in enumerate(mag):
+            if alive[i] and (best < 0 or m > mag[best]):
+                best = i
+        alive[best] = False
+        taken.append(best)
+    return sorted(taken)
+
+
+def bits(a):
+    return a.view(np.uint32) if a.dtype == np.float32 else a.view(np.uint16)
+
+
+KINDS = ["normal", "few_levels", "all_equal", "sparse", "signed_zero_mix", "descending", "ascending"]
+
+
+# ----------------------------------------------------------------------- brute force
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("kind", KINDS)
+def test_selection_matches_repeated_argmax(kind, dtype):
+    for n in (1, 2, 7, 64, 193):
+        x = wl.small_case(kind, n, seed=100 + n, dtype=dtype)
+        mag = magnitudes(x)
+        for k in sorted({0, 1, n // 3, n - 1, n} - {-1}):
+            if k < 0:
+                continue
+            idx, val, _ = orc.compress(x, k)
+            assert idx.tolist() == brute_force_topk(mag, k), (kind, dtype, n, k)
+            assert np.array_equal(bits(val), bits(x)[idx])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_selection_is_optimal_and_lexicographically_first_over_all_subsets(dtype):
+    # For n <= 10 enumerate every k-subset: the chosen one must have the largest multiset
+    # of magnitudes (compared as sorted-descending tuples) and, among those, the smallest
+    # sorted index tuple.
+    for seed, kind in enumerate(["few_levels", "normal", "sparse", "few_levels"]):
+        n = 7 + seed
+        x = wl.small_case(kind, n, seed=900 + seed, dtype=dtype)
+        mag = magnitudes(x)
+        for k in range(0, n + 1):
+            best = None
+            for sub in itertools.combinations(range(n), k):
+                score = (tuple(sorted((mag[i] for i in sub), reverse=True)), tuple(-i for i in sub))
+                if best is None or score > best[0]:
+                    best = (score, sub)
+            idx, _, _ = orc.compress(x, k)
+            assert tuple(idx.tolist()) == best[1], (kind, n, k)
+
+
+# ------------------------------------------------------------------------- invariants
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("kind", ["normal", "few_levels", "sparse", "nonfinite", "random_bits"])
+def test_selection_invariants(kind, dtype):
+    n = 50_021
+    x = wl.small_case(kind, n, seed=7, dtype=dtype)
+    sign_clear = np.uint32(0x7FFFFFFF) if dtype == "f32" else np.uint16(0x7FFF)
+    key = bits(x) & sign_clear
+    for k in (1, 500, n // 2, n - 1):
+        idx, val, _ = orc.compress(x, k)
+        assert idx.dtype == np.int32 and idx.size == k
+        assert np.all(np.diff(idx.astype(np.int64)) > 0) and idx[0] >= 0 and idx[-1] < n
+        assert np.array_equal(bits(val), bits(x)[idx])
+        mask = np.zeros(n, dtype=bool)
+        mask[idx] = True
+        kmin = key[mask].min()
+        assert kmin >= key[~mask].max()
+        # lowest index wins among elements that tie with the smallest kept key
+        tied_dropped = np.nonzero(~mask & (key == kmin))[0]
+        tied_kept = np.nonzero(mask & (key == kmin))[0]
+        if tied_dropped.size:
+            assert tied_kept.max() < tied_dropped.min()
+
+
+# ---------------------------------------------------------- library special cases
+def test_distinct_magnitudes_agree_with_numpy_and_torch():
+    import torch
+
+    rng = np.random.Generator(np.random.PCG64(5))
+    n = 20_000
+    # distinct magnitudes by construction: a permutation of 1..n scaled, random signs
+    x = (rng.permutation(n).astype(np.float32) + 1.0) * np.float32(0.125)
+    x *= rng.choice(np.array([-1.0, 1.0], dtype=np.float32), size=n)
+    for k in (1, 17, 2_000, n - 1, n):
+        idx, _, _ = orc.compress(x, k)
+        ref_np = np.sort(np.argsort(-np.abs(x), kind="stable")[:k])
+        ref_t = torch.topk(torch.from_numpy(x).abs(), k).indices.sort().values.numpy()
+        assert np.array_equal(idx, ref_np)
+        assert np.array_equal(idx, ref_t)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_lexsort_statement_of_the_definition(dtype):
+    # Same definition through numpy's lexsort (key descending, index ascending), with ties.
+    for kind in ("few_levels", "normal", "sparse"):
+        n = 30_011
+        x = wl.small_case(kind, n, seed=11, dtype=dtype)
+        mag = magnitudes(x)
+        order = np.lexsort((np.arange(n), -mag))
+        for k in (3, 999, n // 2):
+            idx, _, _ = orc.compress(x, k)
+            assert np.array_equal(idx, np.sort(order[:k]))
+
+
+# ---------------------------------------------------------------------- closed forms
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_closed_forms(dtype):
+    n = 1000
+    eq = wl.small_case("all_equal", n, 0, dtype)
+    for k in (1, 10, n):
+        idx, val, err = orc.compress(eq, k)
+        assert np.array_equal(idx, np.arange(k))
+        assert math.isclose(float(err), 1.5 * math.sqrt(n - k), rel_tol=1e-6)
+    x = wl.small_case("normal", n, 3, dtype)
+    idx, val, err = orc.compress(x, n)  # k = n is the identity
+    assert np.array_equal(idx, np.arange(n)) and np.array_equal(bits(val), bits(x)) and float(err) == 0.0
+    idx, val, _ = orc.compress(x, 1)  # k = 1: first occurrence of the largest magnitude
+    assert idx[0] == int(np.argmax(magnitudes(x)))
+    idx, val, err = orc.compress(x, 0)  # k = 0: nothing kept, everything is error
+    assert idx.size == 0 and math.isclose(float(err), math.sqrt(float(np.sum(magnitudes(x) ** 2))), rel_tol=1e-6)
+    d = wl.small_case("descending", 200, 0, dtype)  # distinct and exactly representable in bf16 up to 256
+    assert np.array_equal(orc.compress(d, 20)[0], np.arange(20))
+    a = wl.small_case("ascending", 200, 0, dtype)
+    assert np.array_equal(orc.compress(a, 20)[0], np.arange(180, 200))
+
+
+def test_negative_values_rank_by_magnitude_and_keep_their_sign():
+    x = np.array([0.5, -3.0, 2.0, -0.25, 3.0, -2.5], dtype=np.float32)
+    idx, val, err = orc.compress(x, 3)
+    assert idx.tolist() == [1, 4, 5]
+    assert val.tolist() == [-3.0, 3.0, -2.5]
+    assert math.isclose(float(err), math.sqrt(0.25 + 4.0 + 0.0625), rel_tol=1e-7)
+    idx, _, _ = orc.compress(x, 1)  # |-3| ties with |3|: lowest index
+    assert idx.tolist() == [1]
+
+
+def test_nonfinite_ordering_and_bit_exact_values():
+    u = np.array([0x3F800000, 0x7F800000, 0xFFC01234, 0x00000001, 0x80000000, 0x7FC00000, 0xFF800000], dtype=np.uint32)
+    x = u.view(np.float32)
+    # keys: NaN payload 0x7FC01234 > NaN 0x7FC00000 > Inf (two of them, index order) > 1.0 > denormal > -0
+    idx, val, _ = orc.compress(x, 4)
+    assert idx.tolist() == [1, 2, 5, 6]
+    assert np.array_equal(val.view(np.uint32), u[[1, 2, 5, 6]])
+    idx, val, _ = orc.compress(x, 6)
+    assert idx.tolist() == [0, 1, 2, 3, 5, 6]
+    assert val.view(np.uint32)[3] == 1  # denormal kept bit-exact (no flush to zero)
+
+
+# -------------------------------------------------------------------- reconstruction
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("kind", ["normal", "few_levels", "nonfinite"])
+def test_decompress_is_the_masked_input(kind, dtype):
+    n = 10_007
+    x = wl.small_case(kind, n, seed=21, dtype=dtype)
+    for k in (0, 1, 100, n):
+        idx, val, _ = orc.compress(x, k)
+        y = orc.decompress(idx, val, n)
+        mask = np.zeros(n, dtype=bool)
+        mask[idx] = True
+        expect = np.where(mask, bits(x), 0).astype(bits(x).dtype)  # +0.0 is the all-zero pattern
+        assert np.array_equal(bits(y), expect)
+        if k and kind != "nonfinite":
+            idx2, val2, _ = orc.compress(y, k)  # idempotent while the smallest kept magnitude is non-zero
+            if magnitudes(val).min() > 0:
+                assert np.array_equal(idx2, idx) and np.array_equal(bits(val2), bits(val))
+
+
+def test_decompress_accepts_any_order_and_rejects_out_of_range():
+    idx = np.array([5, 0, 3], dtype=np.int32)
+    val = np.array([1.0, -2.0, 3.0], dtype=np.float32)
+    assert orc.decompress(idx, val, 6).tolist() == [-2.0, 0.0, 0.0, 3.0, 0.0, 1.0]
+    with pytest.raises(ValueError):
+        orc.decompress(np.array([6], dtype=np.int32), val[:1], 6)
+
+
+# ------------------------------------------------------------------------ error norm
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_error_norm_identity_in_fp64(dtype):
+    n = 200_003
+    x = wl.small_case("normal", n, seed=33, dtype=dtype)
+    tot = float(np.sum(magnitudes(x) ** 2))
+    for k in (1, n // 100, n // 3):
+        idx, val, err = orc.compress(x, k)
+        kept = float(np.sum(magnitudes(val) ** 2))
+        assert err.dtype == np.float32
+        assert math.isclose(float(err), math.sqrt(tot - kept), rel_tol=2e-7)
+
+
+def test_error_norm_gaussian_closed_form():
+    # For i.i.d. N(0,1) and keep fraction rho, the dropped energy fraction tends to
+    # 1 - 2 [ t phi(t) + 1 - Phi(t) ] with t = Phi^{-1}(1 - rho/2).
+    from scipy.stats import norm
+
+    n = 4_000_000
+    x = wl.normal_f32(n, seed=44)
+    rho = 0.01
+    t = norm.ppf(1 - rho / 2)
+    expect = math.sqrt(1 - 2 * (t * norm.pdf(t) + 1 - norm.cdf(t)))
+    idx, val, err = orc.compress(x, int(n * rho))
+    rel = float(err) / math.sqrt(float(np.sum(x.astype(np.float64) ** 2)))
+    assert abs(rel - expect) < 2e-3
+    assert abs(float(np.min(np.abs(val))) - t) < 2e-2  # the threshold is the (1 - rho/2) quantile
+
+
+# --------------------------------------------------------------------------- segmented
+def test_segmented_is_per_tensor():
+    xs = [wl.small_case("normal", 5000, 1), wl.small_case("few_levels", 129, 2), wl.small_case("sparse", 1, 3),
+          np.empty(0, dtype=np.float32)]
+    ks = [50, 129, 0, 0]
+    idx, val, off, err = orc.compress_segmented(xs, ks)
+    assert off.tolist() == [0, 50, 179, 179, 179]
+    for s, (x, k) in enumerate(zip(xs, ks)):
+        i1, v1, e1 = orc.compress(x, k)
+        assert np.array_equal(idx[off[s]:off[s + 1]], i1)
+        assert np.array_equal(val[off[s]:off[s + 1]].view(np.uint32), v1.view(np.uint32))
+        assert err[s] == e1
+
+
+# ------------------------------------------------------------- ratio rule and wire size
+def test_adaptive_ratio_rule_hand_example():
+    with open(os.path.join(GOLDEN, "adacompress_hand_example.json")) as f:
+        g = json.load(f)
+    for case in g["cases"]:
+        out = orc.adaptive_ratios(case["R"], case["r"], case["coeff"])
+        assert np.allclose(out, case["r_i"], rtol=1e-12, atol=0)
+
+
+def test_wire_size_arithmetic_printed_in_the_paper():
+    with open(os.path.join(GOLDEN, "wire_size.json")) as f:
+        g = json.load(f)
+    # Top-K figure caption: a d-vector of 32-bit values (32 d bits) becomes k values plus k
+    # 32-bit indices (64 k bits).
+    d, k = 1_000_000, orc.k_for_ratio(1_000_000, g["ratio"])
+    assert k == d // g["ratio"]
+    assert 32 * d == g["fig_topk_dense_bits_per_element"] * d
+    assert (32 + 32) * k == g["fig_topk_wire_bits_per_kept"] * k
+    # Latency figure caption: at ratio 100 with fp32 values and int64 indices the data sent
+    # is 33.3x smaller; the same accounting gives the coefficient 3 of Eq. "adacompress".
+    shrink = (4 * d) / ((4 + 8) * k)
+    assert abs(shrink - g["latency_fig_shrink_at_ratio_100"]) < 0.05
+    assert (4 + 8) / 4 == g["adacompress_coefficient"]
+
+
+def test_k_for_ratio_rounding():
+    assert orc.k_for_ratio(393_216, 100.0) == 3_932  # 1 % of the GPT-2-small tensor, floor
+    assert orc.k_for_ratio(1000, 1.0) == 1000  # ratio 1: no compression
+    assert orc.k_for_ratio(1000, 3000.0) == 1  # never fewer than one element
+    assert orc.k_for_ratio(0, 10.0) == 0
+    assert orc.k_for_ratio(10, 0.5) == -1  # a ratio below 1 is not a compression ratio
