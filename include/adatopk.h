@@ -1,0 +1,110 @@
+/*
+ * adatopk.h -- C ABI of the MI355X (gfx950) AdaTopK compressor.
+ *
+ * The operation is the Top-K sparsification of the paper's Sec. 5.1 (caption of the
+ * Top-K figure): of a d-vector, the k entries of largest absolute value are sent as
+ * (index, value) pairs and every other entry is 0 after decompression.  Sec. 5.2
+ * (Eq. "adacompress") gives every slow link its own ratio, hence the segmented call
+ * with one k per tensor.
+ *
+ * Result, fixed where the paper is silent:
+ *   - key(x) = bit pattern of x with the sign bit cleared, compared as an unsigned
+ *     integer (so NaN > Inf > finite, and -0 ties with +0);
+ *   - the k largest keys are kept; ties at the k-th key go to the lowest indices;
+ *   - outputs are in ascending index order; values are the untouched bits of the input;
+ *   - err = L2 norm of (x - decompress(compress(x))) = sqrt(sum of squares of the
+ *     dropped entries), accumulated in fp64, returned as fp32;
+ *   - decompress writes +0.0 (all-zero bits) everywhere except at the given indices.
+ *
+ * Conventions for every call:
+ *   - "device" pointers are HIP device memory of the current device; "host" pointers
+ *     are ordinary process memory.  The caller owns every buffer.  The library never
+ *     allocates, frees or synchronises, and copies nothing back to the host: all
+ *     work is enqueued on `hip_stream` (a hipStream_t, NULL = the default stream)
+ *     and the call returns at once.  Output sizes are known beforehand (exactly k).
+ *   - a tensor is its flat contiguous buffer; indices are int32 and local to the
+ *     tensor (to the segment in the segmented call), so n must be below 2^31.
+ *   - bf16 values travel as 16-bit patterns.
+ *   - the workspace is scratch: contents are undefined between calls and it may be
+ *     reused by the next call on the same stream.  Calls that share a workspace
+ *     must be ordered by the stream.
+ *   - errors are returned as adatopk_status; nothing is enqueued when the status is
+ *     ADATOPK_EINVAL or ADATOPK_EWORKSPACE.
+ */
+#ifndef ADATOPK_H
+#define ADATOPK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { ADATOPK_F32 = 0, ADATOPK_BF16 = 1 } adatopk_dtype;
+
+typedef enum {
+    ADATOPK_OK = 0,
+    ADATOPK_EINVAL = 1,     /* bad n / k / dtype / offsets, NULL or misaligned pointer */
+    ADATOPK_EWORKSPACE = 2, /* workspace smaller than adatopk_workspace_bytes() */
+    ADATOPK_ERUNTIME = 3,   /* a HIP launch failed */
+    ADATOPK_ENOTIMPL = 4
+} adatopk_status;
+
+/* Bytes of device workspace that a compress call over `num_segments` tensors holding
+ * `n_total` elements in all needs (single-tensor call: num_segments = 1).  Returns 0
+ * for invalid arguments.  Host-only; touches no device. */
+size_t adatopk_workspace_bytes(int64_t n_total, int32_t num_segments, adatopk_dtype dt);
+
+/* Top-K sparsification of one tensor (Sec. 5.1).
+ *   dense         device, n values of type dt, aligned to the element size
+ *   k             0 <= k <= n; k == 0 or n == 0 keep nothing
+ *   idx_out       device, k int32: kept indices, ascending
+ *   val_out       device, k values of type dt: val_out[j] = bits of dense[idx_out[j]]
+ *   err_norm_out  device, 1 float, or NULL to skip the store
+ *   workspace     device, 256-byte aligned, at least adatopk_workspace_bytes(n, 1, dt)
+ * EINVAL: n < 0, k < 0, k > n, n >= 2^31, unknown dt, NULL where a buffer is needed,
+ * misaligned pointer.  EWORKSPACE: workspace too small. */
+adatopk_status adatopk_compress(const void *dense, int64_t n, adatopk_dtype dt, int64_t k,
+                                int32_t *idx_out, void *val_out, float *err_norm_out,
+                                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Decompression (Sec. 5.1): dense_out = +0.0 everywhere, then dense_out[idx[j]] = val[j].
+ *   idx, val   device, k entries; indices unique; any order (ascending is fastest)
+ *   dense_out  device, n values of type dt
+ * Indices outside [0, n) are skipped; with duplicate indices one of the values wins.
+ * k == 0 gives all zeros.  EINVAL as for compress. */
+adatopk_status adatopk_decompress(const int32_t *idx, const void *val, int64_t k, adatopk_dtype dt,
+                                  void *dense_out, int64_t n, void *hip_stream);
+
+/* Segmented compress: S independent tensors, tensor s with its own k[s] (the per-link
+ * ratios of Sec. 5.2), every pass launched once for all of them.
+ *   dense       host array of S device pointers
+ *   n, k        host arrays of S entries
+ *   out_offset  host array of S+1 entries, the exclusive scan of k: tensor s writes
+ *               idx_out / val_out entries [out_offset[s], out_offset[s+1])
+ *   idx_out, val_out  device, out_offset[S] entries
+ *   err_norm_out      device, S floats, or NULL
+ *   workspace   device, at least adatopk_workspace_bytes(sum of n, S, dt)
+ * The host arrays are read before the call returns.  EINVAL additionally when S < 0 or
+ * out_offset is not the scan of k. */
+adatopk_status adatopk_compress_segmented(const void *const *dense, const int64_t *n, const int64_t *k,
+                                          int32_t S, adatopk_dtype dt, int32_t *idx_out, void *val_out,
+                                          const int64_t *out_offset, float *err_norm_out,
+                                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Host-only: the adaptive ratio rule, Sec. 5.2, Eq. "adacompress":
+ *   r_out[i] = max(1, coeff * r_user * R[i] / max_p R[p])
+ * R = estimated uncompressed communication time of each of the m links (>= 0, not all
+ * zero); coeff = 3 in the paper (fp32 value + int64 index).  EINVAL otherwise. */
+adatopk_status adatopk_adaptive_ratios(const double *R, int32_t m, double r_user, double coeff,
+                                       double *r_out);
+
+/* Host-only: elements kept at ratio r_i >= 1: max(1, floor(n / r_i)), at most n; 0 when
+ * n <= 0; -1 when r_i < 1 or is NaN. */
+int64_t adatopk_k_for_ratio(int64_t n, double r_i);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADATOPK_H */

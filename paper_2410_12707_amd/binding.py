@@ -1,0 +1,178 @@
+"""Python names for the C ABI of ``libadatopk.so`` (see ``include/adatopk.h``).
+
+Argument marshalling only: every step of compress / decompress runs in the HIP kernels of
+the library.  torch supplies device memory and the current stream.  There is no fallback:
+if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libadatopk.so")
+
+F32, BF16 = 0, 1
+OK, EINVAL, EWORKSPACE, ERUNTIME, ENOTIMPL = 0, 1, 2, 3, 4
+_STATUS = {OK: "ADATOPK_OK", EINVAL: "ADATOPK_EINVAL", EWORKSPACE: "ADATOPK_EWORKSPACE",
+           ERUNTIME: "ADATOPK_ERUNTIME", ENOTIMPL: "ADATOPK_ENOTIMPL"}
+
+_lib = None
+
+
+class AdaTopKError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        super().__init__("%s returned %s" % (where, _STATUS.get(status, status)))
+        self.status = status
+
+
+def load_library() -> ctypes.CDLL:
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libadatopk.so is not built: run `python -m paper_2410_12707_amd.build` "
+                          "(or __graft_entry__.build()) first; there is no CPU fallback")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, i32, p, sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t
+    lib.adatopk_workspace_bytes.argtypes = [i64, i32, i32]
+    lib.adatopk_workspace_bytes.restype = sz
+    lib.adatopk_compress.argtypes = [p, i64, i32, i64, p, p, p, p, sz, p]
+    lib.adatopk_compress.restype = i32
+    lib.adatopk_decompress.argtypes = [p, p, i64, i32, p, i64, p]
+    lib.adatopk_decompress.restype = i32
+    lib.adatopk_compress_segmented.argtypes = [p, p, p, i32, i32, p, p, p, p, p, sz, p]
+    lib.adatopk_compress_segmented.restype = i32
+    lib.adatopk_adaptive_ratios.argtypes = [p, i32, ctypes.c_double, ctypes.c_double, p]
+    lib.adatopk_adaptive_ratios.restype = i32
+    lib.adatopk_k_for_ratio.argtypes = [i64, ctypes.c_double]
+    lib.adatopk_k_for_ratio.restype = i64
+    lib.adatopk_measure_enable.argtypes = [i32]
+    lib.adatopk_measure_enable.restype = i32
+    lib.adatopk_measure_stage_count.restype = i32
+    lib.adatopk_measure_stage_name.argtypes = [i32]
+    lib.adatopk_measure_stage_name.restype = ctypes.c_char_p
+    lib.adatopk_measure_read.argtypes = [p]
+    lib.adatopk_measure_read.restype = i32
+    lib.adatopk_measure_copy.argtypes = [p, p, sz, p]
+    lib.adatopk_measure_copy.restype = i32
+    lib.adatopk_measure_read_only.argtypes = [p, sz, p, p]
+    lib.adatopk_measure_read_only.restype = i32
+    lib.adatopk_measure_fill.argtypes = [p, sz, p]
+    lib.adatopk_measure_fill.restype = i32
+    _lib = lib
+    return lib
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise AdaTopKError(status, where)
+
+
+def _dtype_code(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return F32
+    if t == torch.bfloat16:
+        return BF16
+    raise TypeError("adatopk supports float32 and bfloat16 tensors, got %s" % t)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor) -> int:
+    if not (t.is_cuda and t.is_contiguous()):
+        raise ValueError("adatopk needs contiguous device tensors")
+    return t.data_ptr()
+
+
+def adatopk_workspace_bytes(n_total: int, num_segments: int, dtype: torch.dtype) -> int:
+    return int(load_library().adatopk_workspace_bytes(int(n_total), int(num_segments), _dtype_code(dtype)))
+
+
+def new_workspace(n_total: int, num_segments: int, dtype: torch.dtype, device="cuda") -> torch.Tensor:
+    nbytes = adatopk_workspace_bytes(n_total, num_segments, dtype)
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def adatopk_compress(dense: torch.Tensor, k: int, idx_out: torch.Tensor, val_out: torch.Tensor,
+                     err_norm_out: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+    """Enqueues compress of one tensor on the current stream; outputs are written in place."""
+    lib = load_library()
+    err_ptr = _dev(err_norm_out) if err_norm_out is not None else None
+    _check(lib.adatopk_compress(_dev(dense), dense.numel(), _dtype_code(dense.dtype), int(k), _dev(idx_out),
+                                _dev(val_out), err_ptr, _dev(workspace), workspace.numel(), _stream()),
+           "adatopk_compress")
+
+
+def adatopk_decompress(idx: torch.Tensor, val: torch.Tensor, k: int, dense_out: torch.Tensor) -> None:
+    lib = load_library()
+    _check(lib.adatopk_decompress(_dev(idx), _dev(val), int(k), _dtype_code(dense_out.dtype), _dev(dense_out),
+                                  dense_out.numel(), _stream()), "adatopk_decompress")
+
+
+def adatopk_compress_segmented(dense: Sequence[torch.Tensor], ks: Sequence[int], idx_out: torch.Tensor,
+                               val_out: torch.Tensor, out_offset: Sequence[int],
+                               err_norm_out: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+    lib = load_library()
+    S = len(dense)
+    dt = _dtype_code(dense[0].dtype) if S else F32
+    ptrs = (ctypes.c_void_p * max(S, 1))(*[_dev(t) for t in dense])
+    ns = (ctypes.c_int64 * max(S, 1))(*[t.numel() for t in dense])
+    kk = (ctypes.c_int64 * max(S, 1))(*[int(v) for v in ks])
+    off = (ctypes.c_int64 * (S + 1))(*[int(v) for v in out_offset])
+    err_ptr = _dev(err_norm_out) if err_norm_out is not None else None
+    _check(lib.adatopk_compress_segmented(ptrs, ns, kk, S, dt, _dev(idx_out), _dev(val_out), off, err_ptr,
+                                          _dev(workspace), workspace.numel(), _stream()),
+           "adatopk_compress_segmented")
+
+
+def adatopk_adaptive_ratios(R: Sequence[float], r_user: float, coeff: float = 3.0):
+    lib = load_library()
+    m = len(R)
+    arr = (ctypes.c_double * max(m, 1))(*[float(v) for v in R])
+    out = (ctypes.c_double * max(m, 1))()
+    _check(lib.adatopk_adaptive_ratios(arr, m, float(r_user), float(coeff), out), "adatopk_adaptive_ratios")
+    return [out[i] for i in range(m)]
+
+
+def adatopk_k_for_ratio(n: int, r_i: float) -> int:
+    return int(load_library().adatopk_k_for_ratio(int(n), float(r_i)))
+
+
+# ------------------------------------------------------------------ measurement hooks
+def measure_enable(on: bool) -> None:
+    _check(load_library().adatopk_measure_enable(1 if on else 0), "adatopk_measure_enable")
+
+
+def measure_stage_names():
+    lib = load_library()
+    return [lib.adatopk_measure_stage_name(i).decode() for i in range(lib.adatopk_measure_stage_count())]
+
+
+def measure_read():
+    lib = load_library()
+    n = lib.adatopk_measure_stage_count()
+    buf = (ctypes.c_float * n)()
+    _check(lib.adatopk_measure_read(buf), "adatopk_measure_read")
+    return [buf[i] for i in range(n)]
+
+
+def measure_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().adatopk_measure_copy(_dev(dst), _dev(src), nbytes, _stream()), "adatopk_measure_copy")
+
+
+def measure_read_only(src: torch.Tensor, sink: torch.Tensor) -> None:
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().adatopk_measure_read_only(_dev(src), nbytes, _dev(sink), _stream()),
+           "adatopk_measure_read_only")
+
+
+def measure_fill(dst: torch.Tensor) -> None:
+    nbytes = dst.numel() * dst.element_size()
+    _check(load_library().adatopk_measure_fill(_dev(dst), nbytes, _stream()), "adatopk_measure_fill")

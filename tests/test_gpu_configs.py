@@ -1,0 +1,71 @@
+"""The five benchmark configurations at full size: HIP path vs the CPU oracle, bit-exact."""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+
+from oracle import adatopk_oracle as orc
+from paper_2410_12707_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+ERR_RTOL = 1e-5
+
+
+def full_check(x, k):
+    import gpu_harness as H
+
+    ri, rv, re = orc.compress(x, k)
+    gi, gv, ge = H.gpu_compress(x, k)
+    assert np.array_equal(gi, ri) and np.array_equal(H.bits(gv), H.bits(rv))
+    assert H.same_err(ge, re, ERR_RTOL), (ge, re)
+    gy = H.gpu_decompress(gi, gv, x.size)
+    assert np.array_equal(H.bits(gy), H.bits(orc.decompress(ri, rv, x.size)))
+    return ri, rv
+
+
+def test_config1_gpt2_small_hidden():
+    w = wl.config1()
+    assert w.ks == [3932]
+    full_check(w.tensors[0], w.ks[0])
+
+
+@pytest.mark.parametrize("keep", [(1, 1000), (1, 100), (1, 10)])
+def test_config2_gpt2_small_gelu(keep):
+    w = wl.config2(keep)
+    assert w.tensors[0].size == 25_165_824 and w.ks[0] == {1000: 25_165, 100: 251_658, 10: 2_516_582}[keep[1]]
+    full_check(w.tensors[0], w.ks[0])
+
+
+def test_config3_resnet101_gradient():
+    w = wl.config3()
+    assert w.tensors[0].size == 25_690_112 and w.ks == [256_901]
+    full_check(w.tensors[0], w.ks[0])
+
+
+def test_config4_segmented_adaptive_ratios():
+    import gpu_harness as H
+
+    w = wl.config4()
+    assert len(w.tensors) == 24 and all(t.size == 8_388_608 for t in w.tensors)
+    gi, gv, off, ge = H.gpu_compress_segmented(w.tensors, w.ks)
+    with ThreadPoolExecutor(max_workers=8) as ex:  # the oracle, one tensor per thread
+        refs = list(ex.map(lambda a: orc.compress(a[0], a[1]), zip(w.tensors, w.ks)))
+    for s, (ri, rv, re) in enumerate(refs):
+        assert np.array_equal(gi[off[s]:off[s + 1]], ri), s
+        assert np.array_equal(H.bits(gv[off[s]:off[s + 1]]), H.bits(rv)), s
+        assert H.same_err(ge[s], re, ERR_RTOL), (s, ge[s], re)
+
+
+def test_config5_bf16_ties_at_threshold():
+    w = wl.config5()
+    x = w.tensors[0]
+    assert x.size == 26_214_400 and w.ks == [131_072]
+    ri, rv = full_check(x, w.ks[0])
+    # the case exists for its ties: count them, and check that the quota really cuts through them
+    key = x & np.uint16(0x7FFF)
+    kmin = (rv & np.uint16(0x7FFF)).min()
+    tied = int(np.count_nonzero(key == kmin))
+    taken = int(np.count_nonzero((rv & np.uint16(0x7FFF)) == kmin))
+    print("config5: %d elements tie at the threshold key 0x%04x, %d of them kept" % (tied, kmin, taken))
+    assert tied > 1000 and 0 < taken < tied

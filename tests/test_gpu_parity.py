@@ -1,0 +1,124 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the C ABI.
+
+Bar: indices, values and the reconstructed tensor bit-exact; the fp32 error norm within
+1e-5 relative (the kernels accumulate in fp64 like the oracle, in another order).
+"""
+import numpy as np
+import pytest
+
+from oracle import adatopk_oracle as orc
+from paper_2410_12707_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+ERR_RTOL = 1e-5
+
+
+def check_one(x, k, offset_elems=0, label=""):
+    import gpu_harness as H
+
+    n = x.size
+    ri, rv, re = orc.compress(x, k)
+    gi, gv, ge = H.gpu_compress(x, k, offset_elems)
+    assert gi.size == k and np.array_equal(gi, ri), "indices differ " + label
+    assert np.array_equal(H.bits(gv), H.bits(rv)), "values differ " + label
+    assert H.same_err(ge, re, ERR_RTOL), "err %r vs %r %s" % (ge, re, label)
+    ry = orc.decompress(ri, rv, n)
+    gy = H.gpu_decompress(gi, gv, n, offset_elems)
+    assert np.array_equal(H.bits(gy), H.bits(ry)), "reconstruction differs " + label
+
+
+def ks_for(n):
+    return sorted({0, 1, n // 100, n // 3, n - 1, n} & set(range(0, n + 1)))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("kind", ["normal", "few_levels", "all_equal", "all_zero", "signed_zero_mix", "sparse",
+                                  "nonfinite", "random_bits", "descending"])
+def test_small_and_ragged_sizes(kind, dtype):
+    # below one vector, one wavefront, one tile (8192 fp32 / 16384 bf16), a few tiles and a
+    # ragged tail, several chunks
+    for n in (1, 3, 64, 1000, 8192, 8193, 16385, 70001):
+        x = wl.small_case(kind, n, seed=1000 + n, dtype=dtype)
+        for k in ks_for(n):
+            check_one(x, k, label="%s %s n=%d k=%d" % (kind, dtype, n, k))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_many_chunks_and_tiles(dtype):
+    # 3.3M elements: hundreds of chunks, several tiles each, ragged last chunk
+    n = 3_300_017
+    for kind, k in (("normal", n // 100), ("few_levels", n // 7), ("sparse", n // 20), ("random_bits", n // 1000)):
+        check_one(wl.small_case(kind, n, seed=77, dtype=dtype), k, label="%s %s" % (kind, dtype))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_misaligned_base_pointer(dtype):
+    n = 40_003
+    x = wl.small_case("normal", n, seed=5, dtype=dtype)
+    for off in (1, 3):
+        check_one(x, n // 50, offset_elems=off, label="offset %d" % off)
+
+
+def test_ties_straddling_tiles_and_chunks():
+    # the tied value sits on both sides of every tile and chunk boundary; the quota ends mid-way
+    n = 300_000
+    x = np.full(n, 0.5, dtype=np.float32)
+    x[::3] = 2.0  # 100000 larger values
+    x[1::8192] = -2.0
+    for k in (1, 99_999, 100_000 + 37, 100_000 + 8192 * 5 + 1, n - 1):
+        check_one(x, k, label="ties k=%d" % k)
+
+
+def test_decompress_unsorted_and_out_of_range():
+    import gpu_harness as H
+
+    n = 100_000
+    rng = np.random.Generator(np.random.PCG64(9))
+    idx = rng.permutation(n)[:5000].astype(np.int32)
+    val = rng.standard_normal(5000, dtype=np.float32)
+    assert np.array_equal(H.bits(H.gpu_decompress(idx, val, n)), H.bits(orc.decompress(idx, val, n)))
+    bad = idx.copy()
+    bad[::10] = n + 5  # skipped by contract
+    bad[1::10] = -3
+    ok = (bad >= 0) & (bad < n)
+    assert np.array_equal(H.bits(H.gpu_decompress(bad, val, n)), H.bits(orc.decompress(bad[ok], val[ok], n)))
+    assert np.all(H.gpu_decompress(np.empty(0, np.int32), np.empty(0, np.float32), 1000) == 0)
+
+
+def test_runs_are_bit_identical():
+    import gpu_harness as H
+
+    x = wl.small_case("few_levels", 1_000_003, seed=3)
+    a = H.gpu_compress(x, 123_456)
+    for _ in range(3):
+        b = H.gpu_compress(x, 123_456)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(H.bits(a[1]), H.bits(b[1]))
+        assert np.float32(a[2]).view(np.uint32) == np.float32(b[2]).view(np.uint32)
+
+
+def test_segmented_mixed_lengths():
+    import gpu_harness as H
+
+    lens = [70_001, 0, 5, 8192, 1, 250_000, 16_384, 33]
+    kinds = ["normal", "normal", "few_levels", "sparse", "normal", "few_levels", "all_equal", "nonfinite"]
+    xs = [wl.small_case(kd, n, seed=40 + i) for i, (kd, n) in enumerate(zip(kinds, lens))]
+    ks = [700, 0, 5, 100, 0, 40_000, 16_384, 11]
+    gi, gv, off, ge = H.gpu_compress_segmented(xs, ks)
+    ri, rv, roff, re = orc.compress_segmented(xs, ks)
+    assert np.array_equal(off, roff) and np.array_equal(gi, ri) and np.array_equal(H.bits(gv), H.bits(rv))
+    for s in range(len(xs)):
+        assert H.same_err(ge[s], re[s], ERR_RTOL), (s, ge[s], re[s])
+
+
+def test_segmented_more_segments_than_one_launch_holds():
+    import gpu_harness as H
+
+    rng = np.random.Generator(np.random.PCG64(17))
+    lens = rng.integers(1, 30_000, size=70).tolist()
+    xs = [wl.small_case("normal", n, seed=500 + i, dtype="bf16") for i, n in enumerate(lens)]
+    ks = [max(1, n // 13) for n in lens]
+    gi, gv, off, ge = H.gpu_compress_segmented(xs, ks)
+    ri, rv, roff, re = orc.compress_segmented(xs, ks)
+    assert np.array_equal(gi, ri) and np.array_equal(H.bits(gv), H.bits(rv))
+    assert all(H.same_err(ge[s], re[s], ERR_RTOL) for s in range(len(xs)))
