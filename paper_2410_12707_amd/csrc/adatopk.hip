@@ -9,22 +9,27 @@
 // both types share one 31-bit key).  The exact k-th largest key T is found by a 3-level
 // MSD radix select with digits of 11 / 10 / 10 bits:
 //   k_init    zero the per-segment state and the three global histograms
-//   k_hist1   one read of the input: per-chunk LDS histogram of the top digit; every chunk
-//             stores the suffix sums of its histogram; the last block of a segment picks the
-//             digit bucket B1 that holds the k-th key and turns the stored suffix sums into
-//             the offset of every chunk in the candidate list
-//   k_gather  second read of the input: every element whose top digit is >= B1 goes, in
-//             index order, into the candidate list L (index, value); members of bucket B1 are
-//             histogrammed on the second digit; squares of the elements below the bucket are
-//             summed in fp64; the last block picks the second digit B2
-//   k_hist3   over L only (about k + the bucket population): histogram of the third digit of
-//             the elements that match (B1,B2); the last block fixes T, the tie quota q and
-//             the output offsets of every list block
-//   k_emit    over L: stable compaction into idx_out / val_out (key > T, plus the first q keys
-//             equal to T), squares of dropped list members, final fixed-order error reduction
-// All cross-block ordering comes from counts stored per chunk and scanned by the last block
-// that finishes (a ticket counter): no block ever waits for another block, so no launch can
-// hang, and every result (also the fp64 error sum) is the same from run to run.
+//   k_hist1   one read of the input: per-chunk LDS histogram of the top digit, added into the
+//             segment's global histogram G1; every chunk also stores the suffix sums of its
+//             own histogram (one row per chunk)
+//   k_gather  prologue (every block, redundantly): G1 -> digit bucket B1 holding the k-th key;
+//             the chunk's slot range in the candidate list L = sum over the earlier chunks of
+//             their stored count of digits >= B1.  Then the second read of the input: every
+//             element whose top digit is >= B1 goes, in index order, into L (index, value);
+//             members of bucket B1 are histogrammed on the second digit (G2); squares of the
+//             elements below the bucket are summed in fp64 per chunk
+//   k_hist3   over L only (about k + the bucket population).  Prologue: G2 -> second digit B2.
+//             Histogram of the third digit of the entries matching (B1,B2) into G3, one row of
+//             suffix sums per list block
+//   k_emit    over L.  Prologue: G3 -> threshold key T and tie quota q; output offsets of the
+//             list block from the rows of the earlier blocks.  Stable compaction into idx_out /
+//             val_out (key > T, plus the first q keys equal to T); squares of dropped entries;
+//             the block that finishes last adds all error partials in a fixed order
+// Cross-block order comes only from counts that an EARLIER kernel stored and that every block
+// of the next kernel scans for itself: no block waits for another block (no launch can hang),
+// no block needs a release fence (on this chip an agent-scope fence writes back the L2 of its
+// XCD, about 1.5 us per workgroup, serialised), and every result, the fp64 error sum included,
+// is the same from run to run.
 //
 // Decompress: k_fill (16-byte zero stores) then k_scatter.
 #include <hip/hip_runtime.h>
@@ -50,13 +55,14 @@ constexpr int LB_ELEMS = 16384;     // input elements per list block when sizing
 static_assert(U * NW <= 64 && LU * NW <= 64, "per-tile wave counts must fit one wavefront scan");
 static_assert(NB1 % BLOCK == 0 && NB2 % BLOCK == 0 && NB3 % BLOCK == 0, "bins split evenly over threads");
 static_assert(BITS1 + BITS2 + BITS3 == 31, "digits cover the 31-bit key");
+static_assert(BLOCK >= 256, "k_emit scans the list blocks of a segment with one thread each");
 
 struct SegState {  // one per segment, zeroed by k_init; 64 bytes
-    uint32_t ticket1, ticket2, ticket3, ticket4;
+    uint32_t ticket;        // list blocks that have published their error partial
     uint32_t B1, c_gt1, m;  // bucket of level 1, #keys above it, length of the candidate list
     uint32_t B2, c_gt2;     // bucket of level 2, #keys above (B1,B2)
     uint32_t T, q, c_gt;    // threshold key, tie quota, #keys above T
-    uint32_t pad[4];
+    uint32_t pad[7];
 };
 static_assert(sizeof(SegState) == 64, "state record size");
 
@@ -78,10 +84,9 @@ struct Launch {
     SegState *state;
     uint32_t *G1, *G2, *G3;                    // [MAXSEG][NBx] global histograms
     uint32_t *rows1;                           // [chunks][NB1] suffix sums of the chunk histograms
-    uint32_t *chunk_off, *chunk_cnt;           // [chunks] slot range of each chunk in L
     double *chunk_err;                         // [chunks] sum of squares below the bucket
     uint32_t *rows3;                           // [list blocks][NB3] suffix sums
-    uint32_t *ldef, *lgt_off, *leq_off;        // [list blocks]
+    uint32_t *ldef;                            // [list blocks] #keys above the 21-bit prefix
     double *lerr;                              // [list blocks]
     int32_t *L_idx;
     void *L_val;
@@ -225,28 +230,28 @@ template <int NB> __device__ __forceinline__ void flush_bins(const uint32_t *h, 
         if (c) __hip_atomic_fetch_add(&G[b], c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
-template <int NB> __device__ __forceinline__ void load_bins(uint32_t *h, const uint32_t *G) {
-    for (int b = threadIdx.x; b < NB; b += BLOCK)
-        h[b] = __hip_atomic_load(&G[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
+// Error-norm hand-off without cache maintenance: thread 0 of every list block publishes its
+// partial with a device-coherent store, waits until the store is acknowledged, and takes a
+// ticket; the block that draws the last ticket reads all partials with device-coherent loads.
+// (A release fence here would write back the whole L2 once per block.)  No block waits.
+__device__ __forceinline__ void coherent_store_f64(double *p, double v) {
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), static_cast<unsigned long long>(__double_as_longlong(v)),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ uint32_t coherent_load(const uint32_t *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ double coherent_load_f64(const double *p) {
+    return __longlong_as_double(static_cast<long long>(__hip_atomic_load(
+        reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
 }
-
-// True in exactly one block per ticket: the one that arrives last.  Every block's global
-// writes made before the call are visible to that block after it.
-__device__ __forceinline__ bool last_block_done(uint32_t *ticket, uint32_t nblocks, uint32_t *s_flag) {
-    __threadfence();
-    __syncthreads();
+__device__ __forceinline__ bool publish_and_take_ticket(double *slot, double v, uint32_t *ticket, uint32_t nblocks,
+                                                        uint32_t *s_flag) {
     if (threadIdx.x == 0) {
-        const uint32_t t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        coherent_store_f64(slot, v);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const uint32_t t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         *s_flag = (t == nblocks - 1u) ? 1u : 0u;
     }
     __syncthreads();
-    const bool last = *s_flag != 0u;
-    if (last) __threadfence();
-    return last;
+    return *s_flag != 0u;
 }
 
 __device__ __forceinline__ int find_segment_by(const Launch &a, int g, bool by_chunk) {
@@ -256,6 +261,21 @@ __device__ __forceinline__ int find_segment_by(const Launch &a, int g, bool by_c
         if (g >= begin) s = i;
     }
     return s;
+}
+
+// Global histogram G[NB] (complete: written by an earlier kernel) -> bucket B holding the
+// krem-th largest digit and the count `above` it.  h[NB], sm[NW], s_pick[2] are LDS scratch.
+template <int NB>
+__device__ __forceinline__ void pick_from_global(const uint32_t *G, uint32_t krem, uint32_t *h, uint32_t *sm,
+                                                 uint32_t *s_pick, uint32_t &B, uint32_t &above) {
+    for (int b = threadIdx.x; b < NB; b += BLOCK) h[b] = G[b];
+    __syncthreads();
+    block_suffix_inplace<NB>(h, sm);
+    block_pick_bucket<NB>(h, krem, s_pick);
+    __syncthreads();
+    B = s_pick[0];
+    above = s_pick[1];
+    __syncthreads();
 }
 
 // ------------------------------------------------------------------ k_init
@@ -293,8 +313,6 @@ __device__ __forceinline__ void hist1_tile(const void *x, int64_t t0, int64_t en
 template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist1(Launch a) {
     __shared__ uint32_t h[NB1];
     __shared__ uint32_t sm[NW];
-    __shared__ uint32_t s_flag;
-    __shared__ uint32_t s_pick[2];
     constexpr int TILE = BLOCK * U * VEC;
 
     const int g = blockIdx.x;
@@ -318,34 +336,6 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist1(Launch a) {
     block_suffix_inplace<NB1>(h, sm);
     uint32_t *row = a.rows1 + static_cast<size_t>(g) * NB1;
     for (int b = threadIdx.x; b < NB1; b += BLOCK) row[b] = h[b];
-
-    if (!last_block_done(&a.state[s].ticket1, sg.nchunks, &s_flag)) return;
-
-    // Last block of the segment: pick the bucket, then lay the chunks out in the list.
-    load_bins<NB1>(h, a.G1 + s * NB1);
-    block_suffix_inplace<NB1>(h, sm);
-    block_pick_bucket<NB1>(h, static_cast<uint32_t>(sg.k), s_pick);
-    __syncthreads();
-    const uint32_t B1 = s_pick[0];
-    uint32_t carry = 0;
-    for (int c0 = 0; c0 < sg.nchunks; c0 += BLOCK) {
-        const int cc = c0 + threadIdx.x;
-        uint32_t cnt = 0;
-        if (cc < sg.nchunks && B1 < NB1)
-            cnt = coherent_load(a.rows1 + static_cast<size_t>(sg.chunk_begin + cc) * NB1 + B1);
-        uint32_t total;
-        const uint32_t inc = block_incl_scan(cnt, sm, &total);
-        if (cc < sg.nchunks) {
-            a.chunk_off[sg.chunk_begin + cc] = carry + inc - cnt;
-            a.chunk_cnt[sg.chunk_begin + cc] = cnt;
-        }
-        carry += total;
-    }
-    if (threadIdx.x == 0) {
-        a.state[s].B1 = B1;
-        a.state[s].c_gt1 = s_pick[1];
-        a.state[s].m = carry;
-    }
 }
 
 // ------------------------------------------------------------------ k_gather
@@ -413,11 +403,10 @@ __device__ __forceinline__ void gather_tile(const void *x, int64_t t0, int64_t e
 
 template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     using R = typename Raw<VEC>::type;
-    __shared__ uint32_t h2[NB2];
+    __shared__ uint32_t h[NB1];  // top-digit histogram during the prologue, then the second-digit one
     __shared__ uint32_t wcnt[2][U * NW];
     __shared__ uint32_t sm[NW];
     __shared__ double smd[NW];
-    __shared__ uint32_t s_flag;
     __shared__ uint32_t s_pick[2];
     constexpr int TILE = BLOCK * U * VEC;
 
@@ -427,12 +416,29 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     const int c = g - sg.chunk_begin;
     const int64_t beg = static_cast<int64_t>(c) * a.E;
     const int64_t end = (beg + a.E < sg.n) ? beg + a.E : sg.n;
-    const uint32_t B1 = a.state[s].B1;
-    const uint32_t cnt = a.chunk_cnt[g];
-    const int64_t lo = sg.l_base + a.chunk_off[g];
+
+    // Prologue, the same in every block of the segment: bucket of the top digit, then this
+    // chunk's slot range in the list = scan of the earlier chunks' counts of digits >= B1.
+    uint32_t B1, c_gt1;
+    pick_from_global<NB1>(a.G1 + s * NB1, static_cast<uint32_t>(sg.k), h, sm, s_pick, B1, c_gt1);
+    uint32_t part = 0, cnt = 0;
+    if (B1 < NB1) {
+        const uint32_t *col = a.rows1 + static_cast<size_t>(sg.chunk_begin) * NB1 + B1;
+        for (int cc = threadIdx.x; cc < c; cc += BLOCK) part += col[static_cast<size_t>(cc) * NB1];
+        cnt = col[static_cast<size_t>(c) * NB1];
+    }
+    uint32_t off;
+    block_incl_scan(part, sm, &off);
+    if (c == sg.nchunks - 1 && threadIdx.x == 0) {
+        a.state[s].B1 = B1;
+        a.state[s].c_gt1 = c_gt1;
+        a.state[s].m = off + cnt;
+    }
+    const int64_t lo = sg.l_base + off;
     int32_t *Li = a.L_idx + lo;
     R *Lv = static_cast<R *>(a.L_val) + lo;
 
+    uint32_t *h2 = h;
     for (int b = threadIdx.x; b < NB2; b += BLOCK) h2[b] = 0;
     __syncthreads();
 
@@ -450,18 +456,6 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     if (threadIdx.x == 0) a.chunk_err[g] = bsum;
     __syncthreads();
     flush_bins<NB2>(h2, a.G2 + s * NB2);
-
-    if (!last_block_done(&a.state[s].ticket2, sg.nchunks, &s_flag)) return;
-
-    load_bins<NB2>(h2, a.G2 + s * NB2);
-    block_suffix_inplace<NB2>(h2, sm);
-    const uint32_t c_gt1 = a.state[s].c_gt1;
-    block_pick_bucket<NB2>(h2, static_cast<uint32_t>(sg.k) - c_gt1, s_pick);
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        a.state[s].B2 = s_pick[0];
-        a.state[s].c_gt2 = c_gt1 + s_pick[1];
-    }
 }
 
 // ------------------------------------------------------------------ list kernels
@@ -476,9 +470,8 @@ __device__ __forceinline__ void list_range(uint32_t m, int lb, int lb_count, uin
 
 template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
     using R = typename Raw<VEC>::type;
-    __shared__ uint32_t h3[NB3];
+    __shared__ uint32_t h[NB2 > NB3 ? NB2 : NB3];
     __shared__ uint32_t sm[NW];
-    __shared__ uint32_t s_flag;
     __shared__ uint32_t s_pick[2];
 
     const int g = blockIdx.x;
@@ -486,11 +479,21 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
     const SegDesc &sg = a.seg[s];
     const int lb = g - sg.lb_begin;
     const uint32_t m = a.state[s].m;
-    const uint32_t P = (a.state[s].B1 << BITS2) | a.state[s].B2;  // 21-bit prefix of the threshold
+    const uint32_t B1 = a.state[s].B1, c_gt1 = a.state[s].c_gt1;
+
+    // Prologue: bucket of the second digit among the members of bucket B1.
+    uint32_t B2, above2;
+    pick_from_global<NB2>(a.G2 + s * NB2, static_cast<uint32_t>(sg.k) - c_gt1, h, sm, s_pick, B2, above2);
+    if (lb == 0 && threadIdx.x == 0) {
+        a.state[s].B2 = B2;
+        a.state[s].c_gt2 = c_gt1 + above2;
+    }
+    const uint32_t P = (B1 << BITS2) | B2;  // 21-bit prefix of the threshold
     const R *Lv = static_cast<const R *>(a.L_val) + sg.l_base;
     uint32_t beg, end;
     list_range(m, lb, sg.lb_count, beg, end);
 
+    uint32_t *h3 = h;
     for (int b = threadIdx.x; b < NB3; b += BLOCK) h3[b] = 0;
     __syncthreads();
     uint32_t def = 0;  // keys above the prefix: kept whatever the last digit is
@@ -509,48 +512,16 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
     uint32_t deftot;
     block_incl_scan(def, sm, &deftot);
     if (threadIdx.x == 0) a.ldef[g] = deftot;
-
-    if (!last_block_done(&a.state[s].ticket3, sg.lb_count, &s_flag)) return;
-
-    load_bins<NB3>(h3, a.G3 + s * NB3);
-    block_suffix_inplace<NB3>(h3, sm);
-    const uint32_t c_gt2 = a.state[s].c_gt2;
-    block_pick_bucket<NB3>(h3, static_cast<uint32_t>(sg.k) - c_gt2, s_pick);
-    __syncthreads();
-    const uint32_t B3 = s_pick[0];
-    uint32_t carry_gt = 0, carry_eq = 0;
-    for (int b0 = 0; b0 < sg.lb_count; b0 += BLOCK) {
-        const int bb = b0 + threadIdx.x;
-        uint32_t gt = 0, eq = 0;
-        if (bb < sg.lb_count && B3 < NB3) {
-            const uint32_t *r = a.rows3 + static_cast<size_t>(sg.lb_begin + bb) * NB3;
-            const uint32_t ge = coherent_load(r + B3);
-            const uint32_t above = (B3 + 1 < NB3) ? coherent_load(r + B3 + 1) : 0u;
-            gt = coherent_load(a.ldef + sg.lb_begin + bb) + above;
-            eq = ge - above;
-        }
-        uint32_t tot_gt, tot_eq;
-        const uint32_t inc_gt = block_incl_scan(gt, sm, &tot_gt);
-        const uint32_t inc_eq = block_incl_scan(eq, sm, &tot_eq);
-        if (bb < sg.lb_count) {
-            a.lgt_off[sg.lb_begin + bb] = carry_gt + inc_gt - gt;
-            a.leq_off[sg.lb_begin + bb] = carry_eq + inc_eq - eq;
-        }
-        carry_gt += tot_gt;
-        carry_eq += tot_eq;
-    }
-    if (threadIdx.x == 0) {
-        const uint32_t c_gt = c_gt2 + s_pick[1];
-        a.state[s].T = (B3 < NB3) ? ((P << BITS3) | B3) : 0xFFFFFFFFu;
-        a.state[s].c_gt = c_gt;
-        a.state[s].q = static_cast<uint32_t>(sg.k) - c_gt;
-    }
 }
 
 template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     using R = typename Raw<VEC>::type;
+    __shared__ uint32_t h[NB3];
     __shared__ uint32_t wcnt[2][2][LU * NW];
+    __shared__ uint32_t sm[NW];
     __shared__ double smd[NW];
+    __shared__ uint32_t s_pick[2];
+    __shared__ uint32_t s_off[2];
     __shared__ uint32_t s_flag;
 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -559,8 +530,35 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     const SegDesc &sg = a.seg[s];
     const int lb = g - sg.lb_begin;
     const uint32_t m = a.state[s].m;
-    const uint32_t T = a.state[s].T, q = a.state[s].q;
+    const uint32_t P = (a.state[s].B1 << BITS2) | a.state[s].B2;
+    const uint32_t c_gt2 = a.state[s].c_gt2;
     const uint32_t kout = static_cast<uint32_t>(sg.k);
+
+    // Prologue: last digit -> threshold key T and tie quota q; then this block's output
+    // offsets = scan over the earlier list blocks of (#keys above T, #keys equal to T).
+    uint32_t B3, above3;
+    pick_from_global<NB3>(a.G3 + s * NB3, kout - c_gt2, h, sm, s_pick, B3, above3);
+    const uint32_t T = (B3 < NB3) ? ((P << BITS3) | B3) : 0xFFFFFFFFu;
+    const uint32_t q = kout - (c_gt2 + above3);
+    {
+        uint32_t gt = 0, eq = 0;
+        if (static_cast<int>(threadIdx.x) < sg.lb_count && B3 < NB3) {
+            const uint32_t *r = a.rows3 + static_cast<size_t>(sg.lb_begin + threadIdx.x) * NB3;
+            const uint32_t above = (B3 + 1 < NB3) ? r[B3 + 1] : 0u;
+            gt = a.ldef[sg.lb_begin + threadIdx.x] + above;
+            eq = r[B3] - above;
+        }
+        uint32_t tot;
+        const uint32_t inc_gt = block_incl_scan(gt, sm, &tot);
+        const uint32_t inc_eq = block_incl_scan(eq, sm, &tot);
+        if (static_cast<int>(threadIdx.x) == lb) {
+            s_off[0] = inc_gt - gt;
+            s_off[1] = inc_eq - eq;
+        }
+        __syncthreads();
+    }
+    uint32_t run_gt = s_off[0], run_eq = s_off[1];
+
     const int32_t *Li = a.L_idx + sg.l_base;
     const R *Lv = static_cast<const R *>(a.L_val) + sg.l_base;
     int32_t *oi = a.idx_out + sg.out_off;
@@ -568,13 +566,12 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     uint32_t beg, end;
     list_range(m, lb, sg.lb_count, beg, end);
 
-    uint32_t run_gt = a.lgt_off[g], run_eq = a.leq_off[g];
     double acc = 0.0;
     int buf = 0;
     for (uint32_t t0 = beg; t0 < end; t0 += BLOCK * LU, buf ^= 1) {
         uint32_t raw[LU];
         int32_t id[LU];
-        uint32_t pre_gt[LU], pre_eq[LU], cls[LU];  // cls: 0 below T, 1 equal, 2 above
+        uint32_t pre_gt[LU], pre_eq[LU], cls[LU];  // cls: 0 below T, 1 equal, 2 above, 3 no element
 #pragma unroll
         for (int j = 0; j < LU; ++j) {
             const uint32_t i = t0 + j * BLOCK + threadIdx.x;
@@ -616,18 +613,15 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
         run_gt += tg;
         run_eq += te;
     }
-    const double bsum = block_sum_f64(acc, smd);
-    if (threadIdx.x == 0) a.lerr[g] = bsum;
-
-    if (!last_block_done(&a.state[s].ticket4, sg.lb_count, &s_flag)) return;
     if (a.err_out == nullptr) return;
 
-    // Error norm of the segment: chunk partials, then list-block partials, in a fixed order.
+    // Error norm of the segment: the block that draws the last ticket adds the chunk partials,
+    // then the list-block partials, in a fixed order.
+    const double bsum = block_sum_f64(acc, smd);
+    if (!publish_and_take_ticket(a.lerr + g, bsum, &a.state[s].ticket, sg.lb_count, &s_flag)) return;
     double part = 0.0;
-    for (int cc = threadIdx.x; cc < sg.nchunks; cc += BLOCK)
-        part += __hip_atomic_load(a.chunk_err + sg.chunk_begin + cc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    for (int bb = threadIdx.x; bb < sg.lb_count; bb += BLOCK)
-        part += __hip_atomic_load(a.lerr + sg.lb_begin + bb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int cc = threadIdx.x; cc < sg.nchunks; cc += BLOCK) part += a.chunk_err[sg.chunk_begin + cc];
+    for (int bb = threadIdx.x; bb < sg.lb_count; bb += BLOCK) part += coherent_load_f64(a.lerr + sg.lb_begin + bb);
     const double tot = block_sum_f64(part, smd);
     if (threadIdx.x == 0) a.err_out[s] = static_cast<float>(sqrt(tot));
 }
@@ -699,8 +693,7 @@ int32_t list_blocks(int64_t n, int32_t S) {
 }
 
 struct Carve {
-    size_t state, G1, G2, G3, rows1, chunk_off, chunk_cnt, chunk_err, rows3, ldef, lgt_off, leq_off, lerr, L_idx,
-        L_val, total;
+    size_t state, G1, G2, G3, rows1, chunk_err, rows3, ldef, lerr, L_idx, L_val, total;
 };
 
 // Workspace layout for up to max_chunks chunks, max_lb list blocks and n_total list slots.
@@ -717,13 +710,9 @@ Carve carve(int64_t max_chunks, int64_t max_lb, int64_t n_total, adatopk_dtype d
     c.G2 = take(sizeof(uint32_t) * NB2 * MAXSEG);
     c.G3 = take(sizeof(uint32_t) * NB3 * MAXSEG);
     c.rows1 = take(sizeof(uint32_t) * NB1 * max_chunks);
-    c.chunk_off = take(sizeof(uint32_t) * max_chunks);
-    c.chunk_cnt = take(sizeof(uint32_t) * max_chunks);
     c.chunk_err = take(sizeof(double) * max_chunks);
     c.rows3 = take(sizeof(uint32_t) * NB3 * max_lb);
     c.ldef = take(sizeof(uint32_t) * max_lb);
-    c.lgt_off = take(sizeof(uint32_t) * max_lb);
-    c.leq_off = take(sizeof(uint32_t) * max_lb);
     c.lerr = take(sizeof(double) * max_lb);
     c.L_idx = take(sizeof(int32_t) * static_cast<size_t>(n_total));
     c.L_val = take(static_cast<size_t>(elem_size(dt)) * static_cast<size_t>(n_total));
@@ -807,13 +796,9 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
         a.G2 = reinterpret_cast<uint32_t *>(ws + cv.G2);
         a.G3 = reinterpret_cast<uint32_t *>(ws + cv.G3);
         a.rows1 = reinterpret_cast<uint32_t *>(ws + cv.rows1);
-        a.chunk_off = reinterpret_cast<uint32_t *>(ws + cv.chunk_off);
-        a.chunk_cnt = reinterpret_cast<uint32_t *>(ws + cv.chunk_cnt);
         a.chunk_err = reinterpret_cast<double *>(ws + cv.chunk_err);
         a.rows3 = reinterpret_cast<uint32_t *>(ws + cv.rows3);
         a.ldef = reinterpret_cast<uint32_t *>(ws + cv.ldef);
-        a.lgt_off = reinterpret_cast<uint32_t *>(ws + cv.lgt_off);
-        a.leq_off = reinterpret_cast<uint32_t *>(ws + cv.leq_off);
         a.lerr = reinterpret_cast<double *>(ws + cv.lerr);
         a.L_idx = reinterpret_cast<int32_t *>(ws + cv.L_idx);
         a.L_val = ws + cv.L_val;
