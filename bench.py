@@ -2,7 +2,8 @@
 """Benchmark of the AdaTopK hot path on one MI355X.
 
 A step is one pass of the whole path over one tensor: adatopk_compress (threshold select,
-stable compaction, error norm) followed by adatopk_decompress (zero fill + scatter), through
+stable compaction, error norm) followed by adatopk_decompress_sorted (zero fill + scatter of the
+ascending pairs that compress wrote, one kernel), through
 the C ABI, on the GPT-2-small post-GELU activation fp32 [32,1024,768] at k = 1 %.  Inputs are
 resident in HBM before the timed region; the timed steps rotate over four distinct copies of
 the input (403 MB, more than the 256 MB last-level cache) so that no step finds its input
@@ -65,7 +66,7 @@ def main() -> int:
 
     def step(i: int) -> None:
         B.adatopk_compress(xs[i % NBUF], k, idx, val, err, ws)
-        B.adatopk_decompress(idx, val, k, y)
+        B.adatopk_decompress_sorted(idx, val, k, y)
 
     for i in range(args.warmup):
         step(i)
@@ -82,12 +83,12 @@ def main() -> int:
     # same loop on one buffer only (input may be served by the last-level cache): reported aside
     for i in range(args.warmup):
         B.adatopk_compress(xs[0], k, idx, val, err, ws)
-        B.adatopk_decompress(idx, val, k, y)
+        B.adatopk_decompress_sorted(idx, val, k, y)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         B.adatopk_compress(xs[0], k, idx, val, err, ws)
-        B.adatopk_decompress(idx, val, k, y)
+        B.adatopk_decompress_sorted(idx, val, k, y)
     torch.cuda.synchronize()
     warm_sec = (time.perf_counter() - t0) / args.steps
 
@@ -109,7 +110,7 @@ def main() -> int:
     algo = {
         "k_hist1": 4 * n,                # one read of the input
         "k_gather": 4 * n + 8 * k,       # second read of the input + the (index, value) pairs
-        "k_fill": 4 * n,                 # one write of the dense output
+        "k_merge": 4 * n + 8 * k,        # one write of the dense output + the pairs read
     }
     dom = max(algo, key=lambda nm: stage_us[nm] or 0.0)
     dom_s = stage_us[dom] * 1e-6

@@ -77,6 +77,13 @@ adatopk_status adatopk_compress(const void *dense, int64_t n, adatopk_dtype dt, 
 adatopk_status adatopk_decompress(const int32_t *idx, const void *val, int64_t k, adatopk_dtype dt,
                                   void *dense_out, int64_t n, void *hip_stream);
 
+/* Decompression when idx is strictly ascending, which is how adatopk_compress writes it: the
+ * same result as adatopk_decompress from one kernel that writes every output line once.  The
+ * order is the caller's promise and is not checked: with idx not ascending every store still
+ * stays inside dense_out, but entries may be dropped.  Arguments and errors as above. */
+adatopk_status adatopk_decompress_sorted(const int32_t *idx, const void *val, int64_t k, adatopk_dtype dt,
+                                         void *dense_out, int64_t n, void *hip_stream);
+
 /* Segmented compress: S independent tensors, tensor s with its own k[s] (the per-link
  * ratios of Sec. 5.2), every pass launched once for all of them.
  *   dense       host array of S device pointers

@@ -26,7 +26,7 @@ extern "C" {
 adatopk_status adatopk_measure_enable(int32_t on);
 
 /* Number of kernel stages a timed call can report, and their names (static strings):
- * the kernels of compress in launch order, then those of decompress. */
+ * the kernels of compress in launch order, then those of the two decompress calls. */
 int32_t adatopk_measure_stage_count(void);
 const char *adatopk_measure_stage_name(int32_t stage);
 

@@ -13,7 +13,9 @@ from typing import Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libadatopk.so")
+# ADATOPK_LIBRARY selects another build of the same C ABI (for instance one compiled with
+# different launch-shape constants); the default is the in-tree library.
+LIB_PATH = os.environ.get("ADATOPK_LIBRARY") or os.path.join(_HERE, "libadatopk.so")
 
 F32, BF16 = 0, 1
 OK, EINVAL, EWORKSPACE, ERUNTIME, ENOTIMPL = 0, 1, 2, 3, 4
@@ -44,6 +46,8 @@ def load_library() -> ctypes.CDLL:
     lib.adatopk_compress.restype = i32
     lib.adatopk_decompress.argtypes = [p, p, i64, i32, p, i64, p]
     lib.adatopk_decompress.restype = i32
+    lib.adatopk_decompress_sorted.argtypes = [p, p, i64, i32, p, i64, p]
+    lib.adatopk_decompress_sorted.restype = i32
     lib.adatopk_compress_segmented.argtypes = [p, p, p, i32, i32, p, p, p, p, p, sz, p]
     lib.adatopk_compress_segmented.restype = i32
     lib.adatopk_adaptive_ratios.argtypes = [p, i32, ctypes.c_double, ctypes.c_double, p]
@@ -113,6 +117,13 @@ def adatopk_decompress(idx: torch.Tensor, val: torch.Tensor, k: int, dense_out: 
     lib = load_library()
     _check(lib.adatopk_decompress(_dev(idx), _dev(val), int(k), _dtype_code(dense_out.dtype), _dev(dense_out),
                                   dense_out.numel(), _stream()), "adatopk_decompress")
+
+
+def adatopk_decompress_sorted(idx: torch.Tensor, val: torch.Tensor, k: int, dense_out: torch.Tensor) -> None:
+    """Decompress for strictly ascending idx (what adatopk_compress produces)."""
+    lib = load_library()
+    _check(lib.adatopk_decompress_sorted(_dev(idx), _dev(val), int(k), _dtype_code(dense_out.dtype),
+                                         _dev(dense_out), dense_out.numel(), _stream()), "adatopk_decompress_sorted")
 
 
 def adatopk_compress_segmented(dense: Sequence[torch.Tensor], ks: Sequence[int], idx_out: torch.Tensor,

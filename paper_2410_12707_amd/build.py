@@ -18,13 +18,14 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False) -> str:
+def build_library(verbose: bool = False, out: str = LIB, defines=()) -> str:
+    """Compiles the library to `out`; `defines` are extra -D macros (launch-shape overrides)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB] + SOURCES
+    cmd = [hipcc] + HIPCC_FLAGS + ["-D" + d for d in defines] + ["-o", out] + SOURCES
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
+    return out
 
 
 def library_is_stale() -> bool:

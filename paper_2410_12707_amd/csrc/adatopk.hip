@@ -41,24 +41,39 @@
 
 namespace {
 
-constexpr int BLOCK = 512;          // threads per workgroup (8 wavefronts)
-constexpr int NW = BLOCK / 64;      // wavefronts per workgroup
-constexpr int U = 4;                // 16-byte groups per thread per tile
+// Launch-shape constants; the -D overrides exist for tuning sweeps only.
+#ifndef ADATOPK_BLOCK
+#define ADATOPK_BLOCK 512
+#endif
+#ifndef ADATOPK_HREP
+#define ADATOPK_HREP 2
+#endif
+#ifndef ADATOPK_CTARGET
+#define ADATOPK_CTARGET 512
+#endif
+constexpr int BLOCK = ADATOPK_BLOCK;  // threads per workgroup
+constexpr int NW = BLOCK / 64;        // wavefronts per workgroup
+constexpr int EPT = 16;               // input elements per thread per tile
+constexpr int TILE = BLOCK * EPT;     // input elements per workgroup per tile, both dtypes
+constexpr int HREP = ADATOPK_HREP;    // copies of the top-digit LDS histogram (spreads same-bin lanes over banks)
 constexpr int LU = 4;               // list elements per thread per tile in the list kernels
 constexpr int BITS1 = 11, BITS2 = 10, BITS3 = 10;
 constexpr int NB1 = 1 << BITS1, NB2 = 1 << BITS2, NB3 = 1 << BITS3;
 constexpr int SH1 = BITS2 + BITS3;  // key >> SH1 = first digit
 constexpr int SH2 = BITS3;
 constexpr int MAXSEG = 32;          // segments per launch (the table travels as kernel arguments)
-constexpr int CTARGET = 512;        // chunks aimed at per launch (2 workgroups per CU)
+constexpr int CTARGET = ADATOPK_CTARGET;  // chunks aimed at per launch
 constexpr int LB_ELEMS = 16384;     // input elements per list block when sizing the list grid
-static_assert(U * NW <= 64 && LU * NW <= 64, "per-tile wave counts must fit one wavefront scan");
+constexpr size_t MERGE_SPANS = 2048;      // output spans aimed at by the one-kernel decompress
+constexpr size_t MERGE_MIN_SPAN = 16384;  // bytes; smaller outputs use fewer workgroups
+static_assert(LU * NW <= 64, "per-tile wave counts must fit one wavefront scan");
+static_assert(HREP == 1 || HREP == 2 || HREP == 4, "histogram copies");
 static_assert(NB1 % BLOCK == 0 && NB2 % BLOCK == 0 && NB3 % BLOCK == 0, "bins split evenly over threads");
 static_assert(BITS1 + BITS2 + BITS3 == 31, "digits cover the 31-bit key");
 static_assert(BLOCK >= 256, "k_emit scans the list blocks of a segment with one thread each");
 
 struct SegState {  // one per segment, zeroed by k_init; 64 bytes
-    uint32_t ticket;        // list blocks that have published their error partial
+    uint32_t unused0;
     uint32_t B1, c_gt1, m;  // bucket of level 1, #keys above it, length of the candidate list
     uint32_t B2, c_gt2;     // bucket of level 2, #keys above (B1,B2)
     uint32_t T, q, c_gt;    // threshold key, tie quota, #keys above T
@@ -73,7 +88,7 @@ struct SegDesc {
     int32_t n, k;
     int32_t chunk_begin, nchunks;
     int32_t lb_begin, lb_count;
-    uint32_t aligned16;  // tensor base is 16-byte aligned
+    uint32_t aligned4;   // tensor base is 4-byte aligned (always for fp32): dword loads allowed
     uint32_t pad;
 };
 
@@ -87,7 +102,7 @@ struct Launch {
     double *chunk_err;                         // [chunks] sum of squares below the bucket
     uint32_t *rows3;                           // [list blocks][NB3] suffix sums
     uint32_t *ldef;                            // [list blocks] #keys above the 21-bit prefix
-    double *lerr;                              // [list blocks]
+    double *lerr;                              // [list blocks] squares of list entries below the 21-bit prefix
     int32_t *L_idx;
     void *L_val;
     int32_t *idx_out;
@@ -96,9 +111,10 @@ struct Launch {
 };
 
 // ------------------------------------------------------------------ element access
+// VEC tags the dtype: 4 = fp32 (one element per dword), 8 = bf16 (two per dword, low half first).
 template <int VEC> struct Raw;
-template <> struct Raw<4> { using type = uint32_t; };  // fp32
-template <> struct Raw<8> { using type = uint16_t; };  // bf16
+template <> struct Raw<4> { using type = uint32_t; };
+template <> struct Raw<8> { using type = uint16_t; };
 
 template <int VEC> __device__ __forceinline__ uint32_t key_of(uint32_t raw) {
     return VEC == 4 ? (raw & 0x7FFFFFFFu) : ((raw & 0x7FFFu) << 16);
@@ -106,34 +122,51 @@ template <int VEC> __device__ __forceinline__ uint32_t key_of(uint32_t raw) {
 template <int VEC> __device__ __forceinline__ float value_of(uint32_t raw) {
     return __uint_as_float(VEC == 4 ? raw : (raw << 16));
 }
-
-// One 16-byte group (VEC consecutive elements starting at element i0) -> raw[].
-template <int VEC> __device__ __forceinline__ void load_vec(const void *x, int64_t i0, uint32_t (&raw)[VEC]) {
-    const uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const char *>(x) + i0 * (16 / VEC));
-    if (VEC == 4) {
-        raw[0] = v.x; raw[1] = v.y; raw[2] = v.z; raw[3] = v.w;
-    } else {
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) raw[e] = (w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-    }
+// Element h of a loaded dword, as the raw pattern of one element.
+template <int VEC> __device__ __forceinline__ uint32_t elem_of(uint32_t dword, int h) {
+    return VEC == 4 ? dword : ((dword >> (16 * h)) & 0xFFFFu);
 }
-// Guarded element-wise variant; returns the mask of elements below `end`.
-template <int VEC> __device__ __forceinline__ uint32_t load_guarded(const void *x, int64_t i0, int64_t end,
-                                                                      uint32_t (&raw)[VEC]) {
-    using R = typename Raw<VEC>::type;
-    const R *p = static_cast<const R *>(x);
-    uint32_t m = 0;
+
+// Streaming layout of the two full-input kernels.  A tile is TILE consecutive elements; wave w
+// of the workgroup owns the w-th contiguous 1/NW of it and reads it as SLOTS dword loads of
+// 64 consecutive dwords each (256 contiguous bytes per wave-level load).  Index order inside
+// a wave is therefore: slot, then lane, then half-word - which makes the lane mask of a
+// per-slot compare a bitmap in index order.
+template <int VEC> struct Stream {
+    static constexpr int EPD = VEC / 4;        // elements per dword
+    static constexpr int SLOTS = EPT / EPD;    // dword loads per thread per tile
+    // first element of (wave, slot, lane) in the tile that starts at element t0
+    static __device__ __forceinline__ int64_t first_elem(int64_t t0, int slot) {
+        const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+        return t0 + (static_cast<int64_t>(w * SLOTS + slot) * 64 + lane) * EPD;
+    }
+    // whole tile in range, base 4-byte aligned: plain dword loads
+    static __device__ __forceinline__ void load_fast(const void *x, int64_t t0, uint32_t (&dw)[SLOTS]) {
+        const uint32_t *p = static_cast<const uint32_t *>(x) + first_elem(t0, 0) / EPD;
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-        raw[e] = 0;
-        if (i0 + e < end) {
-            raw[e] = p[i0 + e];
-            m |= 1u << e;
+        for (int e = 0; e < SLOTS; ++e) dw[e] = p[e * 64];
+    }
+    // ragged tile or misaligned bf16 base: element-wise, guarded; valid[e] has bit h set when
+    // element h of slot e is below `end`
+    static __device__ __forceinline__ void load_slow(const void *x, int64_t t0, int64_t end, uint32_t (&dw)[SLOTS],
+                                                     uint32_t (&valid)[SLOTS]) {
+        using R = typename Raw<VEC>::type;
+        const R *p = static_cast<const R *>(x);
+#pragma unroll
+        for (int e = 0; e < SLOTS; ++e) {
+            const int64_t i0 = first_elem(t0, e);
+            uint32_t d = 0, v = 0;
+#pragma unroll
+            for (int h = 0; h < EPD; ++h)
+                if (i0 + h < end) {
+                    d |= static_cast<uint32_t>(p[i0 + h]) << (16 * h);
+                    v |= 1u << h;
+                }
+            dw[e] = d;
+            valid[e] = v;
         }
     }
-    return m;
-}
+};
 
 // ------------------------------------------------------------------ wave / block helpers
 __device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
@@ -230,30 +263,6 @@ template <int NB> __device__ __forceinline__ void flush_bins(const uint32_t *h, 
         if (c) __hip_atomic_fetch_add(&G[b], c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
-// Error-norm hand-off without cache maintenance: thread 0 of every list block publishes its
-// partial with a device-coherent store, waits until the store is acknowledged, and takes a
-// ticket; the block that draws the last ticket reads all partials with device-coherent loads.
-// (A release fence here would write back the whole L2 once per block.)  No block waits.
-__device__ __forceinline__ void coherent_store_f64(double *p, double v) {
-    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), static_cast<unsigned long long>(__double_as_longlong(v)),
-                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ double coherent_load_f64(const double *p) {
-    return __longlong_as_double(static_cast<long long>(__hip_atomic_load(
-        reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
-}
-__device__ __forceinline__ bool publish_and_take_ticket(double *slot, double v, uint32_t *ticket, uint32_t nblocks,
-                                                        uint32_t *s_flag) {
-    if (threadIdx.x == 0) {
-        coherent_store_f64(slot, v);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        const uint32_t t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *s_flag = (t == nblocks - 1u) ? 1u : 0u;
-    }
-    __syncthreads();
-    return *s_flag != 0u;
-}
-
 __device__ __forceinline__ int find_segment_by(const Launch &a, int g, bool by_chunk) {
     int s = 0;
     for (int i = 1; i < a.S; ++i) {
@@ -289,31 +298,25 @@ __global__ __launch_bounds__(BLOCK) void k_init(Launch a) {
 }
 
 // ------------------------------------------------------------------ k_hist1
-template <int VEC, bool FULL>
-__device__ __forceinline__ void hist1_tile(const void *x, int64_t t0, int64_t end, uint32_t *h) {
-    uint32_t raw[U][VEC];
-    uint32_t vm[U];
+// LDS histogram of the top digit with HREP interleaved copies: lane l adds into copy l % HREP of
+// its bin, stored at word bin * HREP + copy, so lanes that share a hot bin spread over banks.
+template <int VEC, bool FAST>
+__device__ __forceinline__ void hist1_tile(const uint32_t (&dw)[Stream<VEC>::SLOTS],
+                                           const uint32_t (&valid)[Stream<VEC>::SLOTS], uint32_t *h) {
+    constexpr int EPD = Stream<VEC>::EPD;
+    const uint32_t copy = threadIdx.x & (HREP - 1);
 #pragma unroll
-    for (int j = 0; j < U; ++j) {
-        const int64_t i0 = t0 + (static_cast<int64_t>(j) * BLOCK + threadIdx.x) * VEC;
-        if (FULL) {
-            load_vec<VEC>(x, i0, raw[j]);
-            vm[j] = (1u << VEC) - 1u;
-        } else {
-            vm[j] = load_guarded<VEC>(x, i0, end, raw[j]);
-        }
-    }
+    for (int e = 0; e < Stream<VEC>::SLOTS; ++e)
 #pragma unroll
-    for (int j = 0; j < U; ++j)
-#pragma unroll
-        for (int e = 0; e < VEC; ++e)
-            if (FULL || ((vm[j] >> e) & 1u)) atomicAdd(&h[key_of<VEC>(raw[j][e]) >> SH1], 1u);
+        for (int hh = 0; hh < EPD; ++hh)
+            if (FAST || ((valid[e] >> hh) & 1u))
+                atomicAdd(&h[(key_of<VEC>(elem_of<VEC>(dw[e], hh)) >> SH1) * HREP + copy], 1u);
 }
 
 template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist1(Launch a) {
-    __shared__ uint32_t h[NB1];
+    using St = Stream<VEC>;
+    __shared__ uint32_t h[NB1 * HREP];
     __shared__ uint32_t sm[NW];
-    constexpr int TILE = BLOCK * U * VEC;
 
     const int g = blockIdx.x;
     const int s = find_segment_by(a, g, true);
@@ -322,15 +325,45 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist1(Launch a) {
     const int64_t beg = static_cast<int64_t>(c) * a.E;
     const int64_t end = (beg + a.E < sg.n) ? beg + a.E : sg.n;
 
-    for (int b = threadIdx.x; b < NB1; b += BLOCK) h[b] = 0;
+    for (int b = threadIdx.x; b < NB1 * HREP; b += BLOCK) h[b] = 0;
     __syncthreads();
 
+    uint32_t cur[St::SLOTS], nxt[St::SLOTS], valid[St::SLOTS];
     int64_t t0 = beg;
-    if (sg.aligned16)
-        for (; t0 + TILE <= end; t0 += TILE) hist1_tile<VEC, true>(sg.x, t0, end, h);
-    for (; t0 < end; t0 += TILE) hist1_tile<VEC, false>(sg.x, t0, end, h);
+    if (sg.aligned4 && t0 + TILE <= end) {  // full tiles, the next one in flight while this one is counted
+        St::load_fast(sg.x, t0, cur);
+        for (;;) {
+            const bool more = t0 + 2 * static_cast<int64_t>(TILE) <= end;
+            if (more) St::load_fast(sg.x, t0 + TILE, nxt);
+            __builtin_amdgcn_sched_barrier(0);
+            hist1_tile<VEC, true>(cur, valid, h);
+            t0 += TILE;
+            if (!more) break;
+#pragma unroll
+            for (int e = 0; e < St::SLOTS; ++e) cur[e] = nxt[e];
+        }
+    }
+    for (; t0 < end; t0 += TILE) {
+        St::load_slow(sg.x, t0, end, cur, valid);
+        hist1_tile<VEC, false>(cur, valid, h);
+    }
     __syncthreads();
 
+    if (HREP > 1) {  // fold the copies into copy 0, compacted to h[0 .. NB1)
+        uint32_t folded[NB1 / BLOCK];
+#pragma unroll
+        for (int j = 0; j < NB1 / BLOCK; ++j) {
+            const int b = threadIdx.x + j * BLOCK;
+            uint32_t t = 0;
+#pragma unroll
+            for (int r = 0; r < HREP; ++r) t += h[b * HREP + r];
+            folded[j] = t;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < NB1 / BLOCK; ++j) h[threadIdx.x + j * BLOCK] = folded[j];
+        __syncthreads();
+    }
     flush_bins<NB1>(h, a.G1 + s * NB1);
     __syncthreads();
     block_suffix_inplace<NB1>(h, sm);
@@ -339,62 +372,106 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist1(Launch a) {
 }
 
 // ------------------------------------------------------------------ k_gather
-template <int VEC, bool FULL>
-__device__ __forceinline__ void gather_tile(const void *x, int64_t t0, int64_t end, uint32_t B1, uint32_t *h2,
-                                            uint32_t *wcnt, uint32_t &running, uint32_t cnt, int32_t *Li,
+// One tile.  Common path per element: clear the sign, compare with the bucket's lowest key
+// (the compare's lane mask is the keep bitmap of the slot), add the square of a dropped
+// element in fp64.  Kept elements are rare (about k/n + the bucket's share): each wave packs
+// its kept (index, value) pairs of the tile into an LDS staging row in index order, and after
+// the workgroup has exchanged its per-wave counts the row is written out with full-wave
+// stores; bucket members also count their second digit there.  Pairs beyond STAGE per wave and
+// tile (dense inputs, k close to n) are stored straight from the registers.
+constexpr int STAGE = 256;
+
+template <int VEC, bool FAST>
+__device__ __forceinline__ void gather_tile(const uint32_t (&dw)[Stream<VEC>::SLOTS],
+                                            const uint32_t (&valid)[Stream<VEC>::SLOTS], int64_t t0, uint32_t thr_lo,
+                                            uint32_t thr_hi, uint32_t *h2, uint32_t *wcnt, uint2 *stage,
+                                            uint32_t &running, uint32_t cnt, int32_t *Li,
                                             typename Raw<VEC>::type *Lv, double &acc) {
+    using St = Stream<VEC>;
+    using R = typename Raw<VEC>::type;
+    constexpr int EPD = St::EPD, SLOTS = St::SLOTS;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    uint32_t raw[U][VEC];
-    uint32_t vm[U];
+    uint64_t m[SLOTS][EPD];
+    uint32_t wc = 0;
 #pragma unroll
-    for (int j = 0; j < U; ++j) {
-        const int64_t i0 = t0 + (static_cast<int64_t>(j) * BLOCK + threadIdx.x) * VEC;
-        if (FULL) {
-            load_vec<VEC>(x, i0, raw[j]);
-            vm[j] = (1u << VEC) - 1u;
-        } else {
-            vm[j] = load_guarded<VEC>(x, i0, end, raw[j]);
-        }
-    }
-    uint32_t keepbits[U], lane_pre[U];
+    for (int e = 0; e < SLOTS; ++e)
 #pragma unroll
-    for (int j = 0; j < U; ++j) {
-        uint32_t kb = 0, lp = 0, wc = 0;
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-            const bool valid = FULL || ((vm[j] >> e) & 1u);
-            const uint32_t key = key_of<VEC>(raw[j][e]);
-            const uint32_t d = key >> SH1;
-            const bool keep = valid && d >= B1;
-            if (valid && d == B1) atomicAdd(&h2[(key >> SH2) & (NB2 - 1)], 1u);
-            const double xd = (valid && d < B1) ? static_cast<double>(value_of<VEC>(raw[j][e])) : 0.0;
+        for (int hh = 0; hh < EPD; ++hh) {
+            const uint32_t raw = elem_of<VEC>(dw[e], hh);
+            const bool ok = FAST || ((valid[e] >> hh) & 1u);
+            const bool keep = ok && key_of<VEC>(raw) >= thr_lo;
+            m[e][hh] = __ballot(keep);
+            wc += __popcll(m[e][hh]);
+            const double xd = (ok && !keep) ? static_cast<double>(value_of<VEC>(raw)) : 0.0;
             acc = fma(xd, xd, acc);
-            const uint64_t bal = __ballot(keep);
-            lp += lanes_below(bal);
-            wc += __popcll(bal);
-            kb |= (keep ? 1u : 0u) << e;
         }
-        keepbits[j] = kb;
-        lane_pre[j] = lp;
-        if (lane == 0) wcnt[j * NW + w] = wc;
+    if (lane == 0) wcnt[w] = wc;
+    if (wc != 0) {  // pack this wave's kept pairs, rank = position inside the wave's part of the tile
+        uint32_t slot_rank = 0;
+#pragma unroll
+        for (int e = 0; e < SLOTS; ++e) {
+            uint64_t any = 0;
+#pragma unroll
+            for (int hh = 0; hh < EPD; ++hh) any |= m[e][hh];
+            if (any == 0) continue;  // wave-uniform
+            uint32_t r = slot_rank;
+#pragma unroll
+            for (int hh = 0; hh < EPD; ++hh) r += lanes_below(m[e][hh]);
+            const uint32_t i0 = static_cast<uint32_t>(St::first_elem(t0, e));
+#pragma unroll
+            for (int hh = 0; hh < EPD; ++hh) {
+                if ((m[e][hh] >> lane) & 1u) {
+                    if (r < STAGE) stage[r] = make_uint2(i0 + hh, elem_of<VEC>(dw[e], hh));
+                    ++r;
+                }
+                slot_rank += __popcll(m[e][hh]);
+            }
+        }
     }
     __syncthreads();
-    const uint32_t c = (lane < U * NW) ? wcnt[lane] : 0u;
-    const uint32_t inc = wave_incl_scan(c);
-    const uint32_t tot = __shfl(inc, 63);
-    const uint32_t exc = inc - c;
+    uint32_t before = 0, tot = 0;
 #pragma unroll
-    for (int j = 0; j < U; ++j) {
-        uint32_t pos = running + __shfl(exc, j * NW + w) + lane_pre[j];
-        const int64_t i0 = t0 + (static_cast<int64_t>(j) * BLOCK + threadIdx.x) * VEC;
+    for (int i = 0; i < NW; ++i) {
+        const uint32_t t = wcnt[i];
+        before += (i < w) ? t : 0u;
+        tot += t;
+    }
+    const uint32_t base = running + before;
+    const uint32_t staged = wc < STAGE ? wc : STAGE;
+    for (uint32_t i = lane; i < staged; i += 64) {
+        const uint2 pr = stage[i];
+        const uint32_t pos = base + i;
+        if (pos < cnt) {
+            Li[pos] = static_cast<int32_t>(pr.x);
+            Lv[pos] = static_cast<R>(pr.y);
+        }
+        const uint32_t key = key_of<VEC>(pr.y);
+        if (key < thr_hi) atomicAdd(&h2[(key >> SH2) & (NB2 - 1)], 1u);
+    }
+    if (wc > STAGE) {  // wave-uniform, dense inputs only
+        uint32_t slot_rank = 0;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-            if ((keepbits[j] >> e) & 1u) {
-                if (pos < cnt) {
-                    Li[pos] = static_cast<int32_t>(i0 + e);
-                    Lv[pos] = static_cast<typename Raw<VEC>::type>(raw[j][e]);
+        for (int e = 0; e < SLOTS; ++e) {
+            uint32_t r = slot_rank;
+#pragma unroll
+            for (int hh = 0; hh < EPD; ++hh) r += lanes_below(m[e][hh]);
+            const uint32_t i0 = static_cast<uint32_t>(St::first_elem(t0, e));
+#pragma unroll
+            for (int hh = 0; hh < EPD; ++hh) {
+                if ((m[e][hh] >> lane) & 1u) {
+                    if (r >= STAGE) {
+                        const uint32_t raw = elem_of<VEC>(dw[e], hh);
+                        const uint32_t key = key_of<VEC>(raw);
+                        const uint32_t pos = base + r;
+                        if (pos < cnt) {
+                            Li[pos] = static_cast<int32_t>(i0 + hh);
+                            Lv[pos] = static_cast<R>(raw);
+                        }
+                        if (key < thr_hi) atomicAdd(&h2[(key >> SH2) & (NB2 - 1)], 1u);
+                    }
+                    ++r;
                 }
-                ++pos;
+                slot_rank += __popcll(m[e][hh]);
             }
         }
     }
@@ -403,12 +480,13 @@ __device__ __forceinline__ void gather_tile(const void *x, int64_t t0, int64_t e
 
 template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     using R = typename Raw<VEC>::type;
+    using St = Stream<VEC>;
     __shared__ uint32_t h[NB1];  // top-digit histogram during the prologue, then the second-digit one
-    __shared__ uint32_t wcnt[2][U * NW];
+    __shared__ uint32_t wcnt[2][NW];
+    __shared__ uint2 stage_all[NW][STAGE];
     __shared__ uint32_t sm[NW];
     __shared__ double smd[NW];
     __shared__ uint32_t s_pick[2];
-    constexpr int TILE = BLOCK * U * VEC;
 
     const int g = blockIdx.x;
     const int s = find_segment_by(a, g, true);
@@ -416,6 +494,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     const int c = g - sg.chunk_begin;
     const int64_t beg = static_cast<int64_t>(c) * a.E;
     const int64_t end = (beg + a.E < sg.n) ? beg + a.E : sg.n;
+    uint2 *stage = stage_all[threadIdx.x >> 6];
 
     // Prologue, the same in every block of the segment: bucket of the top digit, then this
     // chunk's slot range in the list = scan of the earlier chunks' counts of digits >= B1.
@@ -437,6 +516,8 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     const int64_t lo = sg.l_base + off;
     int32_t *Li = a.L_idx + lo;
     R *Lv = static_cast<R *>(a.L_val) + lo;
+    const uint32_t thr_lo = B1 << SH1;         // lowest key of bucket B1 (2^31 when nothing is kept)
+    const uint32_t thr_hi = (B1 + 1u) << SH1;  // lowest key above the bucket
 
     uint32_t *h2 = h;
     for (int b = threadIdx.x; b < NB2; b += BLOCK) h2[b] = 0;
@@ -445,12 +526,26 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     double acc = 0.0;
     uint32_t running = 0;
     int buf = 0;
+    uint32_t cur[St::SLOTS], nxt[St::SLOTS], valid[St::SLOTS];
     int64_t t0 = beg;
-    if (sg.aligned16)
-        for (; t0 + TILE <= end; t0 += TILE, buf ^= 1)
-            gather_tile<VEC, true>(sg.x, t0, end, B1, h2, wcnt[buf], running, cnt, Li, Lv, acc);
-    for (; t0 < end; t0 += TILE, buf ^= 1)
-        gather_tile<VEC, false>(sg.x, t0, end, B1, h2, wcnt[buf], running, cnt, Li, Lv, acc);
+    if (sg.aligned4 && t0 + TILE <= end) {
+        St::load_fast(sg.x, t0, cur);
+        for (;;) {
+            const bool more = t0 + 2 * static_cast<int64_t>(TILE) <= end;
+            if (more) St::load_fast(sg.x, t0 + TILE, nxt);
+            __builtin_amdgcn_sched_barrier(0);
+            gather_tile<VEC, true>(cur, valid, t0, thr_lo, thr_hi, h2, wcnt[buf], stage, running, cnt, Li, Lv, acc);
+            t0 += TILE;
+            buf ^= 1;
+            if (!more) break;
+#pragma unroll
+            for (int e = 0; e < St::SLOTS; ++e) cur[e] = nxt[e];
+        }
+    }
+    for (; t0 < end; t0 += TILE, buf ^= 1) {
+        St::load_slow(sg.x, t0, end, cur, valid);
+        gather_tile<VEC, false>(cur, valid, t0, thr_lo, thr_hi, h2, wcnt[buf], stage, running, cnt, Li, Lv, acc);
+    }
 
     const double bsum = block_sum_f64(acc, smd);
     if (threadIdx.x == 0) a.chunk_err[g] = bsum;
@@ -472,6 +567,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
     using R = typename Raw<VEC>::type;
     __shared__ uint32_t h[NB2 > NB3 ? NB2 : NB3];
     __shared__ uint32_t sm[NW];
+    __shared__ double smd[NW];
     __shared__ uint32_t s_pick[2];
 
     const int g = blockIdx.x;
@@ -497,12 +593,18 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
     for (int b = threadIdx.x; b < NB3; b += BLOCK) h3[b] = 0;
     __syncthreads();
     uint32_t def = 0;  // keys above the prefix: kept whatever the last digit is
+    double acc = 0.0;  // squares of the keys below the prefix: dropped whatever the last digit is
     for (uint32_t i = beg + threadIdx.x; i < end; i += BLOCK) {
-        const uint32_t key = key_of<VEC>(Lv[i]);
+        const uint32_t raw = Lv[i];
+        const uint32_t key = key_of<VEC>(raw);
         const uint32_t p = key >> SH2;
         def += (p > P) ? 1u : 0u;
         if (p == P) atomicAdd(&h3[key & (NB3 - 1)], 1u);
+        const double xd = (p < P) ? static_cast<double>(value_of<VEC>(raw)) : 0.0;
+        acc = fma(xd, xd, acc);
     }
+    const double bsum = block_sum_f64(acc, smd);
+    if (threadIdx.x == 0) a.lerr[g] = bsum;
     __syncthreads();
     flush_bins<NB3>(h3, a.G3 + s * NB3);
     __syncthreads();
@@ -522,7 +624,6 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     __shared__ double smd[NW];
     __shared__ uint32_t s_pick[2];
     __shared__ uint32_t s_off[2];
-    __shared__ uint32_t s_flag;
 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int g = blockIdx.x;
@@ -534,12 +635,41 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     const uint32_t c_gt2 = a.state[s].c_gt2;
     const uint32_t kout = static_cast<uint32_t>(sg.k);
 
-    // Prologue: last digit -> threshold key T and tie quota q; then this block's output
-    // offsets = scan over the earlier list blocks of (#keys above T, #keys equal to T).
+    // Prologue: last digit -> threshold key T and tie quota q.
     uint32_t B3, above3;
+    uint32_t my_bins[NB3 / BLOCK];  // raw counts of the third-digit bins this thread owns
+#pragma unroll
+    for (int j = 0; j < NB3 / BLOCK; ++j) my_bins[j] = a.G3[s * NB3 + threadIdx.x * (NB3 / BLOCK) + j];
     pick_from_global<NB3>(a.G3 + s * NB3, kout - c_gt2, h, sm, s_pick, B3, above3);
     const uint32_t T = (B3 < NB3) ? ((P << BITS3) | B3) : 0xFFFFFFFFu;
     const uint32_t q = kout - (c_gt2 + above3);
+
+    // Error norm of the segment, by its first list block only.  Everything it needs was stored by
+    // earlier kernels: per-chunk sums of squares below bucket B1 (k_gather), per-list-block sums of
+    // squares below the 21-bit prefix (k_hist3), and the counts of the entries that match the
+    // prefix: all entries of one third-digit bin share one key, hence one square, so the dropped
+    // ones among them add count * value^2.  Fixed summation order.
+    if (lb == 0 && a.err_out != nullptr) {
+        double part = 0.0;
+        for (int cc = threadIdx.x; cc < sg.nchunks; cc += BLOCK) part += a.chunk_err[sg.chunk_begin + cc];
+        for (int bb = threadIdx.x; bb < sg.lb_count; bb += BLOCK) part += a.lerr[sg.lb_begin + bb];
+#pragma unroll
+        for (int j = 0; j < NB3 / BLOCK; ++j) {
+            const uint32_t b = threadIdx.x * (NB3 / BLOCK) + j;
+            uint32_t dropped = 0;
+            if (b < B3 || B3 >= NB3) dropped = my_bins[j];
+            else if (b == B3) dropped = my_bins[j] - q;
+            if (dropped) {
+                const double v = static_cast<double>(__uint_as_float((P << BITS3) | b));
+                part = fma(static_cast<double>(dropped) * v, v, part);
+            }
+        }
+        const double tot = block_sum_f64(part, smd);
+        if (threadIdx.x == 0) a.err_out[s] = static_cast<float>(sqrt(tot));
+    }
+
+    // Output offsets of this list block = scan over the earlier list blocks of
+    // (#keys above T, #keys equal to T).
     {
         uint32_t gt = 0, eq = 0;
         if (static_cast<int>(threadIdx.x) < sg.lb_count && B3 < NB3) {
@@ -566,12 +696,11 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     uint32_t beg, end;
     list_range(m, lb, sg.lb_count, beg, end);
 
-    double acc = 0.0;
     int buf = 0;
     for (uint32_t t0 = beg; t0 < end; t0 += BLOCK * LU, buf ^= 1) {
         uint32_t raw[LU];
         int32_t id[LU];
-        uint32_t pre_gt[LU], pre_eq[LU], cls[LU];  // cls: 0 below T, 1 equal, 2 above, 3 no element
+        uint32_t pre_gt[LU], pre_eq[LU], cls[LU];  // cls: 0 not kept for sure, 1 equal to T, 2 above T
 #pragma unroll
         for (int j = 0; j < LU; ++j) {
             const uint32_t i = t0 + j * BLOCK + threadIdx.x;
@@ -580,7 +709,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
             id[j] = valid ? Li[i] : 0;
             const uint32_t key = key_of<VEC>(raw[j]);
             const bool gt = valid && key > T, eq = valid && key == T;
-            cls[j] = valid ? (gt ? 2u : (eq ? 1u : 0u)) : 3u;
+            cls[j] = gt ? 2u : (eq ? 1u : 0u);
             const uint64_t bg = __ballot(gt), be = __ballot(eq);
             pre_gt[j] = lanes_below(bg);
             pre_eq[j] = lanes_below(be);
@@ -598,32 +727,17 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
         for (int j = 0; j < LU; ++j) {
             const uint32_t gt_before = run_gt + __shfl(ig - cg, j * NW + w) + pre_gt[j];
             const uint32_t eq_before = run_eq + __shfl(ie - ce, j * NW + w) + pre_eq[j];
-            const bool keep = cls[j] == 2u || (cls[j] == 1u && eq_before < q);
-            if (keep) {
+            if (cls[j] == 2u || (cls[j] == 1u && eq_before < q)) {
                 const uint32_t pos = gt_before + (eq_before < q ? eq_before : q);
                 if (pos < kout) {
                     oi[pos] = id[j];
                     ov[pos] = static_cast<R>(raw[j]);
                 }
-            } else if (cls[j] != 3u) {
-                const double xd = static_cast<double>(value_of<VEC>(raw[j]));
-                acc = fma(xd, xd, acc);
             }
         }
         run_gt += tg;
         run_eq += te;
     }
-    if (a.err_out == nullptr) return;
-
-    // Error norm of the segment: the block that draws the last ticket adds the chunk partials,
-    // then the list-block partials, in a fixed order.
-    const double bsum = block_sum_f64(acc, smd);
-    if (!publish_and_take_ticket(a.lerr + g, bsum, &a.state[s].ticket, sg.lb_count, &s_flag)) return;
-    double part = 0.0;
-    for (int cc = threadIdx.x; cc < sg.nchunks; cc += BLOCK) part += a.chunk_err[sg.chunk_begin + cc];
-    for (int bb = threadIdx.x; bb < sg.lb_count; bb += BLOCK) part += coherent_load_f64(a.lerr + sg.lb_begin + bb);
-    const double tot = block_sum_f64(part, smd);
-    if (threadIdx.x == 0) a.err_out[s] = static_cast<float>(sqrt(tot));
 }
 
 // ------------------------------------------------------------------ decompress / streaming kernels
@@ -648,6 +762,74 @@ __global__ __launch_bounds__(BLOCK) void k_scatter(const int32_t *idx, const R *
     if (i >= 0 && i < n) y[i] = val[j];
 }
 
+// Cooperative lower bound by half a workgroup: the first j in [0, k) with idx[j] >= value (k if
+// none), for ascending idx.  The BLOCK / 2 threads of the half probe evenly spaced entries; the
+// number of probes below `value` narrows the range [lo, hi] by BLOCK / 2 per round.  Both halves
+// of the workgroup call this together with the same `rounds` (it contains barriers); cntr is one
+// LDS word owned by the half.  With idx not ascending the result is some position in [0, k]:
+// memory-safe, meaningless.
+__device__ __forceinline__ uint32_t half_block_lower_bound(const int32_t *idx, uint32_t k, int64_t value,
+                                                           int rounds, uint32_t *cntr) {
+    constexpr uint32_t H = BLOCK / 2;
+    const uint32_t t = threadIdx.x % H;
+    uint32_t lo = 0, hi = k;  // invariant: idx[j] < value for j < lo, idx[hi] >= value or hi == k
+    for (int r = 0; r < rounds; ++r) {
+        const uint32_t width = hi - lo;
+        const uint32_t step = width ? (width + H - 1) / H : 1u;
+        const uint64_t p = static_cast<uint64_t>(lo) + static_cast<uint64_t>(t) * step;
+        const bool below = p < hi && static_cast<int64_t>(idx[p]) < value;
+        if (t == 0) *cntr = 0;
+        __syncthreads();
+        const uint64_t bal = __ballot(below);
+        if ((threadIdx.x & 63) == 0 && bal) atomicAdd(cntr, static_cast<uint32_t>(__popcll(bal)));
+        __syncthreads();
+        const uint32_t c = *cntr;  // probes 0 .. c-1 are below value
+        __syncthreads();
+        if (width) {
+            const uint32_t nprobe = (width + step - 1) / step;
+            const uint32_t old_lo = lo;
+            lo = c ? old_lo + (c - 1) * step + 1 : old_lo;
+            hi = c ? (c < nprobe ? old_lo + c * step : hi) : old_lo;
+        }
+    }
+    return lo;
+}
+
+// Decompress for ascending indices in one kernel.  The output is cut into byte spans: workgroup b
+// owns bytes [B_b, B_b+1) with B_0 = 0, B_b = head + b * span (16-byte aligned addresses) and
+// B_last = total.  It zero-fills its span with 16-byte stores, finds its entries by two
+// cooperative searches and writes them after a barrier.  Every output byte is written by one
+// workgroup only; an entry whose index lies outside the span that the search assigned it to
+// (possible only when idx is not ascending) is skipped.
+template <typename R>
+__global__ __launch_bounds__(BLOCK) void k_merge(const int32_t *idx, const R *val, uint32_t k, unsigned char *y,
+                                                 size_t total, size_t head, size_t span, int rounds) {
+    __shared__ uint32_t cntr[2];
+    __shared__ uint32_t s_range[2];
+    const size_t byte_a = blockIdx.x == 0 ? 0 : head + static_cast<size_t>(blockIdx.x) * span;
+    const size_t byte_b = blockIdx.x + 1 == gridDim.x ? total : head + static_cast<size_t>(blockIdx.x + 1) * span;
+    const size_t va = blockIdx.x == 0 ? (head < byte_b ? head : byte_b) : byte_a;  // aligned start
+    const size_t nvec = (byte_b - va) / 16;
+    uint4 *body = reinterpret_cast<uint4 *>(y + va);
+    const uint4 z = make_uint4(0, 0, 0, 0);
+    for (size_t i = threadIdx.x; i < nvec; i += BLOCK) body[i] = z;
+    for (size_t i = byte_a + threadIdx.x; i < va; i += BLOCK) y[i] = 0;
+    for (size_t i = va + nvec * 16 + threadIdx.x; i < byte_b; i += BLOCK) y[i] = 0;
+
+    const int64_t ea = static_cast<int64_t>(byte_a / sizeof(R)), eb = static_cast<int64_t>(byte_b / sizeof(R));
+    const bool upper = threadIdx.x >= BLOCK / 2;
+    const uint32_t pos = half_block_lower_bound(idx, k, upper ? eb : ea, rounds, &cntr[upper ? 1 : 0]);
+    if (threadIdx.x == 0) s_range[0] = pos;
+    if (threadIdx.x == BLOCK / 2) s_range[1] = pos;
+    __syncthreads();  // also orders this workgroup's zero stores before its value stores
+    R *out = reinterpret_cast<R *>(y);
+    const uint32_t jb = s_range[1];
+    for (uint32_t j = s_range[0] + threadIdx.x; j < jb; j += BLOCK) {
+        const int64_t i = idx[j];
+        if (i >= ea && i < eb) out[i] = val[j];
+    }
+}
+
 __global__ __launch_bounds__(BLOCK) void k_copy16(uint4 *dst, const uint4 *src, size_t n16) {
     const size_t stride = static_cast<size_t>(gridDim.x) * BLOCK;
     for (size_t i = static_cast<size_t>(blockIdx.x) * BLOCK + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
@@ -670,7 +852,8 @@ inline int elem_size(adatopk_dtype dt) { return dt == ADATOPK_F32 ? 4 : 2; }
 inline bool dtype_ok(adatopk_dtype dt) { return dt == ADATOPK_F32 || dt == ADATOPK_BF16; }
 
 int64_t chunk_elems(int64_t n_total, adatopk_dtype dt) {
-    const int64_t tile = static_cast<int64_t>(BLOCK) * U * (16 / elem_size(dt));
+    (void)dt;
+    const int64_t tile = TILE;
     int64_t e = (n_total + CTARGET - 1) / CTARGET;
     if (e < tile) e = tile;
     e = (e + tile - 1) / tile * tile;
@@ -727,33 +910,46 @@ void bounds_for(int64_t n_total, int32_t S, adatopk_dtype dt, int64_t *max_chunk
     *max_lb = static_cast<int64_t>(batch) * list_blocks_cap(S);
 }
 
-// ---- stage timing (measurement hook)
-constexpr int NSTAGE_C = 5, NSTAGE_D = 2;
-const char *const kStageNames[NSTAGE_C + NSTAGE_D] = {"k_init", "k_hist1", "k_gather", "k_hist3",
-                                                        "k_emit", "k_fill",  "k_scatter"};
+// ---- stage timing (measurement hook): a chain of events per call kind, one interval per kernel
+enum Stage { ST_INIT, ST_HIST1, ST_GATHER, ST_HIST3, ST_EMIT, ST_FILL, ST_SCATTER, ST_MERGE, NSTAGE };
+const char *const kStageNames[NSTAGE] = {"k_init", "k_hist1", "k_gather", "k_hist3",
+                                         "k_emit", "k_fill",  "k_scatter", "k_merge"};
+constexpr int CHAIN_MAX = 8;
+struct Chain {
+    hipEvent_t ev[CHAIN_MAX];
+    int stage[CHAIN_MAX];  // stage[j] ran between ev[j] and ev[j + 1]
+    int n;                 // events recorded by the latest timed call
+};
 bool g_measure = false;
 bool g_events_made = false;
-hipEvent_t g_ev_c[NSTAGE_C + 1], g_ev_d[NSTAGE_D + 1];
-int g_rec_c = 0, g_rec_d = 0;  // events recorded by the latest timed call
+Chain g_chain_c, g_chain_d;
 
-inline void mark(hipEvent_t *ev, int *count, int slot, hipStream_t st) {
-    if (!g_measure) return;
-    if (hipEventRecord(ev[slot], st) == hipSuccess) *count = slot + 1;
+inline void chain_begin(Chain &c, hipStream_t st) {
+    c.n = 0;
+    if (g_measure && hipEventRecord(c.ev[0], st) == hipSuccess) c.n = 1;
+}
+inline void chain_mark(Chain &c, int stage, hipStream_t st) {
+    if (!g_measure || c.n == 0 || c.n >= CHAIN_MAX) return;
+    if (hipEventRecord(c.ev[c.n], st) == hipSuccess) {
+        c.stage[c.n - 1] = stage;
+        ++c.n;
+    }
 }
 
 template <int VEC> adatopk_status launch_batch(const Launch &a, int total_chunks, int total_lb, hipStream_t st) {
-    g_rec_c = 0;
-    mark(g_ev_c, &g_rec_c, 0, st);
+    chain_begin(g_chain_c, st);
     hipLaunchKernelGGL(k_init, dim3(a.S), dim3(BLOCK), 0, st, a);
-    mark(g_ev_c, &g_rec_c, 1, st);
-    if (total_chunks > 0) hipLaunchKernelGGL(k_hist1<VEC>, dim3(total_chunks), dim3(BLOCK), 0, st, a);
-    mark(g_ev_c, &g_rec_c, 2, st);
-    if (total_chunks > 0) hipLaunchKernelGGL(k_gather<VEC>, dim3(total_chunks), dim3(BLOCK), 0, st, a);
-    mark(g_ev_c, &g_rec_c, 3, st);
+    chain_mark(g_chain_c, ST_INIT, st);
+    if (total_chunks > 0) {
+        hipLaunchKernelGGL(k_hist1<VEC>, dim3(total_chunks), dim3(BLOCK), 0, st, a);
+        chain_mark(g_chain_c, ST_HIST1, st);
+        hipLaunchKernelGGL(k_gather<VEC>, dim3(total_chunks), dim3(BLOCK), 0, st, a);
+        chain_mark(g_chain_c, ST_GATHER, st);
+    }
     hipLaunchKernelGGL(k_hist3<VEC>, dim3(total_lb), dim3(BLOCK), 0, st, a);
-    mark(g_ev_c, &g_rec_c, 4, st);
+    chain_mark(g_chain_c, ST_HIST3, st);
     hipLaunchKernelGGL(k_emit<VEC>, dim3(total_lb), dim3(BLOCK), 0, st, a);
-    mark(g_ev_c, &g_rec_c, 5, st);
+    chain_mark(g_chain_c, ST_EMIT, st);
     return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
 }
 
@@ -819,7 +1015,7 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
             d.nchunks = static_cast<int32_t>((n[s] + E - 1) / E);
             d.lb_begin = lbs;
             d.lb_count = list_blocks(n[s], S);
-            d.aligned16 = (reinterpret_cast<uintptr_t>(dense[s]) % 16 == 0) ? 1u : 0u;
+            d.aligned4 = (reinterpret_cast<uintptr_t>(dense[s]) % 4 == 0) ? 1u : 0u;
             chunks += d.nchunks;
             lbs += d.lb_count;
             l_base += n[s];
@@ -887,11 +1083,10 @@ adatopk_status adatopk_decompress(const int32_t *idx, const void *val, int64_t k
         return ADATOPK_EINVAL;
     if (n == 0) return ADATOPK_OK;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    g_rec_d = 0;
-    mark(g_ev_d, &g_rec_d, 0, st);
+    chain_begin(g_chain_d, st);
     const adatopk_status rc = fill_impl(dense_out, static_cast<size_t>(n) * es, st);
     if (rc != ADATOPK_OK) return rc;
-    mark(g_ev_d, &g_rec_d, 1, st);
+    chain_mark(g_chain_d, ST_FILL, st);
     if (k > 0) {
         const int grid = static_cast<int>((k + BLOCK - 1) / BLOCK);
         if (dt == ADATOPK_F32)
@@ -901,41 +1096,70 @@ adatopk_status adatopk_decompress(const int32_t *idx, const void *val, int64_t k
             hipLaunchKernelGGL(k_scatter<uint16_t>, dim3(grid), dim3(BLOCK), 0, st, idx,
                                static_cast<const uint16_t *>(val), k, static_cast<uint16_t *>(dense_out), n);
     }
-    mark(g_ev_d, &g_rec_d, 2, st);
+    chain_mark(g_chain_d, ST_SCATTER, st);
+    return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
+}
+
+adatopk_status adatopk_decompress_sorted(const int32_t *idx, const void *val, int64_t k, adatopk_dtype dt,
+                                         void *dense_out, int64_t n, void *hip_stream) {
+    if (!dtype_ok(dt) || n < 0 || k < 0 || n >= (static_cast<int64_t>(1) << 31) || k >= (static_cast<int64_t>(1) << 31))
+        return ADATOPK_EINVAL;
+    const int es = elem_size(dt);
+    if (n > 0 && (!dense_out || reinterpret_cast<uintptr_t>(dense_out) % es)) return ADATOPK_EINVAL;
+    if (k > 0 && (!idx || !val || reinterpret_cast<uintptr_t>(idx) % 4 || reinterpret_cast<uintptr_t>(val) % es))
+        return ADATOPK_EINVAL;
+    if (n == 0) return ADATOPK_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const size_t total = static_cast<size_t>(n) * es;
+    size_t head = (16 - reinterpret_cast<uintptr_t>(dense_out) % 16) % 16;
+    if (head > total) head = total;
+    const size_t body = total - head;
+    size_t span = (body / MERGE_SPANS + 15) / 16 * 16;
+    if (span < MERGE_MIN_SPAN) span = MERGE_MIN_SPAN;
+    const unsigned grid = static_cast<unsigned>(body / span + 1);  // the last workgroup takes the remainder
+    int rounds = 0;
+    for (uint64_t w = static_cast<uint64_t>(k); w > 0; ++rounds) w = (w + BLOCK / 2 - 1) / (BLOCK / 2) - 1;
+    chain_begin(g_chain_d, st);
+    if (dt == ADATOPK_F32)
+        hipLaunchKernelGGL(k_merge<uint32_t>, dim3(grid), dim3(BLOCK), 0, st, idx, static_cast<const uint32_t *>(val),
+                           static_cast<uint32_t>(k), static_cast<unsigned char *>(dense_out), total, head, span, rounds);
+    else
+        hipLaunchKernelGGL(k_merge<uint16_t>, dim3(grid), dim3(BLOCK), 0, st, idx, static_cast<const uint16_t *>(val),
+                           static_cast<uint32_t>(k), static_cast<unsigned char *>(dense_out), total, head, span, rounds);
+    chain_mark(g_chain_d, ST_MERGE, st);
     return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
 }
 
 // ---- measurement hooks
 adatopk_status adatopk_measure_enable(int32_t on) {
     if (on && !g_events_made) {
-        for (int i = 0; i <= NSTAGE_C; ++i)
-            if (hipEventCreate(&g_ev_c[i]) != hipSuccess) return ADATOPK_ERUNTIME;
-        for (int i = 0; i <= NSTAGE_D; ++i)
-            if (hipEventCreate(&g_ev_d[i]) != hipSuccess) return ADATOPK_ERUNTIME;
+        for (int i = 0; i < CHAIN_MAX; ++i)
+            if (hipEventCreate(&g_chain_c.ev[i]) != hipSuccess || hipEventCreate(&g_chain_d.ev[i]) != hipSuccess)
+                return ADATOPK_ERUNTIME;
         g_events_made = true;
     }
     g_measure = on != 0;
-    g_rec_c = g_rec_d = 0;
+    g_chain_c.n = g_chain_d.n = 0;
     return ADATOPK_OK;
 }
 
-int32_t adatopk_measure_stage_count(void) { return NSTAGE_C + NSTAGE_D; }
+int32_t adatopk_measure_stage_count(void) { return NSTAGE; }
 
 const char *adatopk_measure_stage_name(int32_t stage) {
-    return (stage >= 0 && stage < NSTAGE_C + NSTAGE_D) ? kStageNames[stage] : "";
+    return (stage >= 0 && stage < NSTAGE) ? kStageNames[stage] : "";
 }
 
 adatopk_status adatopk_measure_read(float *ms_out) {
     if (!ms_out || !g_events_made) return ADATOPK_EINVAL;
-    for (int i = 0; i < NSTAGE_C + NSTAGE_D; ++i) ms_out[i] = -1.0f;
-    if (g_rec_c > 0 && hipEventSynchronize(g_ev_c[g_rec_c - 1]) != hipSuccess) return ADATOPK_ERUNTIME;
-    for (int i = 0; i + 1 < g_rec_c; ++i)
-        if (hipEventElapsedTime(&ms_out[i], g_ev_c[i], g_ev_c[i + 1]) != hipSuccess) return ADATOPK_ERUNTIME;
-    if (g_rec_d > 0 && hipEventSynchronize(g_ev_d[g_rec_d - 1]) != hipSuccess) return ADATOPK_ERUNTIME;
-    for (int i = 0; i + 1 < g_rec_d; ++i)
-        if (hipEventElapsedTime(&ms_out[NSTAGE_C + i], g_ev_d[i], g_ev_d[i + 1]) != hipSuccess)
-            return ADATOPK_ERUNTIME;
-    g_rec_c = g_rec_d = 0;
+    for (int i = 0; i < NSTAGE; ++i) ms_out[i] = -1.0f;
+    Chain *chains[2] = {&g_chain_c, &g_chain_d};
+    for (Chain *c : chains) {
+        if (c->n > 0 && hipEventSynchronize(c->ev[c->n - 1]) != hipSuccess) return ADATOPK_ERUNTIME;
+        for (int j = 0; j + 1 < c->n; ++j)
+            if (hipEventElapsedTime(&ms_out[c->stage[j]], c->ev[j], c->ev[j + 1]) != hipSuccess)
+                return ADATOPK_ERUNTIME;
+        c->n = 0;
+    }
     return ADATOPK_OK;
 }
 

@@ -41,13 +41,13 @@ def gpu_compress(x: np.ndarray, k: int, offset_elems: int = 0, want_err: bool = 
     return to_host(idx)[:k], to_host(val)[:k], (to_host(err)[0] if want_err else None)
 
 
-def gpu_decompress(idx: np.ndarray, val: np.ndarray, n: int, offset_elems: int = 0) -> np.ndarray:
+def gpu_decompress(idx: np.ndarray, val: np.ndarray, n: int, offset_elems: int = 0, sorted_call: bool = False) -> np.ndarray:
     k = int(idx.size)
     di = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)).cuda() if k else torch.zeros(1, dtype=torch.int32, device="cuda")
     dv = to_device(val) if k else torch.zeros(1, dtype=torch.float32 if val.dtype == np.float32 else torch.bfloat16, device="cuda")
     buf = torch.full((n + offset_elems + 8,), 7.0, dtype=dv.dtype, device="cuda")  # poisoned; 8 guard elements
     out = buf[offset_elems:offset_elems + n]
-    B.adatopk_decompress(di, dv, k, out)
+    (B.adatopk_decompress_sorted if sorted_call else B.adatopk_decompress)(di, dv, k, out)
     torch.cuda.synchronize()
     guard = to_host(buf[offset_elems + n:])
     assert np.all(bits(guard) == bits(to_host(torch.full((8,), 7.0, dtype=dv.dtype)))), "decompress wrote past n"

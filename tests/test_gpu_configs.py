@@ -19,8 +19,9 @@ def full_check(x, k):
     gi, gv, ge = H.gpu_compress(x, k)
     assert np.array_equal(gi, ri) and np.array_equal(H.bits(gv), H.bits(rv))
     assert H.same_err(ge, re, ERR_RTOL), (ge, re)
-    gy = H.gpu_decompress(gi, gv, x.size)
-    assert np.array_equal(H.bits(gy), H.bits(orc.decompress(ri, rv, x.size)))
+    ry = orc.decompress(ri, rv, x.size)
+    assert np.array_equal(H.bits(H.gpu_decompress(gi, gv, x.size)), H.bits(ry))
+    assert np.array_equal(H.bits(H.gpu_decompress(gi, gv, x.size, sorted_call=True)), H.bits(ry))
     return ri, rv
 
 

@@ -26,6 +26,8 @@ def check_one(x, k, offset_elems=0, label=""):
     ry = orc.decompress(ri, rv, n)
     gy = H.gpu_decompress(gi, gv, n, offset_elems)
     assert np.array_equal(H.bits(gy), H.bits(ry)), "reconstruction differs " + label
+    gy = H.gpu_decompress(gi, gv, n, offset_elems, sorted_call=True)
+    assert np.array_equal(H.bits(gy), H.bits(ry)), "reconstruction (ascending-index call) differs " + label
 
 
 def ks_for(n):
@@ -84,6 +86,30 @@ def test_decompress_unsorted_and_out_of_range():
     ok = (bad >= 0) & (bad < n)
     assert np.array_equal(H.bits(H.gpu_decompress(bad, val, n)), H.bits(orc.decompress(bad[ok], val[ok], n)))
     assert np.all(H.gpu_decompress(np.empty(0, np.int32), np.empty(0, np.float32), 1000) == 0)
+
+
+def test_decompress_sorted_spans_and_misuse():
+    import gpu_harness as H
+
+    rng = np.random.Generator(np.random.PCG64(10))
+    for n, k, dtype in ((5_000_011, 50_000, "f32"), (5_000_011, 50_000, "bf16"), (1_000_000, 1_000_000, "f32"),
+                        (4097, 1, "bf16"), (100_000, 0, "f32")):
+        idx = np.sort(rng.permutation(n)[:k]).astype(np.int32)
+        val = wl.small_case("normal", max(k, 1), seed=k + 1, dtype=dtype)[:k]
+        for off in (0, 1, 3):
+            got = H.gpu_decompress(idx, val, n, off, sorted_call=True)
+            assert np.array_equal(H.bits(got), H.bits(orc.decompress(idx, val, n))), (n, k, dtype, off)
+    # clustered indices: all entries fall into one span, most spans have none
+    n, k = 3_000_000, 20_000
+    idx = (np.arange(k) + 1_234_567).astype(np.int32)
+    val = wl.small_case("normal", k, seed=2)
+    assert np.array_equal(H.bits(H.gpu_decompress(idx, val, n, 0, True)), H.bits(orc.decompress(idx, val, n)))
+    # a caller that breaks the ascending-order promise gets a memory-safe call: every element written is
+    # either zero or the value that belongs there (the harness checks the guard elements around the buffer)
+    shuffled = rng.permutation(idx).astype(np.int32)
+    got = H.gpu_decompress(shuffled, val, n, 0, True)
+    full = orc.decompress(shuffled, val, n)
+    assert np.all((H.bits(got) == 0) | (H.bits(got) == H.bits(full)))
 
 
 def test_runs_are_bit_identical():
