@@ -174,6 +174,12 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
                                      __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
 }
 
+// base + number of set bits of mask in lanes below this one (the add rides on the mbcnt pair)
+__device__ __forceinline__ uint32_t lanes_below_plus(uint64_t mask, uint32_t base) {
+    return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                                     __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), base));
+}
+
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
     const int lane = threadIdx.x & 63;
 #pragma unroll
@@ -374,24 +380,44 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist1(Launch a) {
 // ------------------------------------------------------------------ k_gather
 // One tile.  Common path per element: clear the sign, compare with the bucket's lowest key
 // (the compare's lane mask is the keep bitmap of the slot), add the square of a dropped
-// element in fp64.  Kept elements are rare (about k/n + the bucket's share): each wave packs
-// its kept (index, value) pairs of the tile into an LDS staging row in index order, and after
-// the workgroup has exchanged its per-wave counts the row is written out with full-wave
-// stores; bucket members also count their second digit there.  Pairs beyond STAGE per wave and
-// tile (dense inputs, k close to n) are stored straight from the registers.
-constexpr int STAGE = 256;
+// element in fp64.  Kept elements are rare (about k/n + the bucket's share).  After the waves
+// have exchanged their counts, every kept (index, value) pair is written to its list position
+// inside an LDS stage that holds STAGE_CAP consecutive list slots of the chunk; the stage goes
+// out to memory with full-width stores only when it would overflow and at the end of the
+// chunk, so the streaming loop itself issues loads only (loads and stores share one in-order
+// counter: a store inside the loop would make every wait for the next tile's loads drain it).
+// A tile that alone holds more than STAGE_CAP pairs (dense input, k close to n) stores directly.
+constexpr int STAGE_CAP = 2048;
+
+// Writes list slots [from, to) of the chunk from the stage to memory and counts the second
+// digit of the bucket members among them.  stage[0] is list slot `from`.
+template <int VEC>
+__device__ __forceinline__ void flush_stage(const uint2 *stage, uint32_t from, uint32_t to, uint32_t cnt,
+                                            uint32_t thr_hi, uint32_t *h2, int32_t *Li,
+                                            typename Raw<VEC>::type *Lv) {
+    for (uint32_t i = from + threadIdx.x; i < to; i += BLOCK) {
+        const uint2 pr = stage[i - from];
+        if (i < cnt) {
+            Li[i] = static_cast<int32_t>(pr.x);
+            Lv[i] = static_cast<typename Raw<VEC>::type>(pr.y);
+        }
+        const uint32_t key = key_of<VEC>(pr.y);
+        if (key < thr_hi) atomicAdd(&h2[(key >> SH2) & (NB2 - 1)], 1u);
+    }
+}
 
 template <int VEC, bool FAST>
 __device__ __forceinline__ void gather_tile(const uint32_t (&dw)[Stream<VEC>::SLOTS],
                                             const uint32_t (&valid)[Stream<VEC>::SLOTS], int64_t t0, uint32_t thr_lo,
                                             uint32_t thr_hi, uint32_t *h2, uint32_t *wcnt, uint2 *stage,
-                                            uint32_t &running, uint32_t cnt, int32_t *Li,
+                                            uint32_t &running, uint32_t &flushed, uint32_t cnt, int32_t *Li,
                                             typename Raw<VEC>::type *Lv, double &acc) {
     using St = Stream<VEC>;
     using R = typename Raw<VEC>::type;
     constexpr int EPD = St::EPD, SLOTS = St::SLOTS;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     uint64_t m[SLOTS][EPD];
+    bool keep[SLOTS][EPD];  // lives as the compare's lane mask, i.e. the same registers as m
     uint32_t wc = 0;
 #pragma unroll
     for (int e = 0; e < SLOTS; ++e)
@@ -399,83 +425,75 @@ __device__ __forceinline__ void gather_tile(const uint32_t (&dw)[Stream<VEC>::SL
         for (int hh = 0; hh < EPD; ++hh) {
             const uint32_t raw = elem_of<VEC>(dw[e], hh);
             const bool ok = FAST || ((valid[e] >> hh) & 1u);
-            const bool keep = ok && key_of<VEC>(raw) >= thr_lo;
-            m[e][hh] = __ballot(keep);
+            keep[e][hh] = ok && key_of<VEC>(raw) >= thr_lo;
+            m[e][hh] = __ballot(keep[e][hh]);
             wc += __popcll(m[e][hh]);
-            const double xd = (ok && !keep) ? static_cast<double>(value_of<VEC>(raw)) : 0.0;
+            const double xd = (ok && !keep[e][hh]) ? static_cast<double>(value_of<VEC>(raw)) : 0.0;
             acc = fma(xd, xd, acc);
         }
     if (lane == 0) wcnt[w] = wc;
-    if (wc != 0) {  // pack this wave's kept pairs, rank = position inside the wave's part of the tile
-        uint32_t slot_rank = 0;
+    __syncthreads();
+    uint32_t before_v = 0, tot_v = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        const uint32_t t = wcnt[i];
+        before_v += (i < w) ? t : 0u;
+        tot_v += t;
+    }
+    // wave-uniform values, moved to scalar registers so that the branches below are scalar
+    const uint32_t before = __builtin_amdgcn_readfirstlane(before_v);
+    const uint32_t tot = __builtin_amdgcn_readfirstlane(tot_v);
+    if (tot == 0) return;  // uniform over the workgroup
+    if (running + tot - flushed > STAGE_CAP) {  // uniform: make room
+        flush_stage<VEC>(stage, flushed, running, cnt, thr_hi, h2, Li, Lv);
+        __syncthreads();
+        flushed = running;
+    }
+    const bool direct = tot > STAGE_CAP;  // uniform: this tile alone does not fit in the stage
+    uint32_t slot_base = running + before;  // list slot of the wave's first kept element of this tile
+    const uint32_t i_lane = static_cast<uint32_t>(St::first_elem(t0, 0));
+    if (!direct) {
+        uint2 *dst = stage - flushed;
 #pragma unroll
         for (int e = 0; e < SLOTS; ++e) {
             uint64_t any = 0;
 #pragma unroll
             for (int hh = 0; hh < EPD; ++hh) any |= m[e][hh];
             if (any == 0) continue;  // wave-uniform
-            uint32_t r = slot_rank;
+            uint32_t pos = slot_base;
 #pragma unroll
-            for (int hh = 0; hh < EPD; ++hh) r += lanes_below(m[e][hh]);
-            const uint32_t i0 = static_cast<uint32_t>(St::first_elem(t0, e));
+            for (int hh = 0; hh < EPD; ++hh) pos = lanes_below_plus(m[e][hh], pos);
 #pragma unroll
             for (int hh = 0; hh < EPD; ++hh) {
-                if ((m[e][hh] >> lane) & 1u) {
-                    if (r < STAGE) stage[r] = make_uint2(i0 + hh, elem_of<VEC>(dw[e], hh));
-                    ++r;
-                }
-                slot_rank += __popcll(m[e][hh]);
+                if (keep[e][hh]) dst[pos] = make_uint2(i_lane + e * 64 * EPD + hh, elem_of<VEC>(dw[e], hh));
+                pos += keep[e][hh] ? 1u : 0u;
+                slot_base += __popcll(m[e][hh]);
             }
         }
-    }
-    __syncthreads();
-    uint32_t before = 0, tot = 0;
-#pragma unroll
-    for (int i = 0; i < NW; ++i) {
-        const uint32_t t = wcnt[i];
-        before += (i < w) ? t : 0u;
-        tot += t;
-    }
-    const uint32_t base = running + before;
-    const uint32_t staged = wc < STAGE ? wc : STAGE;
-    for (uint32_t i = lane; i < staged; i += 64) {
-        const uint2 pr = stage[i];
-        const uint32_t pos = base + i;
-        if (pos < cnt) {
-            Li[pos] = static_cast<int32_t>(pr.x);
-            Lv[pos] = static_cast<R>(pr.y);
-        }
-        const uint32_t key = key_of<VEC>(pr.y);
-        if (key < thr_hi) atomicAdd(&h2[(key >> SH2) & (NB2 - 1)], 1u);
-    }
-    if (wc > STAGE) {  // wave-uniform, dense inputs only
-        uint32_t slot_rank = 0;
+    } else {
 #pragma unroll
         for (int e = 0; e < SLOTS; ++e) {
-            uint32_t r = slot_rank;
+            uint32_t pos = slot_base;
 #pragma unroll
-            for (int hh = 0; hh < EPD; ++hh) r += lanes_below(m[e][hh]);
-            const uint32_t i0 = static_cast<uint32_t>(St::first_elem(t0, e));
+            for (int hh = 0; hh < EPD; ++hh) pos = lanes_below_plus(m[e][hh], pos);
 #pragma unroll
             for (int hh = 0; hh < EPD; ++hh) {
-                if ((m[e][hh] >> lane) & 1u) {
-                    if (r >= STAGE) {
-                        const uint32_t raw = elem_of<VEC>(dw[e], hh);
-                        const uint32_t key = key_of<VEC>(raw);
-                        const uint32_t pos = base + r;
-                        if (pos < cnt) {
-                            Li[pos] = static_cast<int32_t>(i0 + hh);
-                            Lv[pos] = static_cast<R>(raw);
-                        }
-                        if (key < thr_hi) atomicAdd(&h2[(key >> SH2) & (NB2 - 1)], 1u);
+                if (keep[e][hh]) {
+                    const uint32_t raw = elem_of<VEC>(dw[e], hh);
+                    if (pos < cnt) {
+                        Li[pos] = static_cast<int32_t>(i_lane + e * 64 * EPD + hh);
+                        Lv[pos] = static_cast<R>(raw);
                     }
-                    ++r;
+                    const uint32_t key = key_of<VEC>(raw);
+                    if (key < thr_hi) atomicAdd(&h2[(key >> SH2) & (NB2 - 1)], 1u);
+                    ++pos;
                 }
-                slot_rank += __popcll(m[e][hh]);
+                slot_base += __popcll(m[e][hh]);
             }
         }
     }
     running += tot;
+    if (direct) flushed = running;  // nothing of this tile is staged
 }
 
 template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
@@ -483,7 +501,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     using St = Stream<VEC>;
     __shared__ uint32_t h[NB1];  // top-digit histogram during the prologue, then the second-digit one
     __shared__ uint32_t wcnt[2][NW];
-    __shared__ uint2 stage_all[NW][STAGE];
+    __shared__ uint2 stage[STAGE_CAP];
     __shared__ uint32_t sm[NW];
     __shared__ double smd[NW];
     __shared__ uint32_t s_pick[2];
@@ -494,7 +512,6 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     const int c = g - sg.chunk_begin;
     const int64_t beg = static_cast<int64_t>(c) * a.E;
     const int64_t end = (beg + a.E < sg.n) ? beg + a.E : sg.n;
-    uint2 *stage = stage_all[threadIdx.x >> 6];
 
     // Prologue, the same in every block of the segment: bucket of the top digit, then this
     // chunk's slot range in the list = scan of the earlier chunks' counts of digits >= B1.
@@ -524,17 +541,18 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     __syncthreads();
 
     double acc = 0.0;
-    uint32_t running = 0;
+    uint32_t running = 0, flushed = 0;
     int buf = 0;
     uint32_t cur[St::SLOTS], nxt[St::SLOTS], valid[St::SLOTS];
     int64_t t0 = beg;
-    if (sg.aligned4 && t0 + TILE <= end) {
+    if (sg.aligned4 && t0 + TILE <= end) {  // full tiles, the next one in flight while this one is classified
         St::load_fast(sg.x, t0, cur);
         for (;;) {
             const bool more = t0 + 2 * static_cast<int64_t>(TILE) <= end;
             if (more) St::load_fast(sg.x, t0 + TILE, nxt);
             __builtin_amdgcn_sched_barrier(0);
-            gather_tile<VEC, true>(cur, valid, t0, thr_lo, thr_hi, h2, wcnt[buf], stage, running, cnt, Li, Lv, acc);
+            gather_tile<VEC, true>(cur, valid, t0, thr_lo, thr_hi, h2, wcnt[buf], stage, running, flushed, cnt, Li,
+                                   Lv, acc);
             t0 += TILE;
             buf ^= 1;
             if (!more) break;
@@ -544,8 +562,11 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     }
     for (; t0 < end; t0 += TILE, buf ^= 1) {
         St::load_slow(sg.x, t0, end, cur, valid);
-        gather_tile<VEC, false>(cur, valid, t0, thr_lo, thr_hi, h2, wcnt[buf], stage, running, cnt, Li, Lv, acc);
+        gather_tile<VEC, false>(cur, valid, t0, thr_lo, thr_hi, h2, wcnt[buf], stage, running, flushed, cnt, Li, Lv,
+                                acc);
     }
+    __syncthreads();
+    flush_stage<VEC>(stage, flushed, running, cnt, thr_hi, h2, Li, Lv);
 
     const double bsum = block_sum_f64(acc, smd);
     if (threadIdx.x == 0) a.chunk_err[g] = bsum;
