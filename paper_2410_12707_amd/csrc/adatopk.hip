@@ -8,30 +8,32 @@
 // Method.  key(x) = bits(x) with the sign cleared (bf16 is widened to the fp32 pattern, so
 // both types share one 31-bit key).  The exact k-th largest key T is found by a 3-level
 // MSD radix select with digits of 11 / 10 / 10 bits:
-//   k_init    zero the per-segment state and the three global histograms
-//   k_hist1   one read of the input: per-chunk LDS histogram of the top digit, added into the
-//             segment's global histogram G1; every chunk also stores the suffix sums of its
-//             own histogram (one row per chunk)
-//   k_gather  prologue (every block, redundantly): G1 -> digit bucket B1 holding the k-th key;
-//             the chunk's slot range in the candidate list L = sum over the earlier chunks of
-//             their stored count of digits >= B1.  Then the second read of the input: every
-//             element whose top digit is >= B1 goes, in index order, into L (index, value);
-//             members of bucket B1 are histogrammed on the second digit (G2); squares of the
-//             elements below the bucket are summed in fp64 per chunk
+//   k_hist1   one read of the input: per-chunk LDS histogram of the top digit; every chunk stores
+//             the suffix sums of its histogram (one row per chunk, plus every 32nd entry of it
+//             once more, contiguously).  No global atomics, nothing to zero beforehand
+//   k_gather  prologue (every block, redundantly): the column sums of the chunk rows are the
+//             global suffix sums; two steps (64 coarse columns, then the 32 fine columns of the
+//             interval found) give the digit bucket B1 that holds the k-th key, and the same fine
+//             sums restricted to the earlier chunks give this chunk's offset in the candidate
+//             list L.  Then the second read of the input: every element whose top digit is >= B1
+//             goes, in index order, into L (index, value), staged in LDS and written out with
+//             full-width stores; members of bucket B1 are histogrammed on the second digit (G2);
+//             squares of the elements below the bucket are summed in fp64 per chunk
 //   k_hist3   over L only (about k + the bucket population).  Prologue: G2 -> second digit B2.
 //             Histogram of the third digit of the entries matching (B1,B2) into G3, one row of
 //             suffix sums per list block
 //   k_emit    over L.  Prologue: G3 -> threshold key T and tie quota q; output offsets of the
 //             list block from the rows of the earlier blocks.  Stable compaction into idx_out /
-//             val_out (key > T, plus the first q keys equal to T); squares of dropped entries;
-//             the block that finishes last adds all error partials in a fixed order
+//             val_out (key > T, plus the first q keys equal to T).  The first list block adds up
+//             the error norm from partials stored by the earlier kernels, in a fixed order
 // Cross-block order comes only from counts that an EARLIER kernel stored and that every block
 // of the next kernel scans for itself: no block waits for another block (no launch can hang),
 // no block needs a release fence (on this chip an agent-scope fence writes back the L2 of its
 // XCD, about 1.5 us per workgroup, serialised), and every result, the fp64 error sum included,
 // is the same from run to run.
 //
-// Decompress: k_fill (16-byte zero stores) then k_scatter.
+// Decompress: k_fill (16-byte zero stores) then k_scatter; for ascending indices k_merge does
+// both in one kernel, every workgroup filling its own span and writing the entries that fall in it.
 #include <hip/hip_runtime.h>
 
 #include <stdint.h>
@@ -61,6 +63,8 @@ constexpr int BITS1 = 11, BITS2 = 10, BITS3 = 10;
 constexpr int NB1 = 1 << BITS1, NB2 = 1 << BITS2, NB3 = 1 << BITS3;
 constexpr int SH1 = BITS2 + BITS3;  // key >> SH1 = first digit
 constexpr int SH2 = BITS3;
+constexpr int NC1 = 64;             // coarse boundaries of the top digit: every (NB1 / NC1)-th suffix sum
+constexpr int FINE1 = NB1 / NC1;    // fine bins per coarse interval
 constexpr int MAXSEG = 32;          // segments per launch (the table travels as kernel arguments)
 constexpr int CTARGET = ADATOPK_CTARGET;  // chunks aimed at per launch
 constexpr int LB_ELEMS = 16384;     // input elements per list block when sizing the list grid
@@ -71,8 +75,9 @@ static_assert(HREP == 1 || HREP == 2 || HREP == 4, "histogram copies");
 static_assert(NB1 % BLOCK == 0 && NB2 % BLOCK == 0 && NB3 % BLOCK == 0, "bins split evenly over threads");
 static_assert(BITS1 + BITS2 + BITS3 == 31, "digits cover the 31-bit key");
 static_assert(BLOCK >= 256, "k_emit scans the list blocks of a segment with one thread each");
+static_assert(NC1 == 64 && FINE1 == 32 && BLOCK % 64 == 0, "the two-step bucket search works on one wavefront's ballot");
 
-struct SegState {  // one per segment, zeroed by k_init; 64 bytes
+struct SegState {  // one per segment, zeroed by the segment's first k_hist1 block; 64 bytes
     uint32_t unused0;
     uint32_t B1, c_gt1, m;  // bucket of level 1, #keys above it, length of the candidate list
     uint32_t B2, c_gt2;     // bucket of level 2, #keys above (B1,B2)
@@ -97,7 +102,8 @@ struct Launch {
     int32_t S;
     int32_t E;  // elements per chunk (multiple of the tile)
     SegState *state;
-    uint32_t *G1, *G2, *G3;                    // [MAXSEG][NBx] global histograms
+    uint32_t *G2, *G3;                         // [MAXSEG][NBx] global histograms of the 2nd / 3rd digit
+    uint32_t *coarse1;                         // [chunks][NC1] every FINE1-th entry of the chunk's rows1 row
     uint32_t *rows1;                           // [chunks][NB1] suffix sums of the chunk histograms
     double *chunk_err;                         // [chunks] sum of squares below the bucket
     uint32_t *rows3;                           // [list blocks][NB3] suffix sums
@@ -293,16 +299,6 @@ __device__ __forceinline__ void pick_from_global(const uint32_t *G, uint32_t kre
     __syncthreads();
 }
 
-// ------------------------------------------------------------------ k_init
-__global__ __launch_bounds__(BLOCK) void k_init(Launch a) {
-    const int s = blockIdx.x;
-    uint32_t *st = reinterpret_cast<uint32_t *>(&a.state[s]);
-    if (threadIdx.x < sizeof(SegState) / 4) st[threadIdx.x] = 0;
-    for (int b = threadIdx.x; b < NB1; b += BLOCK) a.G1[s * NB1 + b] = 0;
-    for (int b = threadIdx.x; b < NB2; b += BLOCK) a.G2[s * NB2 + b] = 0;
-    for (int b = threadIdx.x; b < NB3; b += BLOCK) a.G3[s * NB3 + b] = 0;
-}
-
 // ------------------------------------------------------------------ k_hist1
 // LDS histogram of the top digit with HREP interleaved copies: lane l adds into copy l % HREP of
 // its bin, stored at word bin * HREP + copy, so lanes that share a hot bin spread over banks.
@@ -370,11 +366,18 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist1(Launch a) {
         for (int j = 0; j < NB1 / BLOCK; ++j) h[threadIdx.x + j * BLOCK] = folded[j];
         __syncthreads();
     }
-    flush_bins<NB1>(h, a.G1 + s * NB1);
-    __syncthreads();
+    // The chunk's row of suffix sums, and every FINE1-th entry of it once more, contiguously: the
+    // next kernel finds the bucket of the k-th key from the column sums of these rows alone.
     block_suffix_inplace<NB1>(h, sm);
     uint32_t *row = a.rows1 + static_cast<size_t>(g) * NB1;
     for (int b = threadIdx.x; b < NB1; b += BLOCK) row[b] = h[b];
+    if (threadIdx.x < NC1) a.coarse1[static_cast<size_t>(g) * NC1 + threadIdx.x] = h[threadIdx.x * FINE1];
+    if (c == 0) {  // first chunk of the segment: clear what the later kernels of this call accumulate into
+        uint32_t *st = reinterpret_cast<uint32_t *>(&a.state[s]);
+        if (threadIdx.x < sizeof(SegState) / 4) st[threadIdx.x] = 0;
+        for (int b = threadIdx.x; b < NB2; b += BLOCK) a.G2[s * NB2 + b] = 0;
+        for (int b = threadIdx.x; b < NB3; b += BLOCK) a.G3[s * NB3 + b] = 0;
+    }
 }
 
 // ------------------------------------------------------------------ k_gather
@@ -502,9 +505,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     __shared__ uint32_t h[NB1];  // top-digit histogram during the prologue, then the second-digit one
     __shared__ uint32_t wcnt[2][NW];
     __shared__ uint2 stage[STAGE_CAP];
-    __shared__ uint32_t sm[NW];
     __shared__ double smd[NW];
-    __shared__ uint32_t s_pick[2];
 
     const int g = blockIdx.x;
     const int s = find_segment_by(a, g, true);
@@ -513,22 +514,89 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     const int64_t beg = static_cast<int64_t>(c) * a.E;
     const int64_t end = (beg + a.E < sg.n) ? beg + a.E : sg.n;
 
-    // Prologue, the same in every block of the segment: bucket of the top digit, then this
-    // chunk's slot range in the list = scan of the earlier chunks' counts of digits >= B1.
-    uint32_t B1, c_gt1;
-    pick_from_global<NB1>(a.G1 + s * NB1, static_cast<uint32_t>(sg.k), h, sm, s_pick, B1, c_gt1);
-    uint32_t part = 0, cnt = 0;
-    if (B1 < NB1) {
-        const uint32_t *col = a.rows1 + static_cast<size_t>(sg.chunk_begin) * NB1 + B1;
-        for (int cc = threadIdx.x; cc < c; cc += BLOCK) part += col[static_cast<size_t>(cc) * NB1];
-        cnt = col[static_cast<size_t>(c) * NB1];
+    // Prologue, the same in every block of the segment.  The rows of k_hist1 hold suffix sums, so
+    // the column sums over the segment's chunks are the global suffix sums S[d] = #{top digit >= d},
+    // non-increasing in d; the bucket is B1 = max d with S[d] >= k.  Step A sums the NC1 coarse
+    // columns and finds the coarse interval, step B sums its FINE1 columns (and, aside, the part
+    // of those sums that belongs to the earlier chunks: this chunk's offset in the list).
+    uint32_t B1 = NB1, c_gt1 = 0, off = 0, cnt = 0, m_total = 0;
+    {
+        uint32_t *redA = h, *redB = h + NC1, *redBelow = h + NC1 + FINE1;
+        if (threadIdx.x < NC1 + 2 * FINE1) h[threadIdx.x] = 0;
+        __syncthreads();
+        const uint32_t kk = static_cast<uint32_t>(sg.k);
+        const int lane = threadIdx.x & 63;
+        {  // step A: 16-byte loads, 8 in flight per thread
+            constexpr int Q = NC1 / 4, G = BLOCK / Q;
+            const int q = threadIdx.x % Q;
+            const uint4 *co = reinterpret_cast<const uint4 *>(a.coarse1 + static_cast<size_t>(sg.chunk_begin) * NC1) + q;
+            uint4 sum = make_uint4(0, 0, 0, 0);
+            for (int cc0 = threadIdx.x / Q; cc0 < sg.nchunks; cc0 += G * 8) {
+                uint4 v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int cc = cc0 + u * G;
+                    v[u] = (cc < sg.nchunks) ? co[static_cast<size_t>(cc) * Q] : make_uint4(0, 0, 0, 0);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    sum.x += v[u].x; sum.y += v[u].y; sum.z += v[u].z; sum.w += v[u].w;
+                }
+            }
+            atomicAdd(&redA[4 * q + 0], sum.x);
+            atomicAdd(&redA[4 * q + 1], sum.y);
+            atomicAdd(&redA[4 * q + 2], sum.z);
+            atomicAdd(&redA[4 * q + 3], sum.w);
+        }
+        __syncthreads();
+        const uint64_t okA = __ballot(redA[lane] >= kk);  // bit j: S[j * FINE1] >= k; a prefix of ones
+        if (kk != 0 && okA != 0) {                        // uniform
+            const int J = 63 - __builtin_clzll(okA);
+            {  // step B: the FINE1 columns of coarse interval J, again 8 16-byte loads in flight
+                constexpr int Q = FINE1 / 4, G = BLOCK / Q;
+                const int q = threadIdx.x % Q;
+                const uint4 *col = reinterpret_cast<const uint4 *>(a.rows1 + static_cast<size_t>(sg.chunk_begin) * NB1 +
+                                                                   J * FINE1) + q;
+                uint4 all = make_uint4(0, 0, 0, 0), below = make_uint4(0, 0, 0, 0);
+                for (int cc0 = threadIdx.x / Q; cc0 < sg.nchunks; cc0 += G * 8) {
+                    uint4 v[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int cc = cc0 + u * G;
+                        v[u] = (cc < sg.nchunks) ? col[static_cast<size_t>(cc) * (NB1 / 4)] : make_uint4(0, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        all.x += v[u].x; all.y += v[u].y; all.z += v[u].z; all.w += v[u].w;
+                        if (cc0 + u * G < c) {
+                            below.x += v[u].x; below.y += v[u].y; below.z += v[u].z; below.w += v[u].w;
+                        }
+                    }
+                }
+                atomicAdd(&redB[4 * q + 0], all.x);
+                atomicAdd(&redB[4 * q + 1], all.y);
+                atomicAdd(&redB[4 * q + 2], all.z);
+                atomicAdd(&redB[4 * q + 3], all.w);
+                atomicAdd(&redBelow[4 * q + 0], below.x);
+                atomicAdd(&redBelow[4 * q + 1], below.y);
+                atomicAdd(&redBelow[4 * q + 2], below.z);
+                atomicAdd(&redBelow[4 * q + 3], below.w);
+            }
+            __syncthreads();
+            const uint64_t okB = __ballot(lane < FINE1 && redB[lane & (FINE1 - 1)] >= kk);
+            const int I = 63 - __builtin_clzll(okB | 1ull);  // bit 0 is set anyway: S[J * FINE1] >= k
+            B1 = J * FINE1 + I;
+            c_gt1 = (I + 1 < FINE1) ? redB[I + 1] : ((J + 1 < NC1) ? redA[J + 1] : 0u);
+            m_total = redB[I];
+            off = redBelow[I];
+            cnt = a.rows1[static_cast<size_t>(g) * NB1 + B1];
+        }
+        __syncthreads();
     }
-    uint32_t off;
-    block_incl_scan(part, sm, &off);
     if (c == sg.nchunks - 1 && threadIdx.x == 0) {
         a.state[s].B1 = B1;
         a.state[s].c_gt1 = c_gt1;
-        a.state[s].m = off + cnt;
+        a.state[s].m = m_total;
     }
     const int64_t lo = sg.l_base + off;
     int32_t *Li = a.L_idx + lo;
@@ -595,6 +663,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
     const int s = find_segment_by(a, g, false);
     const SegDesc &sg = a.seg[s];
     const int lb = g - sg.lb_begin;
+    if (sg.nchunks == 0) return;  // empty tensor: nothing was listed, and nobody cleared its state
     const uint32_t m = a.state[s].m;
     const uint32_t B1 = a.state[s].B1, c_gt1 = a.state[s].c_gt1;
 
@@ -651,6 +720,10 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     const int s = find_segment_by(a, g, false);
     const SegDesc &sg = a.seg[s];
     const int lb = g - sg.lb_begin;
+    if (sg.nchunks == 0) {  // empty tensor: no output, zero error
+        if (lb == 0 && threadIdx.x == 0 && a.err_out != nullptr) a.err_out[s] = 0.0f;
+        return;
+    }
     const uint32_t m = a.state[s].m;
     const uint32_t P = (a.state[s].B1 << BITS2) | a.state[s].B2;
     const uint32_t c_gt2 = a.state[s].c_gt2;
@@ -897,7 +970,7 @@ int32_t list_blocks(int64_t n, int32_t S) {
 }
 
 struct Carve {
-    size_t state, G1, G2, G3, rows1, chunk_err, rows3, ldef, lerr, L_idx, L_val, total;
+    size_t state, G2, G3, rows1, coarse1, chunk_err, rows3, ldef, lerr, L_idx, L_val, total;
 };
 
 // Workspace layout for up to max_chunks chunks, max_lb list blocks and n_total list slots.
@@ -910,10 +983,10 @@ Carve carve(int64_t max_chunks, int64_t max_lb, int64_t n_total, adatopk_dtype d
         return at;
     };
     c.state = take(sizeof(SegState) * MAXSEG);
-    c.G1 = take(sizeof(uint32_t) * NB1 * MAXSEG);
     c.G2 = take(sizeof(uint32_t) * NB2 * MAXSEG);
     c.G3 = take(sizeof(uint32_t) * NB3 * MAXSEG);
     c.rows1 = take(sizeof(uint32_t) * NB1 * max_chunks);
+    c.coarse1 = take(sizeof(uint32_t) * NC1 * max_chunks);
     c.chunk_err = take(sizeof(double) * max_chunks);
     c.rows3 = take(sizeof(uint32_t) * NB3 * max_lb);
     c.ldef = take(sizeof(uint32_t) * max_lb);
@@ -932,9 +1005,9 @@ void bounds_for(int64_t n_total, int32_t S, adatopk_dtype dt, int64_t *max_chunk
 }
 
 // ---- stage timing (measurement hook): a chain of events per call kind, one interval per kernel
-enum Stage { ST_INIT, ST_HIST1, ST_GATHER, ST_HIST3, ST_EMIT, ST_FILL, ST_SCATTER, ST_MERGE, NSTAGE };
-const char *const kStageNames[NSTAGE] = {"k_init", "k_hist1", "k_gather", "k_hist3",
-                                         "k_emit", "k_fill",  "k_scatter", "k_merge"};
+enum Stage { ST_HIST1, ST_GATHER, ST_HIST3, ST_EMIT, ST_FILL, ST_SCATTER, ST_MERGE, NSTAGE };
+const char *const kStageNames[NSTAGE] = {"k_hist1", "k_gather", "k_hist3", "k_emit",
+                                         "k_fill",  "k_scatter", "k_merge"};
 constexpr int CHAIN_MAX = 8;
 struct Chain {
     hipEvent_t ev[CHAIN_MAX];
@@ -959,8 +1032,6 @@ inline void chain_mark(Chain &c, int stage, hipStream_t st) {
 
 template <int VEC> adatopk_status launch_batch(const Launch &a, int total_chunks, int total_lb, hipStream_t st) {
     chain_begin(g_chain_c, st);
-    hipLaunchKernelGGL(k_init, dim3(a.S), dim3(BLOCK), 0, st, a);
-    chain_mark(g_chain_c, ST_INIT, st);
     if (total_chunks > 0) {
         hipLaunchKernelGGL(k_hist1<VEC>, dim3(total_chunks), dim3(BLOCK), 0, st, a);
         chain_mark(g_chain_c, ST_HIST1, st);
@@ -1009,10 +1080,10 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
         a.S = (S - s0 < MAXSEG) ? S - s0 : MAXSEG;
         a.E = static_cast<int32_t>(E);
         a.state = reinterpret_cast<SegState *>(ws + cv.state);
-        a.G1 = reinterpret_cast<uint32_t *>(ws + cv.G1);
         a.G2 = reinterpret_cast<uint32_t *>(ws + cv.G2);
         a.G3 = reinterpret_cast<uint32_t *>(ws + cv.G3);
         a.rows1 = reinterpret_cast<uint32_t *>(ws + cv.rows1);
+        a.coarse1 = reinterpret_cast<uint32_t *>(ws + cv.coarse1);
         a.chunk_err = reinterpret_cast<double *>(ws + cv.chunk_err);
         a.rows3 = reinterpret_cast<uint32_t *>(ws + cv.rows3);
         a.ldef = reinterpret_cast<uint32_t *>(ws + cv.ldef);
