@@ -25,8 +25,13 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; each scaled by the
 # same counter's reading for the library's plain copy kernel of known size), workload below.
-# Filled from profiles/; None where no counter run has been made for that kernel.
-TRAFFIC_BYTES = {}
+# From profiles/hbm_traffic_cfg2_k1pct.md (fetched + written bytes per launch); None where no
+# counter run has been made for that kernel.
+TRAFFIC_BYTES = {
+    "k_hist1": 100719207 + 4333632,
+    "k_gather": 102384613 + 4175431,
+    "k_merge": 9361632 + 111555045,
+}
 
 
 def main() -> int:
@@ -35,6 +40,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run the library's plain copy kernel on the workload-sized buffer (the known-size "
+                         "kernel that hardware-counter readings are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -79,6 +87,11 @@ def main() -> int:
     sec_per_step = (t1 - t0) / args.steps
     dense_bytes = n * 4
     value = dense_bytes / sec_per_step / 1e9
+
+    if args.calibrate_copy:
+        for i in range(max(args.steps, 3)):
+            B.measure_copy(y, xs[i % NBUF])  # reads 4n bytes, writes 4n bytes
+        torch.cuda.synchronize()
 
     # same loop on one buffer only (input may be served by the last-level cache): reported aside
     for i in range(args.warmup):

@@ -20,9 +20,10 @@
 extern "C" {
 #endif
 
-/* on != 0: from now on every compress / decompress call records a HIP event on its
- * stream before its first kernel and after each kernel (events are created on the
- * first enable).  on == 0: stop recording.  Returns ADATOPK_OK or ADATOPK_ERUNTIME. */
+/* on != 0: from now on every kernel of a compress / decompress call is launched with a
+ * start and a stop HIP event that carry the timestamps of the dispatch itself (events are
+ * created on the first enable).  on == 0: plain launches.  Returns ADATOPK_OK or
+ * ADATOPK_ERUNTIME. */
 adatopk_status adatopk_measure_enable(int32_t on);
 
 /* Number of kernel stages a timed call can report, and their names (static strings):
@@ -30,8 +31,8 @@ adatopk_status adatopk_measure_enable(int32_t on);
 int32_t adatopk_measure_stage_count(void);
 const char *adatopk_measure_stage_name(int32_t stage);
 
-/* Waits for the events of the most recent timed compress and of the most recent timed
- * decompress and stores the duration of every stage in milliseconds into
+/* Waits for the stop events of the kernels launched since the last read and stores the
+ * duration of the most recent launch of every stage in milliseconds into
  * ms_out[adatopk_measure_stage_count()] (host memory); stages that did not run since
  * the last read are reported as -1.  Returns ADATOPK_OK or ADATOPK_ERUNTIME. */
 adatopk_status adatopk_measure_read(float *ms_out);

@@ -35,6 +35,7 @@
 // Decompress: k_fill (16-byte zero stores) then k_scatter; for ascending indices k_merge does
 // both in one kernel, every workgroup filling its own span and writing the entries that fall in it.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <stdint.h>
 
@@ -1004,44 +1005,33 @@ void bounds_for(int64_t n_total, int32_t S, adatopk_dtype dt, int64_t *max_chunk
     *max_lb = static_cast<int64_t>(batch) * list_blocks_cap(S);
 }
 
-// ---- stage timing (measurement hook): a chain of events per call kind, one interval per kernel
+// ---- stage timing (measurement hook): in measuring mode every kernel is launched with its own
+// start / stop events, whose timestamps are those of the dispatch itself (as a profiler sees it)
 enum Stage { ST_HIST1, ST_GATHER, ST_HIST3, ST_EMIT, ST_FILL, ST_SCATTER, ST_MERGE, NSTAGE };
 const char *const kStageNames[NSTAGE] = {"k_hist1", "k_gather", "k_hist3", "k_emit",
                                          "k_fill",  "k_scatter", "k_merge"};
-constexpr int CHAIN_MAX = 8;
-struct Chain {
-    hipEvent_t ev[CHAIN_MAX];
-    int stage[CHAIN_MAX];  // stage[j] ran between ev[j] and ev[j + 1]
-    int n;                 // events recorded by the latest timed call
-};
 bool g_measure = false;
 bool g_events_made = false;
-Chain g_chain_c, g_chain_d;
+hipEvent_t g_start[NSTAGE], g_stop[NSTAGE];
+bool g_ran[NSTAGE];  // launched, with events, since the last read
 
-inline void chain_begin(Chain &c, hipStream_t st) {
-    c.n = 0;
-    if (g_measure && hipEventRecord(c.ev[0], st) == hipSuccess) c.n = 1;
-}
-inline void chain_mark(Chain &c, int stage, hipStream_t st) {
-    if (!g_measure || c.n == 0 || c.n >= CHAIN_MAX) return;
-    if (hipEventRecord(c.ev[c.n], st) == hipSuccess) {
-        c.stage[c.n - 1] = stage;
-        ++c.n;
+template <typename K, typename... Args>
+inline void launch(int stage, K kernel, dim3 grid, hipStream_t st, Args... args) {
+    if (g_measure) {
+        hipExtLaunchKernelGGL(kernel, grid, dim3(BLOCK), 0, st, g_start[stage], g_stop[stage], 0, args...);
+        g_ran[stage] = true;
+    } else {
+        hipLaunchKernelGGL(kernel, grid, dim3(BLOCK), 0, st, args...);
     }
 }
 
 template <int VEC> adatopk_status launch_batch(const Launch &a, int total_chunks, int total_lb, hipStream_t st) {
-    chain_begin(g_chain_c, st);
     if (total_chunks > 0) {
-        hipLaunchKernelGGL(k_hist1<VEC>, dim3(total_chunks), dim3(BLOCK), 0, st, a);
-        chain_mark(g_chain_c, ST_HIST1, st);
-        hipLaunchKernelGGL(k_gather<VEC>, dim3(total_chunks), dim3(BLOCK), 0, st, a);
-        chain_mark(g_chain_c, ST_GATHER, st);
+        launch(ST_HIST1, k_hist1<VEC>, dim3(total_chunks), st, a);
+        launch(ST_GATHER, k_gather<VEC>, dim3(total_chunks), st, a);
     }
-    hipLaunchKernelGGL(k_hist3<VEC>, dim3(total_lb), dim3(BLOCK), 0, st, a);
-    chain_mark(g_chain_c, ST_HIST3, st);
-    hipLaunchKernelGGL(k_emit<VEC>, dim3(total_lb), dim3(BLOCK), 0, st, a);
-    chain_mark(g_chain_c, ST_EMIT, st);
+    launch(ST_HIST3, k_hist3<VEC>, dim3(total_lb), st, a);
+    launch(ST_EMIT, k_emit<VEC>, dim3(total_lb), st, a);
     return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
 }
 
@@ -1127,13 +1117,12 @@ int grid_for(size_t work_items, int per_thread) {
     return static_cast<int>(b);
 }
 
-adatopk_status fill_impl(void *dst, size_t bytes, hipStream_t st) {
+adatopk_status fill_impl(void *dst, size_t bytes, hipStream_t st) {  // the k_fill launch of decompress
     if (bytes == 0) return ADATOPK_OK;
     size_t head = (16 - reinterpret_cast<uintptr_t>(dst) % 16) % 16;
     if (head > bytes) head = bytes;
     const size_t body16 = (bytes - head) / 16;
-    hipLaunchKernelGGL(k_fill, dim3(grid_for(body16, 4)), dim3(BLOCK), 0, st, static_cast<unsigned char *>(dst),
-                       bytes, head, body16);
+    launch(ST_FILL, k_fill, dim3(grid_for(body16, 4)), st, static_cast<unsigned char *>(dst), bytes, head, body16);
     return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
 }
 
@@ -1175,20 +1164,17 @@ adatopk_status adatopk_decompress(const int32_t *idx, const void *val, int64_t k
         return ADATOPK_EINVAL;
     if (n == 0) return ADATOPK_OK;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    chain_begin(g_chain_d, st);
     const adatopk_status rc = fill_impl(dense_out, static_cast<size_t>(n) * es, st);
     if (rc != ADATOPK_OK) return rc;
-    chain_mark(g_chain_d, ST_FILL, st);
     if (k > 0) {
         const int grid = static_cast<int>((k + BLOCK - 1) / BLOCK);
         if (dt == ADATOPK_F32)
-            hipLaunchKernelGGL(k_scatter<uint32_t>, dim3(grid), dim3(BLOCK), 0, st, idx,
-                               static_cast<const uint32_t *>(val), k, static_cast<uint32_t *>(dense_out), n);
+            launch(ST_SCATTER, k_scatter<uint32_t>, dim3(grid), st, idx, static_cast<const uint32_t *>(val), k,
+                   static_cast<uint32_t *>(dense_out), n);
         else
-            hipLaunchKernelGGL(k_scatter<uint16_t>, dim3(grid), dim3(BLOCK), 0, st, idx,
-                               static_cast<const uint16_t *>(val), k, static_cast<uint16_t *>(dense_out), n);
+            launch(ST_SCATTER, k_scatter<uint16_t>, dim3(grid), st, idx, static_cast<const uint16_t *>(val), k,
+                   static_cast<uint16_t *>(dense_out), n);
     }
-    chain_mark(g_chain_d, ST_SCATTER, st);
     return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
 }
 
@@ -1211,27 +1197,25 @@ adatopk_status adatopk_decompress_sorted(const int32_t *idx, const void *val, in
     const unsigned grid = static_cast<unsigned>(body / span + 1);  // the last workgroup takes the remainder
     int rounds = 0;
     for (uint64_t w = static_cast<uint64_t>(k); w > 0; ++rounds) w = (w + BLOCK / 2 - 1) / (BLOCK / 2) - 1;
-    chain_begin(g_chain_d, st);
     if (dt == ADATOPK_F32)
-        hipLaunchKernelGGL(k_merge<uint32_t>, dim3(grid), dim3(BLOCK), 0, st, idx, static_cast<const uint32_t *>(val),
-                           static_cast<uint32_t>(k), static_cast<unsigned char *>(dense_out), total, head, span, rounds);
+        launch(ST_MERGE, k_merge<uint32_t>, dim3(grid), st, idx, static_cast<const uint32_t *>(val),
+               static_cast<uint32_t>(k), static_cast<unsigned char *>(dense_out), total, head, span, rounds);
     else
-        hipLaunchKernelGGL(k_merge<uint16_t>, dim3(grid), dim3(BLOCK), 0, st, idx, static_cast<const uint16_t *>(val),
-                           static_cast<uint32_t>(k), static_cast<unsigned char *>(dense_out), total, head, span, rounds);
-    chain_mark(g_chain_d, ST_MERGE, st);
+        launch(ST_MERGE, k_merge<uint16_t>, dim3(grid), st, idx, static_cast<const uint16_t *>(val),
+               static_cast<uint32_t>(k), static_cast<unsigned char *>(dense_out), total, head, span, rounds);
     return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
 }
 
 // ---- measurement hooks
 adatopk_status adatopk_measure_enable(int32_t on) {
     if (on && !g_events_made) {
-        for (int i = 0; i < CHAIN_MAX; ++i)
-            if (hipEventCreate(&g_chain_c.ev[i]) != hipSuccess || hipEventCreate(&g_chain_d.ev[i]) != hipSuccess)
+        for (int i = 0; i < NSTAGE; ++i)
+            if (hipEventCreate(&g_start[i]) != hipSuccess || hipEventCreate(&g_stop[i]) != hipSuccess)
                 return ADATOPK_ERUNTIME;
         g_events_made = true;
     }
     g_measure = on != 0;
-    g_chain_c.n = g_chain_d.n = 0;
+    for (int i = 0; i < NSTAGE; ++i) g_ran[i] = false;
     return ADATOPK_OK;
 }
 
@@ -1243,14 +1227,12 @@ const char *adatopk_measure_stage_name(int32_t stage) {
 
 adatopk_status adatopk_measure_read(float *ms_out) {
     if (!ms_out || !g_events_made) return ADATOPK_EINVAL;
-    for (int i = 0; i < NSTAGE; ++i) ms_out[i] = -1.0f;
-    Chain *chains[2] = {&g_chain_c, &g_chain_d};
-    for (Chain *c : chains) {
-        if (c->n > 0 && hipEventSynchronize(c->ev[c->n - 1]) != hipSuccess) return ADATOPK_ERUNTIME;
-        for (int j = 0; j + 1 < c->n; ++j)
-            if (hipEventElapsedTime(&ms_out[c->stage[j]], c->ev[j], c->ev[j + 1]) != hipSuccess)
-                return ADATOPK_ERUNTIME;
-        c->n = 0;
+    for (int i = 0; i < NSTAGE; ++i) {
+        ms_out[i] = -1.0f;
+        if (!g_ran[i]) continue;
+        g_ran[i] = false;
+        if (hipEventSynchronize(g_stop[i]) != hipSuccess) return ADATOPK_ERUNTIME;
+        if (hipEventElapsedTime(&ms_out[i], g_start[i], g_stop[i]) != hipSuccess) return ADATOPK_ERUNTIME;
     }
     return ADATOPK_OK;
 }
