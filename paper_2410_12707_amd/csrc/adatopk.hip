@@ -69,7 +69,10 @@ constexpr int FINE1 = NB1 / NC1;    // fine bins per coarse interval
 constexpr int MAXSEG = 32;          // segments per launch (the table travels as kernel arguments)
 constexpr int CTARGET = ADATOPK_CTARGET;  // chunks aimed at per launch
 constexpr int LB_ELEMS = 16384;     // input elements per list block when sizing the list grid
-constexpr size_t MERGE_SPANS = 2048;      // output spans aimed at by the one-kernel decompress
+#ifndef ADATOPK_MERGE_SPANS
+#define ADATOPK_MERGE_SPANS 1024
+#endif
+constexpr size_t MERGE_SPANS = ADATOPK_MERGE_SPANS;  // output spans aimed at by the one-kernel decompress
 constexpr size_t MERGE_MIN_SPAN = 16384;  // bytes; smaller outputs use fewer workgroups
 static_assert(LU * NW <= 64, "per-tile wave counts must fit one wavefront scan");
 static_assert(HREP == 1 || HREP == 2 || HREP == 4, "histogram copies");
@@ -857,52 +860,46 @@ __global__ __launch_bounds__(BLOCK) void k_scatter(const int32_t *idx, const R *
     if (i >= 0 && i < n) y[i] = val[j];
 }
 
-// Cooperative lower bound by half a workgroup: the first j in [0, k) with idx[j] >= value (k if
-// none), for ascending idx.  The BLOCK / 2 threads of the half probe evenly spaced entries; the
-// number of probes below `value` narrows the range [lo, hi] by BLOCK / 2 per round.  Both halves
-// of the workgroup call this together with the same `rounds` (it contains barriers); cntr is one
-// LDS word owned by the half.  With idx not ascending the result is some position in [0, k]:
-// memory-safe, meaningless.
-__device__ __forceinline__ uint32_t half_block_lower_bound(const int32_t *idx, uint32_t k, int64_t value,
-                                                           int rounds, uint32_t *cntr) {
-    constexpr uint32_t H = BLOCK / 2;
-    const uint32_t t = threadIdx.x % H;
+// Lower bound by one wavefront: the first j in [0, k) with idx[j] >= value (k if none), for
+// ascending idx.  The 64 lanes probe evenly spaced entries; the number of probes below `value`
+// narrows [lo, hi] 64-fold per round (4 rounds for k = 250 000).  Wave-synchronous: no barrier,
+// so the other wavefronts of the workgroup can do something else meanwhile.  With idx not
+// ascending the result is some position in [0, k]: memory-safe, meaningless.
+__device__ __forceinline__ uint32_t wave_lower_bound(const int32_t *idx, uint32_t k, int64_t value) {
+    const uint32_t lane = threadIdx.x & 63;
     uint32_t lo = 0, hi = k;  // invariant: idx[j] < value for j < lo, idx[hi] >= value or hi == k
-    for (int r = 0; r < rounds; ++r) {
+    while (lo < hi) {         // lo, hi are wave-uniform; the width shrinks to below width / 64 every round
         const uint32_t width = hi - lo;
-        const uint32_t step = width ? (width + H - 1) / H : 1u;
-        const uint64_t p = static_cast<uint64_t>(lo) + static_cast<uint64_t>(t) * step;
+        const uint32_t step = (width + 63) / 64;
+        const uint64_t p = static_cast<uint64_t>(lo) + static_cast<uint64_t>(lane) * step;
         const bool below = p < hi && static_cast<int64_t>(idx[p]) < value;
-        if (t == 0) *cntr = 0;
-        __syncthreads();
-        const uint64_t bal = __ballot(below);
-        if ((threadIdx.x & 63) == 0 && bal) atomicAdd(cntr, static_cast<uint32_t>(__popcll(bal)));
-        __syncthreads();
-        const uint32_t c = *cntr;  // probes 0 .. c-1 are below value
-        __syncthreads();
-        if (width) {
-            const uint32_t nprobe = (width + step - 1) / step;
-            const uint32_t old_lo = lo;
-            lo = c ? old_lo + (c - 1) * step + 1 : old_lo;
-            hi = c ? (c < nprobe ? old_lo + c * step : hi) : old_lo;
-        }
+        const uint32_t c = static_cast<uint32_t>(__popcll(__ballot(below)));  // probes 0 .. c-1 are below value
+        const uint32_t nprobe = (width + step - 1) / step;
+        const uint32_t old_lo = lo;
+        lo = c ? old_lo + (c - 1) * step + 1 : old_lo;
+        hi = c ? (c < nprobe ? old_lo + c * step : hi) : old_lo;
     }
     return lo;
 }
 
 // Decompress for ascending indices in one kernel.  The output is cut into byte spans: workgroup b
 // owns bytes [B_b, B_b+1) with B_0 = 0, B_b = head + b * span (16-byte aligned addresses) and
-// B_last = total.  It zero-fills its span with 16-byte stores, finds its entries by two
-// cooperative searches and writes them after a barrier.  Every output byte is written by one
-// workgroup only; an entry whose index lies outside the span that the search assigned it to
-// (possible only when idx is not ascending) is skipped.
+// B_last = total.  Two of its wavefronts first search idx for the entries of the span while the
+// others already zero-fill it with 16-byte stores; after a barrier the entries are written.
+// Every output byte is written by one workgroup only; an entry whose index lies outside the span
+// that the search assigned it to (possible only when idx is not ascending) is skipped.
 template <typename R>
 __global__ __launch_bounds__(BLOCK) void k_merge(const int32_t *idx, const R *val, uint32_t k, unsigned char *y,
-                                                 size_t total, size_t head, size_t span, int rounds) {
-    __shared__ uint32_t cntr[2];
+                                                 size_t total, size_t head, size_t span) {
     __shared__ uint32_t s_range[2];
     const size_t byte_a = blockIdx.x == 0 ? 0 : head + static_cast<size_t>(blockIdx.x) * span;
     const size_t byte_b = blockIdx.x + 1 == gridDim.x ? total : head + static_cast<size_t>(blockIdx.x + 1) * span;
+    const int64_t ea = static_cast<int64_t>(byte_a / sizeof(R)), eb = static_cast<int64_t>(byte_b / sizeof(R));
+    const int w = threadIdx.x >> 6;
+    if (w < 2) {
+        const uint32_t pos = wave_lower_bound(idx, k, w == 0 ? ea : eb);
+        if ((threadIdx.x & 63) == 0) s_range[w] = pos;
+    }
     const size_t va = blockIdx.x == 0 ? (head < byte_b ? head : byte_b) : byte_a;  // aligned start
     const size_t nvec = (byte_b - va) / 16;
     uint4 *body = reinterpret_cast<uint4 *>(y + va);
@@ -910,12 +907,6 @@ __global__ __launch_bounds__(BLOCK) void k_merge(const int32_t *idx, const R *va
     for (size_t i = threadIdx.x; i < nvec; i += BLOCK) body[i] = z;
     for (size_t i = byte_a + threadIdx.x; i < va; i += BLOCK) y[i] = 0;
     for (size_t i = va + nvec * 16 + threadIdx.x; i < byte_b; i += BLOCK) y[i] = 0;
-
-    const int64_t ea = static_cast<int64_t>(byte_a / sizeof(R)), eb = static_cast<int64_t>(byte_b / sizeof(R));
-    const bool upper = threadIdx.x >= BLOCK / 2;
-    const uint32_t pos = half_block_lower_bound(idx, k, upper ? eb : ea, rounds, &cntr[upper ? 1 : 0]);
-    if (threadIdx.x == 0) s_range[0] = pos;
-    if (threadIdx.x == BLOCK / 2) s_range[1] = pos;
     __syncthreads();  // also orders this workgroup's zero stores before its value stores
     R *out = reinterpret_cast<R *>(y);
     const uint32_t jb = s_range[1];
@@ -1195,14 +1186,12 @@ adatopk_status adatopk_decompress_sorted(const int32_t *idx, const void *val, in
     size_t span = (body / MERGE_SPANS + 15) / 16 * 16;
     if (span < MERGE_MIN_SPAN) span = MERGE_MIN_SPAN;
     const unsigned grid = static_cast<unsigned>(body / span + 1);  // the last workgroup takes the remainder
-    int rounds = 0;
-    for (uint64_t w = static_cast<uint64_t>(k); w > 0; ++rounds) w = (w + BLOCK / 2 - 1) / (BLOCK / 2) - 1;
     if (dt == ADATOPK_F32)
         launch(ST_MERGE, k_merge<uint32_t>, dim3(grid), st, idx, static_cast<const uint32_t *>(val),
-               static_cast<uint32_t>(k), static_cast<unsigned char *>(dense_out), total, head, span, rounds);
+               static_cast<uint32_t>(k), static_cast<unsigned char *>(dense_out), total, head, span);
     else
         launch(ST_MERGE, k_merge<uint16_t>, dim3(grid), st, idx, static_cast<const uint16_t *>(val),
-               static_cast<uint32_t>(k), static_cast<unsigned char *>(dense_out), total, head, span, rounds);
+               static_cast<uint32_t>(k), static_cast<unsigned char *>(dense_out), total, head, span);
     return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
 }
 
