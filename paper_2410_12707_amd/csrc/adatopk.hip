@@ -17,9 +17,9 @@
 //             sums restricted to the earlier chunks give this chunk's offset in the candidate
 //             list L.  Then the second read of the input: every element whose top digit is >= B1
 //             goes, in index order, into L (index, value), staged in LDS and written out with
-//             full-width stores; members of bucket B1 are histogrammed on the second digit (G2);
+//             full-width stores; members of bucket B1 are histogrammed on the second digit (a row per chunk);
 //             squares of the elements below the bucket are summed in fp64 per chunk
-//   k_hist3   over L only (about k + the bucket population).  Prologue: G2 -> second digit B2.
+//   k_hist3   over L only (about k + the bucket population).  Prologue: column sums of those rows -> second digit B2.
 //             Histogram of the third digit of the entries matching (B1,B2) into G3, one row of
 //             suffix sums per list block
 //   k_emit    over L.  Prologue: G3 -> threshold key T and tie quota q; output offsets of the
@@ -66,6 +66,7 @@ constexpr int SH1 = BITS2 + BITS3;  // key >> SH1 = first digit
 constexpr int SH2 = BITS3;
 constexpr int NC1 = 64;             // coarse boundaries of the top digit: every (NB1 / NC1)-th suffix sum
 constexpr int FINE1 = NB1 / NC1;    // fine bins per coarse interval
+constexpr int NC2 = 32;             // the same for the second digit
 constexpr int MAXSEG = 32;          // segments per launch (the table travels as kernel arguments)
 constexpr int CTARGET = ADATOPK_CTARGET;  // chunks aimed at per launch
 constexpr int LB_ELEMS = 16384;     // input elements per list block when sizing the list grid
@@ -79,7 +80,7 @@ static_assert(HREP == 1 || HREP == 2 || HREP == 4, "histogram copies");
 static_assert(NB1 % BLOCK == 0 && NB2 % BLOCK == 0 && NB3 % BLOCK == 0, "bins split evenly over threads");
 static_assert(BITS1 + BITS2 + BITS3 == 31, "digits cover the 31-bit key");
 static_assert(BLOCK >= 256, "k_emit scans the list blocks of a segment with one thread each");
-static_assert(NC1 == 64 && FINE1 == 32 && BLOCK % 64 == 0, "the two-step bucket search works on one wavefront's ballot");
+static_assert(BLOCK % 64 == 0, "whole wavefronts");
 
 struct SegState {  // one per segment, zeroed by the segment's first k_hist1 block; 64 bytes
     uint32_t unused0;
@@ -106,7 +107,8 @@ struct Launch {
     int32_t S;
     int32_t E;  // elements per chunk (multiple of the tile)
     SegState *state;
-    uint32_t *G2, *G3;                         // [MAXSEG][NBx] global histograms of the 2nd / 3rd digit
+    uint32_t *G3;                              // [MAXSEG][NB3] global histogram of the 3rd digit
+    uint32_t *rows2, *coarse2;                 // [chunks][NB2], [chunks][NC2]: the same for the 2nd digit of bucket members
     uint32_t *coarse1;                         // [chunks][NC1] every FINE1-th entry of the chunk's rows1 row
     uint32_t *rows1;                           // [chunks][NB1] suffix sums of the chunk histograms
     double *chunk_err;                         // [chunks] sum of squares below the bucket
@@ -303,6 +305,101 @@ __device__ __forceinline__ void pick_from_global(const uint32_t *G, uint32_t kre
     __syncthreads();
 }
 
+// Bucket search on per-block rows of suffix sums.  rows[r][NB] holds, for block r, the number of
+// its keys whose digit is >= d at entry d; coarse[r][NC] repeats every (NB / NC)-th entry
+// contiguously.  The column sums over the nrows rows are the global suffix sums S[d], non-increasing
+// in d, and the bucket is B = max d with S[d] >= krem.  Step A sums the NC coarse columns and finds
+// the coarse interval, step B sums its NB / NC fine columns (and, aside, the part of those sums that
+// belongs to rows < below_rows).  16-byte loads, 8 in flight per thread.  Every thread of the
+// workgroup calls it and gets the same result; red is LDS scratch of NC + 2 * (NB / NC) words.
+struct ColumnPick {
+    uint32_t B;      // NB when krem == 0 (nothing to select)
+    uint32_t above;  // S[B + 1]
+    uint32_t total;  // S[B]
+    uint32_t below;  // the part of S[B] that comes from rows < below_rows
+};
+template <int NB, int NC>
+__device__ __forceinline__ ColumnPick column_pick(const uint32_t *rows, const uint32_t *coarse, int nrows,
+                                                  int below_rows, uint32_t krem, uint32_t *red) {
+    constexpr int FINE = NB / NC;
+    static_assert(NC <= 64 && FINE <= 64 && NC % 4 == 0 && FINE % 4 == 0 && BLOCK % (NC / 4) == 0 &&
+                      BLOCK % (FINE / 4) == 0 && NC + 2 * FINE <= BLOCK,
+                  "column_pick geometry");
+    uint32_t *redA = red, *redB = red + NC, *redBelow = red + NC + FINE;
+    ColumnPick r{static_cast<uint32_t>(NB), 0u, 0u, 0u};
+    __syncthreads();
+    if (threadIdx.x < NC + 2 * FINE) red[threadIdx.x] = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    {
+        constexpr int Q = NC / 4, G = BLOCK / Q;
+        const int q = threadIdx.x % Q;
+        const uint4 *co = reinterpret_cast<const uint4 *>(coarse) + q;
+        uint4 sum = make_uint4(0, 0, 0, 0);
+        for (int r0 = threadIdx.x / Q; r0 < nrows; r0 += G * 8) {
+            uint4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int rr = r0 + u * G;
+                v[u] = (rr < nrows) ? co[static_cast<size_t>(rr) * Q] : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                sum.x += v[u].x; sum.y += v[u].y; sum.z += v[u].z; sum.w += v[u].w;
+            }
+        }
+        atomicAdd(&redA[4 * q + 0], sum.x);
+        atomicAdd(&redA[4 * q + 1], sum.y);
+        atomicAdd(&redA[4 * q + 2], sum.z);
+        atomicAdd(&redA[4 * q + 3], sum.w);
+    }
+    __syncthreads();
+    const uint64_t okA = __ballot(lane < NC && redA[lane % NC] >= krem);  // bit j: S[j * FINE] >= krem; a prefix of ones
+    if (krem != 0 && okA != 0) {                                            // uniform over the workgroup
+        const int J = 63 - __builtin_clzll(okA);
+        {
+            constexpr int Q = FINE / 4, G = BLOCK / Q;
+            const int q = threadIdx.x % Q;
+            const uint4 *col = reinterpret_cast<const uint4 *>(rows + J * FINE) + q;
+            uint4 all = make_uint4(0, 0, 0, 0), below = make_uint4(0, 0, 0, 0);
+            for (int r0 = threadIdx.x / Q; r0 < nrows; r0 += G * 8) {
+                uint4 v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int rr = r0 + u * G;
+                    v[u] = (rr < nrows) ? col[static_cast<size_t>(rr) * (NB / 4)] : make_uint4(0, 0, 0, 0);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    all.x += v[u].x; all.y += v[u].y; all.z += v[u].z; all.w += v[u].w;
+                    if (r0 + u * G < below_rows) {
+                        below.x += v[u].x; below.y += v[u].y; below.z += v[u].z; below.w += v[u].w;
+                    }
+                }
+            }
+            atomicAdd(&redB[4 * q + 0], all.x);
+            atomicAdd(&redB[4 * q + 1], all.y);
+            atomicAdd(&redB[4 * q + 2], all.z);
+            atomicAdd(&redB[4 * q + 3], all.w);
+            if (below_rows > 0) {
+                atomicAdd(&redBelow[4 * q + 0], below.x);
+                atomicAdd(&redBelow[4 * q + 1], below.y);
+                atomicAdd(&redBelow[4 * q + 2], below.z);
+                atomicAdd(&redBelow[4 * q + 3], below.w);
+            }
+        }
+        __syncthreads();
+        const uint64_t okB = __ballot(lane < FINE && redB[lane % FINE] >= krem);
+        const int I = 63 - __builtin_clzll(okB | 1ull);  // bit 0 is set anyway: S[J * FINE] >= krem
+        r.B = J * FINE + I;
+        r.above = (I + 1 < FINE) ? redB[I + 1] : ((J + 1 < NC) ? redA[J + 1] : 0u);
+        r.total = redB[I];
+        r.below = redBelow[I];
+    }
+    __syncthreads();
+    return r;
+}
+
 // ------------------------------------------------------------------ k_hist1
 // LDS histogram of the top digit with HREP interleaved copies: lane l adds into copy l % HREP of
 // its bin, stored at word bin * HREP + copy, so lanes that share a hot bin spread over banks.
@@ -379,7 +476,6 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist1(Launch a) {
     if (c == 0) {  // first chunk of the segment: clear what the later kernels of this call accumulate into
         uint32_t *st = reinterpret_cast<uint32_t *>(&a.state[s]);
         if (threadIdx.x < sizeof(SegState) / 4) st[threadIdx.x] = 0;
-        for (int b = threadIdx.x; b < NB2; b += BLOCK) a.G2[s * NB2 + b] = 0;
         for (int b = threadIdx.x; b < NB3; b += BLOCK) a.G3[s * NB3 + b] = 0;
     }
 }
@@ -509,6 +605,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     __shared__ uint32_t h[NB1];  // top-digit histogram during the prologue, then the second-digit one
     __shared__ uint32_t wcnt[2][NW];
     __shared__ uint2 stage[STAGE_CAP];
+    __shared__ uint32_t sm[NW];
     __shared__ double smd[NW];
 
     const int g = blockIdx.x;
@@ -518,85 +615,18 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     const int64_t beg = static_cast<int64_t>(c) * a.E;
     const int64_t end = (beg + a.E < sg.n) ? beg + a.E : sg.n;
 
-    // Prologue, the same in every block of the segment.  The rows of k_hist1 hold suffix sums, so
-    // the column sums over the segment's chunks are the global suffix sums S[d] = #{top digit >= d},
-    // non-increasing in d; the bucket is B1 = max d with S[d] >= k.  Step A sums the NC1 coarse
-    // columns and finds the coarse interval, step B sums its FINE1 columns (and, aside, the part
-    // of those sums that belongs to the earlier chunks: this chunk's offset in the list).
-    uint32_t B1 = NB1, c_gt1 = 0, off = 0, cnt = 0, m_total = 0;
-    {
-        uint32_t *redA = h, *redB = h + NC1, *redBelow = h + NC1 + FINE1;
-        if (threadIdx.x < NC1 + 2 * FINE1) h[threadIdx.x] = 0;
-        __syncthreads();
-        const uint32_t kk = static_cast<uint32_t>(sg.k);
-        const int lane = threadIdx.x & 63;
-        {  // step A: 16-byte loads, 8 in flight per thread
-            constexpr int Q = NC1 / 4, G = BLOCK / Q;
-            const int q = threadIdx.x % Q;
-            const uint4 *co = reinterpret_cast<const uint4 *>(a.coarse1 + static_cast<size_t>(sg.chunk_begin) * NC1) + q;
-            uint4 sum = make_uint4(0, 0, 0, 0);
-            for (int cc0 = threadIdx.x / Q; cc0 < sg.nchunks; cc0 += G * 8) {
-                uint4 v[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int cc = cc0 + u * G;
-                    v[u] = (cc < sg.nchunks) ? co[static_cast<size_t>(cc) * Q] : make_uint4(0, 0, 0, 0);
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    sum.x += v[u].x; sum.y += v[u].y; sum.z += v[u].z; sum.w += v[u].w;
-                }
-            }
-            atomicAdd(&redA[4 * q + 0], sum.x);
-            atomicAdd(&redA[4 * q + 1], sum.y);
-            atomicAdd(&redA[4 * q + 2], sum.z);
-            atomicAdd(&redA[4 * q + 3], sum.w);
-        }
-        __syncthreads();
-        const uint64_t okA = __ballot(redA[lane] >= kk);  // bit j: S[j * FINE1] >= k; a prefix of ones
-        if (kk != 0 && okA != 0) {                        // uniform
-            const int J = 63 - __builtin_clzll(okA);
-            {  // step B: the FINE1 columns of coarse interval J, again 8 16-byte loads in flight
-                constexpr int Q = FINE1 / 4, G = BLOCK / Q;
-                const int q = threadIdx.x % Q;
-                const uint4 *col = reinterpret_cast<const uint4 *>(a.rows1 + static_cast<size_t>(sg.chunk_begin) * NB1 +
-                                                                   J * FINE1) + q;
-                uint4 all = make_uint4(0, 0, 0, 0), below = make_uint4(0, 0, 0, 0);
-                for (int cc0 = threadIdx.x / Q; cc0 < sg.nchunks; cc0 += G * 8) {
-                    uint4 v[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const int cc = cc0 + u * G;
-                        v[u] = (cc < sg.nchunks) ? col[static_cast<size_t>(cc) * (NB1 / 4)] : make_uint4(0, 0, 0, 0);
-                    }
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        all.x += v[u].x; all.y += v[u].y; all.z += v[u].z; all.w += v[u].w;
-                        if (cc0 + u * G < c) {
-                            below.x += v[u].x; below.y += v[u].y; below.z += v[u].z; below.w += v[u].w;
-                        }
-                    }
-                }
-                atomicAdd(&redB[4 * q + 0], all.x);
-                atomicAdd(&redB[4 * q + 1], all.y);
-                atomicAdd(&redB[4 * q + 2], all.z);
-                atomicAdd(&redB[4 * q + 3], all.w);
-                atomicAdd(&redBelow[4 * q + 0], below.x);
-                atomicAdd(&redBelow[4 * q + 1], below.y);
-                atomicAdd(&redBelow[4 * q + 2], below.z);
-                atomicAdd(&redBelow[4 * q + 3], below.w);
-            }
-            __syncthreads();
-            const uint64_t okB = __ballot(lane < FINE1 && redB[lane & (FINE1 - 1)] >= kk);
-            const int I = 63 - __builtin_clzll(okB | 1ull);  // bit 0 is set anyway: S[J * FINE1] >= k
-            B1 = J * FINE1 + I;
-            c_gt1 = (I + 1 < FINE1) ? redB[I + 1] : ((J + 1 < NC1) ? redA[J + 1] : 0u);
-            m_total = redB[I];
-            off = redBelow[I];
-            cnt = a.rows1[static_cast<size_t>(g) * NB1 + B1];
-        }
-        __syncthreads();
-    }
+    // The first tile does not depend on the prologue: put its loads in flight now.
+    uint32_t cur[St::SLOTS], nxt[St::SLOTS], valid[St::SLOTS];
+    const bool fast = sg.aligned4 && beg + TILE <= end;
+    if (fast) St::load_fast(sg.x, beg, cur);
+
+    // Prologue, the same in every block of the segment: bucket B1 of the k-th key from the rows of
+    // k_hist1; the part of S[B1] that belongs to the earlier chunks is this chunk's offset in the list.
+    const ColumnPick p1 = column_pick<NB1, NC1>(a.rows1 + static_cast<size_t>(sg.chunk_begin) * NB1,
+                                                a.coarse1 + static_cast<size_t>(sg.chunk_begin) * NC1, sg.nchunks, c,
+                                                static_cast<uint32_t>(sg.k), h);
+    const uint32_t B1 = p1.B, c_gt1 = p1.above, off = p1.below, m_total = p1.total;
+    const uint32_t cnt = (B1 < NB1) ? a.rows1[static_cast<size_t>(g) * NB1 + B1] : 0u;
     if (c == sg.nchunks - 1 && threadIdx.x == 0) {
         a.state[s].B1 = B1;
         a.state[s].c_gt1 = c_gt1;
@@ -615,10 +645,8 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     double acc = 0.0;
     uint32_t running = 0, flushed = 0;
     int buf = 0;
-    uint32_t cur[St::SLOTS], nxt[St::SLOTS], valid[St::SLOTS];
     int64_t t0 = beg;
-    if (sg.aligned4 && t0 + TILE <= end) {  // full tiles, the next one in flight while this one is classified
-        St::load_fast(sg.x, t0, cur);
+    if (fast) {  // full tiles, the next one in flight while this one is classified
         for (;;) {
             const bool more = t0 + 2 * static_cast<int64_t>(TILE) <= end;
             if (more) St::load_fast(sg.x, t0 + TILE, nxt);
@@ -643,7 +671,11 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     const double bsum = block_sum_f64(acc, smd);
     if (threadIdx.x == 0) a.chunk_err[g] = bsum;
     __syncthreads();
-    flush_bins<NB2>(h2, a.G2 + s * NB2);
+    // second-digit counts of this chunk's bucket members, as a row of suffix sums (no global atomics)
+    block_suffix_inplace<NB2>(h2, sm);
+    uint32_t *row = a.rows2 + static_cast<size_t>(g) * NB2;
+    for (int b = threadIdx.x; b < NB2; b += BLOCK) row[b] = h2[b];
+    if (threadIdx.x < NC2) a.coarse2[static_cast<size_t>(g) * NC2 + threadIdx.x] = h2[threadIdx.x * (NB2 / NC2)];
 }
 
 // ------------------------------------------------------------------ list kernels
@@ -661,7 +693,6 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
     __shared__ uint32_t h[NB2 > NB3 ? NB2 : NB3];
     __shared__ uint32_t sm[NW];
     __shared__ double smd[NW];
-    __shared__ uint32_t s_pick[2];
 
     const int g = blockIdx.x;
     const int s = find_segment_by(a, g, false);
@@ -672,8 +703,10 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
     const uint32_t B1 = a.state[s].B1, c_gt1 = a.state[s].c_gt1;
 
     // Prologue: bucket of the second digit among the members of bucket B1.
-    uint32_t B2, above2;
-    pick_from_global<NB2>(a.G2 + s * NB2, static_cast<uint32_t>(sg.k) - c_gt1, h, sm, s_pick, B2, above2);
+    const ColumnPick p2 = column_pick<NB2, NC2>(a.rows2 + static_cast<size_t>(sg.chunk_begin) * NB2,
+                                                a.coarse2 + static_cast<size_t>(sg.chunk_begin) * NC2, sg.nchunks, 0,
+                                                static_cast<uint32_t>(sg.k) - c_gt1, h);
+    const uint32_t B2 = p2.B, above2 = p2.above;
     if (lb == 0 && threadIdx.x == 0) {
         a.state[s].B2 = B2;
         a.state[s].c_gt2 = c_gt1 + above2;
@@ -962,7 +995,7 @@ int32_t list_blocks(int64_t n, int32_t S) {
 }
 
 struct Carve {
-    size_t state, G2, G3, rows1, coarse1, chunk_err, rows3, ldef, lerr, L_idx, L_val, total;
+    size_t state, G3, rows1, coarse1, rows2, coarse2, chunk_err, rows3, ldef, lerr, L_idx, L_val, total;
 };
 
 // Workspace layout for up to max_chunks chunks, max_lb list blocks and n_total list slots.
@@ -975,10 +1008,11 @@ Carve carve(int64_t max_chunks, int64_t max_lb, int64_t n_total, adatopk_dtype d
         return at;
     };
     c.state = take(sizeof(SegState) * MAXSEG);
-    c.G2 = take(sizeof(uint32_t) * NB2 * MAXSEG);
     c.G3 = take(sizeof(uint32_t) * NB3 * MAXSEG);
     c.rows1 = take(sizeof(uint32_t) * NB1 * max_chunks);
     c.coarse1 = take(sizeof(uint32_t) * NC1 * max_chunks);
+    c.rows2 = take(sizeof(uint32_t) * NB2 * max_chunks);
+    c.coarse2 = take(sizeof(uint32_t) * NC2 * max_chunks);
     c.chunk_err = take(sizeof(double) * max_chunks);
     c.rows3 = take(sizeof(uint32_t) * NB3 * max_lb);
     c.ldef = take(sizeof(uint32_t) * max_lb);
@@ -1061,10 +1095,11 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
         a.S = (S - s0 < MAXSEG) ? S - s0 : MAXSEG;
         a.E = static_cast<int32_t>(E);
         a.state = reinterpret_cast<SegState *>(ws + cv.state);
-        a.G2 = reinterpret_cast<uint32_t *>(ws + cv.G2);
         a.G3 = reinterpret_cast<uint32_t *>(ws + cv.G3);
         a.rows1 = reinterpret_cast<uint32_t *>(ws + cv.rows1);
         a.coarse1 = reinterpret_cast<uint32_t *>(ws + cv.coarse1);
+        a.rows2 = reinterpret_cast<uint32_t *>(ws + cv.rows2);
+        a.coarse2 = reinterpret_cast<uint32_t *>(ws + cv.coarse2);
         a.chunk_err = reinterpret_cast<double *>(ws + cv.chunk_err);
         a.rows3 = reinterpret_cast<uint32_t *>(ws + cv.rows3);
         a.ldef = reinterpret_cast<uint32_t *>(ws + cv.ldef);
