@@ -40,6 +40,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--config", default="2", choices=["1", "2a", "2", "2c", "3", "4", "5"],
+                    help="workload: 2 (default, the headline: GELU tensor at k = 1 %%), 2a / 2c = the same tensor at "
+                         "k = 0.1 %% / 10 %%, 1, 3, 4 (segmented batch), 5 (bf16) = the other parity configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run the library's plain copy kernel on the workload-sized buffer (the known-size "
                          "kernel that hardware-counter readings are scaled by)")
@@ -61,20 +64,42 @@ def main() -> int:
     torch.cuda.set_device(0)
     B.load_library()  # fails loudly when the HIP library is not built
 
-    w = wl.config2((1, 100))
-    x_host, k = w.tensors[0], w.ks[0]
-    n = x_host.size
-    NBUF = 4
-    xs = [torch.from_numpy(x_host).cuda() for _ in range(NBUF)]
-    idx = torch.empty(k, dtype=torch.int32, device="cuda")
-    val = torch.empty(k, dtype=torch.float32, device="cuda")
-    err = torch.empty(1, dtype=torch.float32, device="cuda")
-    y = torch.empty(n, dtype=torch.float32, device="cuda")
-    ws = B.new_workspace(n, 1, torch.float32)
+    w = {"1": wl.config1, "2a": lambda: wl.config2((1, 1000)), "2": lambda: wl.config2((1, 100)),
+         "2c": lambda: wl.config2((1, 10)), "3": wl.config3, "4": wl.config4, "5": wl.config5}[args.config]()
+    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    esize = 4 if w.dtype == "f32" else 2
+    S = len(w.tensors)
+    n = w.n_total
+    ks = list(w.ks)
+    k = sum(ks)
+    off = [0]
+    for v in ks:
+        off.append(off[-1] + v)
+
+    def upload(t):
+        if w.dtype == "f32":
+            return torch.from_numpy(t).cuda()
+        return torch.from_numpy(t.view(np.int16)).cuda().view(torch.bfloat16)
+
+    # distinct input copies so that no step finds its input in the 256 MB last-level cache
+    NBUF = 4 if S == 1 else 1  # the segmented batch (805 MB) is larger than that cache by itself
+    xs = [[upload(t) for t in w.tensors] for _ in range(NBUF)]
+    x_host = w.tensors[0]
+    idx = torch.empty(max(k, 1), dtype=torch.int32, device="cuda")
+    val = torch.empty(max(k, 1), dtype=tdt, device="cuda")
+    err = torch.empty(S, dtype=torch.float32, device="cuda")
+    ys = [torch.empty(t.size, dtype=tdt, device="cuda") for t in w.tensors]
+    y = ys[0]
+    ws = B.new_workspace(n, S, tdt)
 
     def step(i: int) -> None:
-        B.adatopk_compress(xs[i % NBUF], k, idx, val, err, ws)
-        B.adatopk_decompress_sorted(idx, val, k, y)
+        if S == 1:
+            B.adatopk_compress(xs[i % NBUF][0], k, idx, val, err, ws)
+            B.adatopk_decompress_sorted(idx, val, k, y)
+        else:
+            B.adatopk_compress_segmented(xs[i % NBUF], ks, idx, val, off, err, ws)
+            for s_ in range(S):
+                B.adatopk_decompress_sorted(idx[off[s_]:off[s_ + 1]], val[off[s_]:off[s_ + 1]], ks[s_], ys[s_])
 
     for i in range(args.warmup):
         step(i)
@@ -85,23 +110,21 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     sec_per_step = (t1 - t0) / args.steps
-    dense_bytes = n * 4
+    dense_bytes = n * esize
     value = dense_bytes / sec_per_step / 1e9
 
     if args.calibrate_copy:
         for i in range(max(args.steps, 3)):
-            B.measure_copy(y, xs[i % NBUF])  # reads 4n bytes, writes 4n bytes
+            B.measure_copy(y, xs[i % NBUF][0])  # reads and writes the bytes of one tensor
         torch.cuda.synchronize()
 
     # same loop on one buffer only (input may be served by the last-level cache): reported aside
     for i in range(args.warmup):
-        B.adatopk_compress(xs[0], k, idx, val, err, ws)
-        B.adatopk_decompress_sorted(idx, val, k, y)
+        step(0)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        B.adatopk_compress(xs[0], k, idx, val, err, ws)
-        B.adatopk_decompress_sorted(idx, val, k, y)
+        step(0)
     torch.cuda.synchronize()
     warm_sec = (time.perf_counter() - t0) / args.steps
 
@@ -119,27 +142,29 @@ def main() -> int:
     B.measure_enable(False)
     stage_us = {nm: (1e3 * acc[j] / cnt[j] if cnt[j] else None) for j, nm in enumerate(names)}
 
-    # algorithmic bytes per launch of the full-size kernels (b = 4 bytes, n elements, k kept)
+    # algorithmic bytes per launch of the full-size kernels (b bytes per value, n elements, k kept);
+    # in the segmented workload k_merge runs once per tensor, so its launch moves 1/S of the bytes
+    b = esize
     algo = {
-        "k_hist1": 4 * n,                # one read of the input
-        "k_gather": 4 * n + 8 * k,       # second read of the input + the (index, value) pairs
-        "k_merge": 4 * n + 8 * k,        # one write of the dense output + the pairs read
+        "k_hist1": b * n,                          # one read of the input
+        "k_gather": b * n + (4 + b) * k,           # second read of the input + the (index, value) pairs
+        "k_merge": (b * n + (4 + b) * k) // S,     # one write of the dense output + the pairs read
     }
     dom = max(algo, key=lambda nm: stage_us[nm] or 0.0)
     dom_s = stage_us[dom] * 1e-6
     achieved = algo[dom] / dom_s / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES.get(dom),
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES.get(dom) if args.config == "2" else None,
                 "algorithmic_bytes": algo[dom], "avg_us": round(stage_us[dom], 2)}
 
     # bytes the whole step must move (12 B/element + the pairs written and read back) against peak
-    step_bytes = 3 * 4 * n + 2 * 8 * k
+    step_bytes = 3 * b * n + 2 * (4 + b) * k
     out = {
         "metric": "compress+decompress dense-input GB/s (fraction of HBM peak) at k=1%",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(sec_per_step * 1e3, 5), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "u32", "data": "synthetic",
-        "config": {"workload": "cfg2: GPT-2-small post-GELU activation fp32 [32,1024,768], n=25165824, k=251658 (1%)",
+        "vs_baseline": None, "dtype": "u32" if w.dtype == "f32" else "u16", "data": "synthetic",
+        "config": {"workload": "%s: %s, %d tensor(s), n=%d, k=%d" % (w.name, w.note, S, n, k),
                    "input_rotation": "%d distinct input buffers (%d MB)" % (NBUF, NBUF * dense_bytes // 10**6)},
         "elements_per_s": round(n / sec_per_step, 0),
         "hbm_fraction_of_peak_min_traffic": round(step_bytes / sec_per_step / 1e9 / HBM_PEAK_GBS, 4),
@@ -151,16 +176,25 @@ def main() -> int:
     if not args.no_cpu_baseline:
         from oracle import adatopk_oracle as orc
 
+        # the oracle as it stands, single thread, on the first tensor of the workload (all of it when S = 1)
+        step(0)
+        torch.cuda.synchronize()
         t0 = time.perf_counter()
-        ri, rv, re = orc.compress(x_host, k)
-        ry = orc.decompress(ri, rv, n)
+        ri, rv, re = orc.compress(x_host, ks[0])
+        ry = orc.decompress(ri, rv, x_host.size)
         cpu_sec = time.perf_counter() - t0
-        ok = (np.array_equal(idx.cpu().numpy(), ri) and np.array_equal(val.cpu().numpy().view(np.uint32), rv.view(np.uint32))
-              and np.array_equal(y.cpu().numpy().view(np.uint32), ry.view(np.uint32))
+        gi = idx[:ks[0]].cpu().numpy()
+        gv = val[:ks[0]].cpu()
+        gv = gv.numpy() if w.dtype == "f32" else gv.view(torch.int16).numpy().view(np.uint16)
+        gy = ys[0].cpu()
+        gy = gy.numpy() if w.dtype == "f32" else gy.view(torch.int16).numpy().view(np.uint16)
+        bits = (lambda a_: a_.view(np.uint32)) if w.dtype == "f32" else (lambda a_: a_)
+        ok = (np.array_equal(gi, ri) and np.array_equal(bits(gv), bits(rv)) and np.array_equal(bits(gy), bits(ry))
               and abs(float(err.cpu()[0]) - float(re)) <= 1e-5 * float(re))
-        out["cpu_baseline"] = {"value": round(dense_bytes / cpu_sec / 1e9, 5), "unit": "GB/s", "cores": 1,
+        out["cpu_baseline"] = {"value": round(x_host.size * esize / cpu_sec / 1e9, 5), "unit": "GB/s", "cores": 1,
                                "kind": "oracle", "seconds": round(cpu_sec, 3),
-                               "sample": "the whole workload tensor once (1 compress + 1 decompress of 25165824 elements)"}
+                               "sample": "tensor 1 of %d of the workload, whole (1 compress + 1 decompress of %d elements)"
+                                         % (S, x_host.size)}
         out["parity_with_oracle"] = bool(ok)
     print(json.dumps(out))
     return 0

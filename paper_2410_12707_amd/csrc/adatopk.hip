@@ -49,7 +49,7 @@ namespace {
 #define ADATOPK_BLOCK 512
 #endif
 #ifndef ADATOPK_HREP
-#define ADATOPK_HREP 2
+#define ADATOPK_HREP 1
 #endif
 #ifndef ADATOPK_CTARGET
 #define ADATOPK_CTARGET 512
@@ -69,14 +69,15 @@ constexpr int FINE1 = NB1 / NC1;    // fine bins per coarse interval
 constexpr int NC2 = 32;             // the same for the second digit
 constexpr int MAXSEG = 32;          // segments per launch (the table travels as kernel arguments)
 constexpr int CTARGET = ADATOPK_CTARGET;  // chunks aimed at per launch
-constexpr int LB_ELEMS = 16384;     // input elements per list block when sizing the list grid
+constexpr int LB_ELEMS = 8192;      // input elements per list block when sizing the list grid
+constexpr int LB_TOTAL = 4096;      // list blocks aimed at per launch, all segments together
 #ifndef ADATOPK_MERGE_SPANS
 #define ADATOPK_MERGE_SPANS 1024
 #endif
 constexpr size_t MERGE_SPANS = ADATOPK_MERGE_SPANS;  // output spans aimed at by the one-kernel decompress
 constexpr size_t MERGE_MIN_SPAN = 16384;  // bytes; smaller outputs use fewer workgroups
 static_assert(LU * NW <= 64, "per-tile wave counts must fit one wavefront scan");
-static_assert(HREP == 1 || HREP == 2 || HREP == 4, "histogram copies");
+static_assert(HREP == 1 || HREP == 2 || HREP == 4 || HREP == 8, "histogram copies");
 static_assert(NB1 % BLOCK == 0 && NB2 % BLOCK == 0 && NB3 % BLOCK == 0, "bins split evenly over threads");
 static_assert(BITS1 + BITS2 + BITS3 == 31, "digits cover the 31-bit key");
 static_assert(BLOCK >= 256, "k_emit scans the list blocks of a segment with one thread each");
@@ -431,19 +432,34 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist1(Launch a) {
     for (int b = threadIdx.x; b < NB1 * HREP; b += BLOCK) h[b] = 0;
     __syncthreads();
 
+    // Full tiles, two register buffers used in turn: the next tile's loads are in flight while this
+    // one is counted.  The loop body loads unconditionally and moves no registers (the last one or
+    // two tiles are peeled): a load under a condition, or a copy of the new buffer into the old one,
+    // makes the compiler wait for the new tile before the old one is processed.
     uint32_t cur[St::SLOTS], nxt[St::SLOTS], valid[St::SLOTS];
     int64_t t0 = beg;
-    if (sg.aligned4 && t0 + TILE <= end) {  // full tiles, the next one in flight while this one is counted
+    int64_t rem = sg.aligned4 ? (end - beg) / TILE : 0;
+    if (rem > 0) {
         St::load_fast(sg.x, t0, cur);
-        for (;;) {
-            const bool more = t0 + 2 * static_cast<int64_t>(TILE) <= end;
-            if (more) St::load_fast(sg.x, t0 + TILE, nxt);
+        while (rem > 2) {
+            St::load_fast(sg.x, t0 + TILE, nxt);
             __builtin_amdgcn_sched_barrier(0);
             hist1_tile<VEC, true>(cur, valid, h);
+            St::load_fast(sg.x, t0 + 2 * static_cast<int64_t>(TILE), cur);
+            __builtin_amdgcn_sched_barrier(0);
+            hist1_tile<VEC, true>(nxt, valid, h);
+            t0 += 2 * static_cast<int64_t>(TILE);
+            rem -= 2;
+        }
+        if (rem == 2) {
+            St::load_fast(sg.x, t0 + TILE, nxt);
+            __builtin_amdgcn_sched_barrier(0);
+            hist1_tile<VEC, true>(cur, valid, h);
+            hist1_tile<VEC, true>(nxt, valid, h);
+            t0 += 2 * static_cast<int64_t>(TILE);
+        } else {
+            hist1_tile<VEC, true>(cur, valid, h);
             t0 += TILE;
-            if (!more) break;
-#pragma unroll
-            for (int e = 0; e < St::SLOTS; ++e) cur[e] = nxt[e];
         }
     }
     for (; t0 < end; t0 += TILE) {
@@ -531,7 +547,8 @@ __device__ __forceinline__ void gather_tile(const uint32_t (&dw)[Stream<VEC>::SL
             keep[e][hh] = ok && key_of<VEC>(raw) >= thr_lo;
             m[e][hh] = __ballot(keep[e][hh]);
             wc += __popcll(m[e][hh]);
-            const double xd = (ok && !keep[e][hh]) ? static_cast<double>(value_of<VEC>(raw)) : 0.0;
+            const float xs = (ok && !keep[e][hh]) ? value_of<VEC>(raw) : 0.0f;  // select in fp32: one op, not two
+            const double xd = static_cast<double>(xs);
             acc = fma(xd, xd, acc);
         }
     if (lane == 0) wcnt[w] = wc;
@@ -617,8 +634,8 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
 
     // The first tile does not depend on the prologue: put its loads in flight now.
     uint32_t cur[St::SLOTS], nxt[St::SLOTS], valid[St::SLOTS];
-    const bool fast = sg.aligned4 && beg + TILE <= end;
-    if (fast) St::load_fast(sg.x, beg, cur);
+    const int64_t ntiles = sg.aligned4 ? (end - beg) / TILE : 0;
+    if (ntiles > 0) St::load_fast(sg.x, beg, cur);
 
     // Prologue, the same in every block of the segment: bucket B1 of the k-th key from the rows of
     // k_hist1; the part of S[B1] that belongs to the earlier chunks is this chunk's offset in the list.
@@ -644,25 +661,37 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
 
     double acc = 0.0;
     uint32_t running = 0, flushed = 0;
-    int buf = 0;
+    int wb = 0;
+    // Full tiles, two register buffers used in turn, unconditional loads, peeled tail (see k_hist1).
     int64_t t0 = beg;
-    if (fast) {  // full tiles, the next one in flight while this one is classified
-        for (;;) {
-            const bool more = t0 + 2 * static_cast<int64_t>(TILE) <= end;
-            if (more) St::load_fast(sg.x, t0 + TILE, nxt);
+    int64_t rem = ntiles;
+    auto tile = [&](const uint32_t(&dw)[St::SLOTS]) {
+        gather_tile<VEC, true>(dw, valid, t0, thr_lo, thr_hi, h2, wcnt[wb], stage, running, flushed, cnt, Li, Lv, acc);
+        t0 += TILE;
+        wb ^= 1;
+    };
+    if (rem > 0) {
+        while (rem > 2) {
+            St::load_fast(sg.x, t0 + TILE, nxt);
             __builtin_amdgcn_sched_barrier(0);
-            gather_tile<VEC, true>(cur, valid, t0, thr_lo, thr_hi, h2, wcnt[buf], stage, running, flushed, cnt, Li,
-                                   Lv, acc);
-            t0 += TILE;
-            buf ^= 1;
-            if (!more) break;
-#pragma unroll
-            for (int e = 0; e < St::SLOTS; ++e) cur[e] = nxt[e];
+            tile(cur);
+            St::load_fast(sg.x, t0 + TILE, cur);
+            __builtin_amdgcn_sched_barrier(0);
+            tile(nxt);
+            rem -= 2;
+        }
+        if (rem == 2) {
+            St::load_fast(sg.x, t0 + TILE, nxt);
+            __builtin_amdgcn_sched_barrier(0);
+            tile(cur);
+            tile(nxt);
+        } else {
+            tile(cur);
         }
     }
-    for (; t0 < end; t0 += TILE, buf ^= 1) {
+    for (; t0 < end; t0 += TILE, wb ^= 1) {
         St::load_slow(sg.x, t0, end, cur, valid);
-        gather_tile<VEC, false>(cur, valid, t0, thr_lo, thr_hi, h2, wcnt[buf], stage, running, flushed, cnt, Li, Lv,
+        gather_tile<VEC, false>(cur, valid, t0, thr_lo, thr_hi, h2, wcnt[wb], stage, running, flushed, cnt, Li, Lv,
                                 acc);
     }
     __syncthreads();
@@ -680,12 +709,21 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
 
 // ------------------------------------------------------------------ list kernels
 // Slot range of list block lb of a segment whose list holds m entries.
-__device__ __forceinline__ void list_range(uint32_t m, int lb, int lb_count, uint32_t &beg, uint32_t &end) {
+// A short list does not need all list blocks of the grid: a block takes at least LB_MIN entries,
+// so only the first `nactive` blocks (at least one) have work; the others return at once and are
+// ignored by everybody.  Both list kernels derive the same split from m.
+constexpr uint32_t LB_MIN = 2048;
+__device__ __forceinline__ void list_range(uint32_t m, int lb, int lb_count, uint32_t &beg, uint32_t &end,
+                                           int &nactive) {
     constexpr uint32_t LT = BLOCK * LU;
-    const uint32_t per = ((m + lb_count - 1) / lb_count + LT - 1) / LT * LT;  // whole tiles per block
+    uint32_t per = (m + lb_count - 1) / lb_count;
+    per = per < LB_MIN ? LB_MIN : per;
+    per = (per + LT - 1) / LT * LT;  // whole tiles per block
     const uint64_t b = static_cast<uint64_t>(per) * lb;
     beg = b < m ? static_cast<uint32_t>(b) : m;
     end = (b + per < m) ? static_cast<uint32_t>(b + per) : m;
+    const uint32_t na = (m + per - 1) / per;
+    nactive = na < 1 ? 1 : static_cast<int>(na);
 }
 
 template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
@@ -700,6 +738,10 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
     const int lb = g - sg.lb_begin;
     if (sg.nchunks == 0) return;  // empty tensor: nothing was listed, and nobody cleared its state
     const uint32_t m = a.state[s].m;
+    uint32_t beg, end;
+    int nactive;
+    list_range(m, lb, sg.lb_count, beg, end, nactive);
+    if (lb >= nactive) return;
     const uint32_t B1 = a.state[s].B1, c_gt1 = a.state[s].c_gt1;
 
     // Prologue: bucket of the second digit among the members of bucket B1.
@@ -713,8 +755,6 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
     }
     const uint32_t P = (B1 << BITS2) | B2;  // 21-bit prefix of the threshold
     const R *Lv = static_cast<const R *>(a.L_val) + sg.l_base;
-    uint32_t beg, end;
-    list_range(m, lb, sg.lb_count, beg, end);
 
     uint32_t *h3 = h;
     for (int b = threadIdx.x; b < NB3; b += BLOCK) h3[b] = 0;
@@ -762,6 +802,10 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
         return;
     }
     const uint32_t m = a.state[s].m;
+    uint32_t beg, end;
+    int nactive;
+    list_range(m, lb, sg.lb_count, beg, end, nactive);
+    if (lb >= nactive) return;
     const uint32_t P = (a.state[s].B1 << BITS2) | a.state[s].B2;
     const uint32_t c_gt2 = a.state[s].c_gt2;
     const uint32_t kout = static_cast<uint32_t>(sg.k);
@@ -783,7 +827,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     if (lb == 0 && a.err_out != nullptr) {
         double part = 0.0;
         for (int cc = threadIdx.x; cc < sg.nchunks; cc += BLOCK) part += a.chunk_err[sg.chunk_begin + cc];
-        for (int bb = threadIdx.x; bb < sg.lb_count; bb += BLOCK) part += a.lerr[sg.lb_begin + bb];
+        for (int bb = threadIdx.x; bb < nactive; bb += BLOCK) part += a.lerr[sg.lb_begin + bb];
 #pragma unroll
         for (int j = 0; j < NB3 / BLOCK; ++j) {
             const uint32_t b = threadIdx.x * (NB3 / BLOCK) + j;
@@ -803,7 +847,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     // (#keys above T, #keys equal to T).
     {
         uint32_t gt = 0, eq = 0;
-        if (static_cast<int>(threadIdx.x) < sg.lb_count && B3 < NB3) {
+        if (static_cast<int>(threadIdx.x) < nactive && B3 < NB3) {
             const uint32_t *r = a.rows3 + static_cast<size_t>(sg.lb_begin + threadIdx.x) * NB3;
             const uint32_t above = (B3 + 1 < NB3) ? r[B3 + 1] : 0u;
             gt = a.ldef[sg.lb_begin + threadIdx.x] + above;
@@ -824,8 +868,6 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     const R *Lv = static_cast<const R *>(a.L_val) + sg.l_base;
     int32_t *oi = a.idx_out + sg.out_off;
     R *ov = static_cast<R *>(a.val_out) + sg.out_off;
-    uint32_t beg, end;
-    list_range(m, lb, sg.lb_count, beg, end);
 
     int buf = 0;
     for (uint32_t t0 = beg; t0 < end; t0 += BLOCK * LU, buf ^= 1) {
@@ -980,10 +1022,10 @@ int64_t chunk_elems(int64_t n_total, adatopk_dtype dt) {
     return e < cap ? e : cap;
 }
 
-int32_t list_blocks_cap(int32_t S) {
-    int32_t c = 1024 / (S < 1 ? 1 : (S > MAXSEG ? MAXSEG : S));
+int32_t list_blocks_cap(int32_t S) {  // k_emit scans a segment's list blocks with one thread each: at most BLOCK
+    int32_t c = LB_TOTAL / (S < 1 ? 1 : (S > MAXSEG ? MAXSEG : S));
     if (c < 16) c = 16;
-    if (c > 256) c = 256;
+    if (c > BLOCK) c = BLOCK;
     return c;
 }
 
@@ -1023,10 +1065,14 @@ Carve carve(int64_t max_chunks, int64_t max_lb, int64_t n_total, adatopk_dtype d
     return c;
 }
 
+// Upper bounds on the chunks and list blocks of any one launch of a call over n_total elements
+// in S segments: a launch holds at most MAXSEG segments, every segment's last chunk may be
+// partial, and the planner never uses more than CTARGET full chunks nor chunks below one tile.
 void bounds_for(int64_t n_total, int32_t S, adatopk_dtype dt, int64_t *max_chunks, int64_t *max_lb) {
-    const int64_t E = chunk_elems(n_total, dt);
+    (void)dt;
     const int32_t batch = S > MAXSEG ? MAXSEG : (S < 1 ? 1 : S);
-    *max_chunks = n_total / E + batch + 1;
+    const int64_t by_tiles = n_total / TILE + 1;
+    *max_chunks = (by_tiles < CTARGET ? by_tiles : CTARGET) + batch + 1;
     *max_lb = static_cast<int64_t>(batch) * list_blocks_cap(S);
 }
 
@@ -1088,11 +1134,23 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
     bounds_for(n_total, S, dt, &max_chunks, &max_lb);
     const Carve cv = carve(max_chunks, max_lb, n_total, dt);
     char *ws = static_cast<char *>(workspace);
-    const int64_t E = chunk_elems(n_total, dt);
 
     for (int32_t s0 = 0; s0 < S; s0 += MAXSEG) {
         Launch a{};
         a.S = (S - s0 < MAXSEG) ? S - s0 : MAXSEG;
+        // Chunk size of this launch: about CTARGET chunks in all, and not more, so that all workgroups
+        // are resident at once (a few chunks beyond that would run as a second, nearly empty round).
+        int64_t n_batch = 0;
+        for (int32_t i = 0; i < a.S; ++i) n_batch += n[s0 + i];
+        int64_t E = chunk_elems(n_batch, dt);
+        for (int iter = 0; iter < 32; ++iter) {
+            int64_t count = 0;
+            for (int32_t i = 0; i < a.S; ++i) count += (n[s0 + i] + E - 1) / E;
+            if (count <= CTARGET) break;
+            const int64_t grown = ((E * count + CTARGET - 1) / CTARGET + TILE - 1) / TILE * TILE;
+            E = grown > E ? grown : E + TILE;
+            if (E > (static_cast<int64_t>(1) << 30)) break;
+        }
         a.E = static_cast<int32_t>(E);
         a.state = reinterpret_cast<SegState *>(ws + cv.state);
         a.G3 = reinterpret_cast<uint32_t *>(ws + cv.G3);
