@@ -75,6 +75,7 @@ constexpr int LB_TOTAL = 4096;      // list blocks aimed at per launch, all segm
 #define ADATOPK_MERGE_SPANS 1024
 #endif
 constexpr size_t MERGE_SPANS = ADATOPK_MERGE_SPANS;  // output spans aimed at by the one-kernel decompress
+constexpr int64_t MERGE_DENSE_RATIO = 32;  // k > n / 32 takes the LDS-built variant of the one-kernel decompress
 constexpr size_t MERGE_MIN_SPAN = 16384;  // bytes; smaller outputs use fewer workgroups
 static_assert(LU * NW <= 64, "per-tile wave counts must fit one wavefront scan");
 static_assert(HREP == 1 || HREP == 2 || HREP == 4 || HREP == 8, "histogram copies");
@@ -991,6 +992,66 @@ __global__ __launch_bounds__(BLOCK) void k_merge(const int32_t *idx, const R *va
     }
 }
 
+// The same for many entries per line (k / n of a few per cent and more), where k_merge's value
+// stores would rewrite most output lines a second time: same spans, same search, but the span is
+// built piece by piece in LDS (zeros, then the entries that fall into the piece) and every
+// piece is written out once with 16-byte stores, so no output line is written twice.  Entries are
+// ascending, so every thread walks its own (strided) subsequence of them forwards.  An entry
+// whose index lies outside the piece that the walk assigned it to (possible only when idx is not
+// ascending) is skipped: every store stays inside the span.
+constexpr int MERGE_PIECE = 32768;  // bytes of LDS per piece
+template <typename R>
+__global__ __launch_bounds__(BLOCK) void k_merge_lds(const int32_t *idx, const R *val, uint32_t k, unsigned char *y,
+                                                     size_t total, size_t head, size_t span) {
+    __shared__ __attribute__((aligned(16))) unsigned char piece[MERGE_PIECE];
+    __shared__ uint32_t s_range[2];
+    const size_t byte_a = blockIdx.x == 0 ? 0 : head + static_cast<size_t>(blockIdx.x) * span;
+    const size_t byte_b = blockIdx.x + 1 == gridDim.x ? total : head + static_cast<size_t>(blockIdx.x + 1) * span;
+    const int w = threadIdx.x >> 6;
+    if (w < 2) {
+        const int64_t bound = static_cast<int64_t>((w == 0 ? byte_a : byte_b) / sizeof(R));
+        const uint32_t pos = wave_lower_bound(idx, k, bound);
+        if ((threadIdx.x & 63) == 0) s_range[w] = pos;
+    }
+    // unaligned head of the whole tensor (workgroup 0 only, < 16 bytes): entries there are written
+    // after the zeros by the same thread order below, so handle it as part of the first piece
+    const size_t va = blockIdx.x == 0 ? (head < byte_b ? head : byte_b) : byte_a;  // 16-byte aligned start
+    __syncthreads();
+    uint32_t j = s_range[0] + threadIdx.x;  // this thread's next entry
+    const uint32_t jb = s_range[1];
+    R *out = reinterpret_cast<R *>(y);
+    if (va > byte_a) {  // workgroup 0: the few bytes before the first aligned address, straight to memory
+        for (size_t i = byte_a + threadIdx.x; i < va; i += BLOCK) y[i] = 0;
+        __syncthreads();
+        const int64_t e1 = static_cast<int64_t>(va / sizeof(R));
+        for (uint32_t jj = s_range[0] + threadIdx.x; jj < jb; jj += BLOCK) {
+            const int64_t i = idx[jj];
+            if (i >= e1) break;
+            if (i >= 0) out[i] = val[jj];
+        }
+    }
+    for (size_t p0 = va; p0 < byte_b; p0 += MERGE_PIECE) {
+        const size_t p1 = (p0 + MERGE_PIECE < byte_b) ? p0 + MERGE_PIECE : byte_b;
+        const int64_t e0 = static_cast<int64_t>(p0 / sizeof(R)), e1 = static_cast<int64_t>(p1 / sizeof(R));
+        uint4 *pz = reinterpret_cast<uint4 *>(piece);
+        for (int i = threadIdx.x; i < MERGE_PIECE / 16; i += BLOCK) pz[i] = make_uint4(0, 0, 0, 0);
+        __syncthreads();
+        R *pl = reinterpret_cast<R *>(piece);
+        while (j < jb) {
+            const int64_t i = idx[j];
+            if (i >= e1) break;
+            if (i >= e0) pl[i - e0] = val[j];
+            j += BLOCK;
+        }
+        __syncthreads();
+        const size_t nvec = (p1 - p0) / 16;
+        uint4 *dst = reinterpret_cast<uint4 *>(y + p0);
+        for (size_t i = threadIdx.x; i < nvec; i += BLOCK) dst[i] = pz[i];
+        for (size_t i = p0 + nvec * 16 + threadIdx.x; i < p1; i += BLOCK) y[i] = piece[i - p0];  // ragged end of the tensor
+        __syncthreads();
+    }
+}
+
 __global__ __launch_bounds__(BLOCK) void k_copy16(uint4 *dst, const uint4 *src, size_t n16) {
     const size_t stride = static_cast<size_t>(gridDim.x) * BLOCK;
     for (size_t i = static_cast<size_t>(blockIdx.x) * BLOCK + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
@@ -1279,12 +1340,18 @@ adatopk_status adatopk_decompress_sorted(const int32_t *idx, const void *val, in
     size_t span = (body / MERGE_SPANS + 15) / 16 * 16;
     if (span < MERGE_MIN_SPAN) span = MERGE_MIN_SPAN;
     const unsigned grid = static_cast<unsigned>(body / span + 1);  // the last workgroup takes the remainder
-    if (dt == ADATOPK_F32)
-        launch(ST_MERGE, k_merge<uint32_t>, dim3(grid), st, idx, static_cast<const uint32_t *>(val),
-               static_cast<uint32_t>(k), static_cast<unsigned char *>(dense_out), total, head, span);
-    else
-        launch(ST_MERGE, k_merge<uint16_t>, dim3(grid), st, idx, static_cast<const uint16_t *>(val),
-               static_cast<uint32_t>(k), static_cast<unsigned char *>(dense_out), total, head, span);
+    const bool dense = k > n / MERGE_DENSE_RATIO;  // more than one entry per few lines: build the lines in LDS
+    const uint32_t ku = static_cast<uint32_t>(k);
+    unsigned char *yb = static_cast<unsigned char *>(dense_out);
+    if (dt == ADATOPK_F32) {
+        const uint32_t *v = static_cast<const uint32_t *>(val);
+        if (dense) launch(ST_MERGE, k_merge_lds<uint32_t>, dim3(grid), st, idx, v, ku, yb, total, head, span);
+        else launch(ST_MERGE, k_merge<uint32_t>, dim3(grid), st, idx, v, ku, yb, total, head, span);
+    } else {
+        const uint16_t *v = static_cast<const uint16_t *>(val);
+        if (dense) launch(ST_MERGE, k_merge_lds<uint16_t>, dim3(grid), st, idx, v, ku, yb, total, head, span);
+        else launch(ST_MERGE, k_merge<uint16_t>, dim3(grid), st, idx, v, ku, yb, total, head, span);
+    }
     return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
 }
 
