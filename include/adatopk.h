@@ -111,6 +111,30 @@ adatopk_status adatopk_adaptive_ratios(const double *R, int32_t m, double r_user
  * n <= 0; -1 when r_i < 1 or is NaN. */
 int64_t adatopk_k_for_ratio(int64_t n, double r_i);
 
+/* Host-only: the estimates that feed the rule (paper Sec. 3.5 and 3.6) and what the rule does to
+ * the pipeline (Sec. 5.2).  All return NaN for invalid arguments (m <= 0, n_b < 1, NULL, negative
+ * or non-finite times).
+ *   adatopk_link_time             alpha-beta model, Sec. 3.5: T_comm(M) = alpha + beta * M
+ *   adatopk_pipeline_time         Eq. "time_pipe", Sec. 3.6:
+ *                                 sum_p (C_p + R_p) + (n_b - 1) * max_p max(C_p, R_p)
+ *   adatopk_pipeline_time_compressed   Eq. "time_pipe_compress", Sec. 5.2, with r_p from Eq. "adacompress":
+ *       variant 0, as printed:    sum_p (C_p + coeff R_p / r_p) + coeff (n_b - 1) max_p max(C_p, R_p) / r_user
+ *       variant 1, every link with its own ratio also in the bottleneck term:
+ *                                 sum_p (C_p + coeff R_p / r_p) + (n_b - 1) max_p max(C_p, coeff R_p / r_p)
+ * C, R: computation and uncompressed communication time of each of the m pipeline stages. */
+double adatopk_link_time(double alpha, double beta, double message_bytes);
+double adatopk_pipeline_time(const double *C, const double *R, int32_t m, int32_t n_b);
+double adatopk_pipeline_time_compressed(const double *C, const double *R, int32_t m, int32_t n_b, double r_user,
+                                        double coeff, int32_t variant);
+
+/* Host-only: from link parameters to the k array of a segmented compress call.  Tensor s of n[s]
+ * values of type dt crosses a link with latency alpha[s] and inverse bandwidth beta[s] (seconds per
+ * byte): R_s = alpha_s + beta_s * bytes(tensor s) (Sec. 3.5), r_s from Eq. "adacompress",
+ * k_out[s] = adatopk_k_for_ratio(n[s], r_s).  r_out may be NULL.  EINVAL as for the rule. */
+adatopk_status adatopk_plan_keep_counts(const double *alpha, const double *beta, const int64_t *n, int32_t m,
+                                        adatopk_dtype dt, double r_user, double coeff, double *r_out,
+                                        int64_t *k_out);
+
 #ifdef __cplusplus
 }
 #endif

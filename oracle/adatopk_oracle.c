@@ -206,3 +206,40 @@ int64_t oracle_k_for_ratio(int64_t n, double r_i) {
     if (k > n) k = n;
     return k;
 }
+
+/* Sec. 3.5, alpha-beta model of one link: T = alpha + beta * M. */
+double oracle_link_time(double alpha, double beta, double bytes) { return alpha + beta * bytes; }
+
+/* Sec. 3.6, Eq. "time_pipe": sum_p (C_p + R_p) + (n_b - 1) * max_p max(C_p, R_p). */
+double oracle_pipeline_time(const double *C, const double *R, int32_t m, int32_t n_b) {
+    double sum = 0.0, worst = 0.0;
+    for (int32_t p = 0; p < m; ++p) {
+        sum += C[p] + R[p];
+        if (C[p] > worst) worst = C[p];
+        if (R[p] > worst) worst = R[p];
+    }
+    return sum + (double)(n_b - 1) * worst;
+}
+
+/* Sec. 5.2, Eq. "time_pipe_compress" with r_p from Eq. "adacompress".
+ * variant 0 is the equation as printed (bottleneck term 3 (n_b - 1) max(C_p, R_p) / r);
+ * variant 1 puts each link's own compressed time coeff R_p / r_p into the bottleneck term. */
+double oracle_pipeline_time_compressed(const double *C, const double *R, int32_t m, int32_t n_b, double r,
+                                       double coeff, int32_t variant) {
+    double Rmax = 0.0;
+    for (int32_t p = 0; p < m; ++p)
+        if (R[p] > Rmax) Rmax = R[p];
+    double sum = 0.0, worst_printed = 0.0, worst_own = 0.0;
+    for (int32_t p = 0; p < m; ++p) {
+        double rp = Rmax > 0.0 ? coeff * r * R[p] / Rmax : 1.0;
+        if (rp < 1.0) rp = 1.0;
+        double sent = coeff * R[p] / rp;
+        sum += C[p] + sent;
+        double a = C[p] > R[p] ? C[p] : R[p];
+        double b = C[p] > sent ? C[p] : sent;
+        if (a > worst_printed) worst_printed = a;
+        if (b > worst_own) worst_own = b;
+    }
+    if (variant == 0) return sum + coeff * (double)(n_b - 1) * worst_printed / r;
+    return sum + (double)(n_b - 1) * worst_own;
+}

@@ -44,6 +44,13 @@ def _load():
         lib.oracle_adaptive_ratios.argtypes = [p, i32, ctypes.c_double, ctypes.c_double, p]
         lib.oracle_k_for_ratio.argtypes = [i64, ctypes.c_double]
         lib.oracle_k_for_ratio.restype = i64
+        dbl = ctypes.c_double
+        lib.oracle_link_time.argtypes = [dbl, dbl, dbl]
+        lib.oracle_link_time.restype = dbl
+        lib.oracle_pipeline_time.argtypes = [p, p, i32, i32]
+        lib.oracle_pipeline_time.restype = dbl
+        lib.oracle_pipeline_time_compressed.argtypes = [p, p, i32, i32, dbl, dbl, i32]
+        lib.oracle_pipeline_time_compressed.restype = dbl
         _lib = lib
     return _lib
 
@@ -118,3 +125,23 @@ def adaptive_ratios(R, r: float, coeff: float = 3.0) -> np.ndarray:
 
 def k_for_ratio(n: int, r_i: float) -> int:
     return int(_load().oracle_k_for_ratio(int(n), float(r_i)))
+
+
+def link_time(alpha: float, beta: float, nbytes: float) -> float:
+    """Sec. 3.5: T_comm = alpha + beta * M."""
+    return float(_load().oracle_link_time(float(alpha), float(beta), float(nbytes)))
+
+
+def pipeline_time(C, R, n_b: int) -> float:
+    """Sec. 3.6, Eq. "time_pipe"."""
+    C = np.ascontiguousarray(C, dtype=np.float64)
+    R = np.ascontiguousarray(R, dtype=np.float64)
+    return float(_load().oracle_pipeline_time(_ptr(C), _ptr(R), C.size, int(n_b)))
+
+
+def pipeline_time_compressed(C, R, n_b: int, r: float, coeff: float = 3.0, variant: int = 0) -> float:
+    """Sec. 5.2, Eq. "time_pipe_compress"; variant 0 as printed, 1 with each link's own ratio in the last term."""
+    C = np.ascontiguousarray(C, dtype=np.float64)
+    R = np.ascontiguousarray(R, dtype=np.float64)
+    return float(_load().oracle_pipeline_time_compressed(_ptr(C), _ptr(R), C.size, int(n_b), float(r), float(coeff),
+                                                         int(variant)))

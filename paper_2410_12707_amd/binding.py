@@ -54,6 +54,15 @@ def load_library() -> ctypes.CDLL:
     lib.adatopk_adaptive_ratios.restype = i32
     lib.adatopk_k_for_ratio.argtypes = [i64, ctypes.c_double]
     lib.adatopk_k_for_ratio.restype = i64
+    dbl = ctypes.c_double
+    lib.adatopk_link_time.argtypes = [dbl, dbl, dbl]
+    lib.adatopk_link_time.restype = dbl
+    lib.adatopk_pipeline_time.argtypes = [p, p, i32, i32]
+    lib.adatopk_pipeline_time.restype = dbl
+    lib.adatopk_pipeline_time_compressed.argtypes = [p, p, i32, i32, dbl, dbl, i32]
+    lib.adatopk_pipeline_time_compressed.restype = dbl
+    lib.adatopk_plan_keep_counts.argtypes = [p, p, p, i32, i32, dbl, dbl, p, p]
+    lib.adatopk_plan_keep_counts.restype = i32
     lib.adatopk_measure_enable.argtypes = [i32]
     lib.adatopk_measure_enable.restype = i32
     lib.adatopk_measure_stage_count.restype = i32
@@ -153,6 +162,37 @@ def adatopk_adaptive_ratios(R: Sequence[float], r_user: float, coeff: float = 3.
 
 def adatopk_k_for_ratio(n: int, r_i: float) -> int:
     return int(load_library().adatopk_k_for_ratio(int(n), float(r_i)))
+
+
+def _dbl_array(v):
+    return (ctypes.c_double * max(len(v), 1))(*[float(x) for x in v])
+
+
+def adatopk_link_time(alpha: float, beta: float, message_bytes: float) -> float:
+    return float(load_library().adatopk_link_time(float(alpha), float(beta), float(message_bytes)))
+
+
+def adatopk_pipeline_time(C: Sequence[float], R: Sequence[float], n_b: int) -> float:
+    return float(load_library().adatopk_pipeline_time(_dbl_array(C), _dbl_array(R), len(C), int(n_b)))
+
+
+def adatopk_pipeline_time_compressed(C: Sequence[float], R: Sequence[float], n_b: int, r_user: float,
+                                     coeff: float = 3.0, variant: int = 0) -> float:
+    return float(load_library().adatopk_pipeline_time_compressed(_dbl_array(C), _dbl_array(R), len(C), int(n_b),
+                                                                 float(r_user), float(coeff), int(variant)))
+
+
+def adatopk_plan_keep_counts(alpha: Sequence[float], beta: Sequence[float], n: Sequence[int], dtype_code: int,
+                             r_user: float, coeff: float = 3.0):
+    """(ratios, keep counts) for tensors of n[s] values crossing links (alpha[s], beta[s])."""
+    m = len(n)
+    ns = (ctypes.c_int64 * max(m, 1))(*[int(v) for v in n])
+    r_out = (ctypes.c_double * max(m, 1))()
+    k_out = (ctypes.c_int64 * max(m, 1))()
+    _check(load_library().adatopk_plan_keep_counts(_dbl_array(alpha), _dbl_array(beta), ns, m, int(dtype_code),
+                                                   float(r_user), float(coeff), r_out, k_out),
+           "adatopk_plan_keep_counts")
+    return [r_out[i] for i in range(m)], [int(k_out[i]) for i in range(m)]
 
 
 # ------------------------------------------------------------------ measurement hooks

@@ -119,3 +119,48 @@ def test_k_for_ratio(lib):
             assert B.adatopk_k_for_ratio(n, r) == orc.k_for_ratio(n, r), (n, r)
     assert B.adatopk_k_for_ratio(10, 0.5) == -1
     assert B.adatopk_k_for_ratio(10, float("nan")) == -1
+
+
+def test_link_and_pipeline_estimates(lib):
+    import math
+
+    from oracle import adatopk_oracle as orc
+    from paper_2410_12707_amd import binding as B
+
+    with open(os.path.join(ROOT, "tests", "golden", "pipeline_hand_example.json")) as f:
+        g = json.load(f)
+    ln, pp, pl = g["link"], g["pipeline"], g["plan"]
+    assert B.adatopk_link_time(ln["alpha"], ln["beta"], ln["bytes"]) == pytest.approx(ln["T"], rel=1e-12)
+    assert B.adatopk_pipeline_time(pp["C"], pp["R"], pp["n_b"]) == pytest.approx(pp["time_pipe"], rel=1e-12)
+    assert B.adatopk_pipeline_time_compressed(pp["C"], pp["R"], pp["n_b"], pp["r"], pp["coeff"], 0) == pytest.approx(
+        pp["time_pipe_compress_printed"], rel=1e-12)
+    assert B.adatopk_pipeline_time_compressed(pp["C"], pp["R"], pp["n_b"], pp["r"], pp["coeff"], 1) == pytest.approx(
+        pp["time_pipe_compress_own_ratio"], rel=1e-12)
+    ratios, ks = B.adatopk_plan_keep_counts(pl["alpha"], pl["beta"], pl["n"], B.F32, pl["r"], pl["coeff"])
+    assert ratios == pytest.approx(pl["r_i"], rel=1e-12) and ks == pl["k"]
+    # against the oracle on a synthetic 8 Mbps .. 10 Gbps link set (the bandwidth range of the paper's testbeds)
+    import numpy as np
+
+    rng = np.random.Generator(np.random.PCG64(1))
+    m = 24
+    bw = np.exp(rng.uniform(np.log(8e6 / 8), np.log(10e9 / 8), size=m))  # bytes per second
+    alpha, beta = rng.uniform(1e-4, 5e-2, size=m), 1.0 / bw
+    n = [8 * 1024 * 1024] * m
+    C = rng.uniform(0.01, 0.5, size=m)
+    Rs = [orc.link_time(a, b, 4.0 * nn) for a, b, nn in zip(alpha, beta, n)]
+    ratios, ks = B.adatopk_plan_keep_counts(alpha.tolist(), beta.tolist(), n, B.F32, 100.0, 3.0)
+    assert ratios == pytest.approx(orc.adaptive_ratios(Rs, 100.0, 3.0).tolist(), rel=1e-12)
+    assert ks == [orc.k_for_ratio(nn, r) for nn, r in zip(n, ratios)]
+    for variant in (0, 1):
+        assert B.adatopk_pipeline_time_compressed(C.tolist(), Rs, 4, 100.0, 3.0, variant) == pytest.approx(
+            orc.pipeline_time_compressed(C, Rs, 4, 100.0, 3.0, variant), rel=1e-12)
+    assert B.adatopk_pipeline_time(C.tolist(), Rs, 4) == pytest.approx(orc.pipeline_time(C, Rs, 4), rel=1e-12)
+    # invalid arguments
+    assert math.isnan(B.adatopk_link_time(-1.0, 1.0, 1.0))
+    assert math.isnan(B.adatopk_pipeline_time([1.0], [1.0], 0))
+    assert math.isnan(B.adatopk_pipeline_time_compressed([1.0], [1.0], 2, 0.0, 3.0, 0))
+    assert math.isnan(B.adatopk_pipeline_time_compressed([1.0], [1.0], 2, 10.0, 3.0, 2))
+    with pytest.raises(B.AdaTopKError):
+        B.adatopk_plan_keep_counts([0.0], [0.0], [10], B.F32, 10.0, 3.0)  # no link takes any time
+    with pytest.raises(B.AdaTopKError):
+        B.adatopk_plan_keep_counts([0.1], [1e-6], [-1], B.F32, 10.0, 3.0)

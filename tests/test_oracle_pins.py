@@ -285,3 +285,29 @@ def test_k_for_ratio_rounding():
     assert orc.k_for_ratio(1000, 3000.0) == 1  # never fewer than one element
     assert orc.k_for_ratio(0, 10.0) == 0
     assert orc.k_for_ratio(10, 0.5) == -1  # a ratio below 1 is not a compression ratio
+
+
+# ------------------------------------------- link model and pipeline-time estimates (Sec. 3.5, 3.6, 5.2)
+def test_link_and_pipeline_estimates_hand_example():
+    with open(os.path.join(GOLDEN, "pipeline_hand_example.json")) as f:
+        g = json.load(f)
+    ln, pp = g["link"], g["pipeline"]
+    assert math.isclose(orc.link_time(ln["alpha"], ln["beta"], ln["bytes"]), ln["T"], rel_tol=1e-12)
+    assert math.isclose(orc.pipeline_time(pp["C"], pp["R"], pp["n_b"]), pp["time_pipe"], rel_tol=1e-12)
+    assert np.allclose(orc.adaptive_ratios(pp["R"], pp["r"], pp["coeff"]), pp["r_i"], rtol=1e-12)
+    assert math.isclose(orc.pipeline_time_compressed(pp["C"], pp["R"], pp["n_b"], pp["r"], pp["coeff"], 0),
+                        pp["time_pipe_compress_printed"], rel_tol=1e-12)
+    assert math.isclose(orc.pipeline_time_compressed(pp["C"], pp["R"], pp["n_b"], pp["r"], pp["coeff"], 1),
+                        pp["time_pipe_compress_own_ratio"], rel_tol=1e-12)
+    # special cases that follow from the equations: one micro-batch has no bottleneck term; ratio 1/coeff
+    # on equal links sends exactly the uncompressed volume
+    C, R = [0.3, 0.7], [2.0, 2.0]
+    assert math.isclose(orc.pipeline_time(C, R, 1), 5.0, rel_tol=1e-12)
+    assert math.isclose(orc.pipeline_time_compressed(C, R, 1, 1.0 / 3.0 * 3.0, 3.0, 1),
+                        orc.pipeline_time(C, [r_ * 3.0 / 3.0 for r_ in R], 1), rel_tol=1e-12)
+    pl = g["plan"]
+    Rs = [orc.link_time(a, b, 4.0 * n) for a, b, n in zip(pl["alpha"], pl["beta"], pl["n"])]
+    assert np.allclose(Rs, pl["R"], rtol=1e-12)
+    ri = orc.adaptive_ratios(Rs, pl["r"], pl["coeff"])
+    assert np.allclose(ri, pl["r_i"], rtol=1e-12)
+    assert [orc.k_for_ratio(n, r) for n, r in zip(pl["n"], ri)] == pl["k"]
