@@ -24,7 +24,8 @@
  *     and the call returns at once.  Output sizes are known beforehand (exactly k).
  *   - a tensor is its flat contiguous buffer; indices are int32 and local to the
  *     tensor (to the segment in the segmented call), so n must be below 2^31.
- *   - bf16 values travel as 16-bit patterns.
+ *   - bf16 and fp16 (IEEE binary16) values travel as 16-bit patterns; the paper's tensors are
+ *     fp32 (Sec. 5.2), the 16-bit types are the half-width forms of the same operation.
  *   - the workspace is scratch: contents are undefined between calls and it may be
  *     reused by the next call on the same stream.  Calls that share a workspace
  *     must be ordered by the stream.
@@ -41,7 +42,7 @@
 extern "C" {
 #endif
 
-typedef enum { ADATOPK_F32 = 0, ADATOPK_BF16 = 1 } adatopk_dtype;
+typedef enum { ADATOPK_F32 = 0, ADATOPK_BF16 = 1, ADATOPK_F16 = 2 } adatopk_dtype;
 
 typedef enum {
     ADATOPK_OK = 0,
@@ -83,6 +84,18 @@ adatopk_status adatopk_decompress(const int32_t *idx, const void *val, int64_t k
  * stays inside dense_out, but entries may be dropped.  Arguments and errors as above. */
 adatopk_status adatopk_decompress_sorted(const int32_t *idx, const void *val, int64_t k, adatopk_dtype dt,
                                          void *dense_out, int64_t n, void *hip_stream);
+
+/* Accumulating decompression: dense_inout[idx[j]] += val[j], every other entry untouched.  A node
+ * whose gradient is the sum of what several users send back (backward pass of Sec. 3.4: gradients
+ * return to the argument nodes) calls it once per incoming message on a zeroed or running buffer.
+ *   fp32: the fp32 sum.  bf16 / fp16: the exact sum of the two values rounded once to the type,
+ *   to nearest, ties to even.  A NaN sum is stored as some NaN pattern of the type.
+ *   idx, val     device, k entries, indices unique within the call; any order
+ *   dense_inout  device, n values of type dt
+ * Indices outside [0, n) are skipped; with duplicate indices in one call one of the additions may be
+ * lost.  Calls on one buffer must be ordered by the stream.  EINVAL as for decompress. */
+adatopk_status adatopk_decompress_accumulate(const int32_t *idx, const void *val, int64_t k, adatopk_dtype dt,
+                                             void *dense_inout, int64_t n, void *hip_stream);
 
 /* Segmented compress: S independent tensors, tensor s with its own k[s] (the per-link
  * ratios of Sec. 5.2), every pass launched once for all of them.

@@ -12,7 +12,7 @@
  * Sec. 5.2, Eq. "adacompress": the per-link ratio rule):
  *
  *   1. key_i  = bit pattern of x_i with the sign bit cleared, read as an unsigned
- *               integer (31 bits for fp32, 15 bits for bf16).  Ordering keys is
+ *               integer (31 bits for fp32, 15 bits for bf16 and fp16).  Ordering keys is
  *               ordering |x| for every finite value, and extends it to Inf / NaN.
  *   2. sort all (key_i, i) by key descending, then index ascending  (full sort).
  *   3. the first k pairs are the selected set.
@@ -60,6 +60,16 @@ static float bf16_to_f32(uint16_t h) {
     float f;
     memcpy(&f, &u, sizeof f);
     return f;
+}
+
+/* IEEE binary16 -> fp32, exact: 1 sign, 5 exponent (bias 15), 10 fraction bits. */
+float oracle_f16_to_f32(uint16_t h) {
+    const int sign = (h >> 15) & 1, e = (h >> 10) & 0x1F, m = h & 0x3FF;
+    double v;
+    if (e == 0) v = ldexp((double)m, -24);                   /* zero and denormals: m * 2^-24 */
+    else if (e == 31) v = m ? (double)NAN : (double)INFINITY;
+    else v = ldexp((double)(1024 + m), e - 25);              /* (1 + m/1024) * 2^(e-15) */
+    return (float)(sign ? -v : v);
 }
 
 /* Steps 1-4: fills idx[k] (ascending).  keys[] holds key_i for all i.  The caller
@@ -135,6 +145,34 @@ int oracle_compress_bf16(const uint16_t *x, int64_t n, int64_t k, int32_t *idx, 
     return rc;
 }
 
+/* fp16: the key is again the 15 bits below the sign; only the widening for step 5 differs. */
+int oracle_compress_f16(const uint16_t *x, int64_t n, int64_t k, int32_t *idx, uint16_t *val, float *err) {
+    if (n < 0 || k < 0 || k > n || n > INT32_MAX) return -1;
+    uint32_t *keys = (uint32_t *)malloc((size_t)(n > 0 ? n : 1) * sizeof *keys);
+    uint8_t *sel = (uint8_t *)calloc((size_t)(n > 0 ? n : 1), 1);
+    if (!keys || !sel) { free(keys); free(sel); return -1; }
+    for (int64_t i = 0; i < n; ++i) keys[i] = (uint32_t)(x[i] & 0x7FFFu);
+    int rc = select_topk(keys, n, k, idx);
+    if (rc == 0) {
+        for (int64_t j = 0; j < k; ++j) {
+            val[j] = x[idx[j]];
+            sel[idx[j]] = 1;
+        }
+        if (err) {
+            double s = 0.0;
+            for (int64_t i = 0; i < n; ++i)
+                if (!sel[i]) {
+                    double v = (double)oracle_f16_to_f32(x[i]);
+                    s += v * v;
+                }
+            *err = (float)sqrt(s);
+        }
+    }
+    free(keys);
+    free(sel);
+    return rc;
+}
+
 /* Step 6.  Indices must be unique and inside [0, n); anything else is an error. */
 int oracle_decompress_f32(const int32_t *idx, const float *val, int64_t k, float *y, int64_t n) {
     if (n < 0 || k < 0) return -1;
@@ -146,12 +184,79 @@ int oracle_decompress_f32(const int32_t *idx, const float *val, int64_t k, float
     return 0;
 }
 
+/* Any 16-bit type (bf16, fp16): patterns are moved, never interpreted. */
 int oracle_decompress_bf16(const int32_t *idx, const uint16_t *val, int64_t k, uint16_t *y, int64_t n) {
     if (n < 0 || k < 0) return -1;
     memset(y, 0, (size_t)n * sizeof *y);
     for (int64_t j = 0; j < k; ++j) {
         if (idx[j] < 0 || (int64_t)idx[j] >= n) return -1;
         y[idx[j]] = val[j];
+    }
+    return 0;
+}
+
+/* Rounding of a real number to a binary format with p significand bits (hidden bit included) and
+ * normal exponents emin..emax, to nearest, ties to even, by the format's definition: the spacing of
+ * representable numbers around s is 2^(e - p + 1) with e = max(floor(log2 |s|), emin). */
+static double round_to_format(double s, int p, int emin, int emax) {
+    if (s == 0.0 || isnan(s) || isinf(s)) return s;
+    int e;
+    (void)frexp(fabs(s), &e);
+    e -= 1; /* 2^e <= |s| < 2^(e+1) */
+    if (e < emin) e = emin;
+    double quantum = ldexp(1.0, e - (p - 1));
+    double r = rint(s / quantum) * quantum; /* rint: nearest, ties to even, in the default rounding mode */
+    if (fabs(r) >= ldexp(1.0, emax + 1)) r = copysign(INFINITY, s);
+    return r;
+}
+
+/* bf16: 8 significand bits, exponents -126..127; its values are fp32 values with 16 zero low bits. */
+uint16_t oracle_round_bf16(double s) {
+    if (isnan(s)) return 0x7FC0;
+    float f = (float)round_to_format(s, 8, -126, 127); /* exact: every bf16 value is an fp32 value */
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    return (uint16_t)(u >> 16);
+}
+
+/* fp16: 11 significand bits, exponents -14..15. */
+uint16_t oracle_round_f16(double s) {
+    if (isnan(s)) return 0x7E00;
+    double r = round_to_format(s, 11, -14, 15);
+    uint16_t sign = signbit(r) ? 0x8000 : 0;
+    double a = fabs(r);
+    if (isinf(a)) return (uint16_t)(sign | 0x7C00);
+    if (a < ldexp(1.0, -14)) return (uint16_t)(sign | (uint16_t)(a * 16777216.0)); /* a = m * 2^-24 */
+    int e;
+    double f = frexp(a, &e); /* a = f * 2^e with f in [0.5, 1) = (1 + m/1024) * 2^(e-1) */
+    return (uint16_t)(sign | ((uint16_t)(e - 1 + 15) << 10) | (uint16_t)((f * 2.0 - 1.0) * 1024.0));
+}
+
+/* Accumulating decompress: y[idx[j]] += val[j], the exact sum rounded once to the type (to nearest,
+ * ties to even); everything else in y is left alone.  Indices unique and inside [0, n). */
+int oracle_decompress_accumulate_f32(const int32_t *idx, const float *val, int64_t k, float *y, int64_t n) {
+    if (n < 0 || k < 0) return -1;
+    for (int64_t j = 0; j < k; ++j) {
+        if (idx[j] < 0 || (int64_t)idx[j] >= n) return -1;
+        y[idx[j]] = (float)((double)y[idx[j]] + (double)val[j]); /* 53 bits hold the sum well enough to round once */
+    }
+    return 0;
+}
+
+int oracle_decompress_accumulate_bf16(const int32_t *idx, const uint16_t *val, int64_t k, uint16_t *y, int64_t n) {
+    if (n < 0 || k < 0) return -1;
+    for (int64_t j = 0; j < k; ++j) {
+        if (idx[j] < 0 || (int64_t)idx[j] >= n) return -1;
+        y[idx[j]] = oracle_round_bf16((double)bf16_to_f32(y[idx[j]]) + (double)bf16_to_f32(val[j]));
+    }
+    return 0;
+}
+
+int oracle_decompress_accumulate_f16(const int32_t *idx, const uint16_t *val, int64_t k, uint16_t *y, int64_t n) {
+    if (n < 0 || k < 0) return -1;
+    for (int64_t j = 0; j < k; ++j) {
+        if (idx[j] < 0 || (int64_t)idx[j] >= n) return -1;
+        y[idx[j]] = oracle_round_f16((double)oracle_f16_to_f32(y[idx[j]]) + (double)oracle_f16_to_f32(val[j]));
     }
     return 0;
 }
@@ -174,6 +279,16 @@ int oracle_compress_segmented_bf16(const uint16_t *x, const int64_t *in_offset, 
     for (int32_t s = 0; s < S; ++s) {
         int rc = oracle_compress_bf16(x + in_offset[s], in_offset[s + 1] - in_offset[s], k[s],
                                       idx + out_offset[s], val + out_offset[s], err ? err + s : NULL);
+        if (rc) return rc;
+    }
+    return 0;
+}
+
+int oracle_compress_segmented_f16(const uint16_t *x, const int64_t *in_offset, const int64_t *k, int32_t S,
+                                  int32_t *idx, uint16_t *val, const int64_t *out_offset, float *err) {
+    for (int32_t s = 0; s < S; ++s) {
+        int rc = oracle_compress_f16(x + in_offset[s], in_offset[s + 1] - in_offset[s], k[s],
+                                     idx + out_offset[s], val + out_offset[s], err ? err + s : NULL);
         if (rc) return rc;
     }
     return 0;

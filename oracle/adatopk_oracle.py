@@ -4,7 +4,8 @@ TEST INFRASTRUCTURE: only ``tests/``, ``__graft_entry__.smoke()`` and the
 ``cpu_baseline`` leg of ``bench.py`` may import this module.  It holds no arithmetic of
 its own: every function marshals numpy arrays into the C routines, which state the
 method as the paper's Sec. 5.1 (Top-K sparsification figure) and Sec. 5.2
-(Eq. "adacompress") define it.  bf16 tensors travel as ``uint16`` bit patterns.
+(Eq. "adacompress") define it.  bf16 tensors travel as ``uint16`` bit patterns, fp16
+tensors as ``float16`` arrays.
 """
 from __future__ import annotations
 
@@ -37,6 +38,16 @@ def _load():
         i64, i32, p = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
         lib.oracle_compress_f32.argtypes = [p, i64, i64, p, p, p]
         lib.oracle_compress_bf16.argtypes = [p, i64, i64, p, p, p]
+        lib.oracle_compress_f16.argtypes = [p, i64, i64, p, p, p]
+        lib.oracle_compress_segmented_f16.argtypes = [p, p, p, i32, p, p, p, p]
+        lib.oracle_f16_to_f32.argtypes = [ctypes.c_uint16]
+        lib.oracle_f16_to_f32.restype = ctypes.c_float
+        for nm in ("f32", "bf16", "f16"):
+            getattr(lib, "oracle_decompress_accumulate_" + nm).argtypes = [p, p, i64, p, i64]
+        lib.oracle_round_bf16.argtypes = [ctypes.c_double]
+        lib.oracle_round_bf16.restype = ctypes.c_uint16
+        lib.oracle_round_f16.argtypes = [ctypes.c_double]
+        lib.oracle_round_f16.restype = ctypes.c_uint16
         lib.oracle_decompress_f32.argtypes = [p, p, i64, p, i64]
         lib.oracle_decompress_bf16.argtypes = [p, p, i64, p, i64]
         lib.oracle_compress_segmented_f32.argtypes = [p, p, p, i32, p, p, p, p]
@@ -61,9 +72,13 @@ def _ptr(a: np.ndarray):
 
 def _flat(x: np.ndarray) -> np.ndarray:
     x = np.ascontiguousarray(x).reshape(-1)
-    if x.dtype not in (np.float32, np.uint16):
-        raise TypeError("oracle takes float32, or uint16 holding bf16 bit patterns")
+    if x.dtype not in (np.float32, np.uint16, np.float16):
+        raise TypeError("oracle takes float32, float16, or uint16 holding bf16 bit patterns")
     return x
+
+
+def _by_dtype(dt, f32, bf16, f16):
+    return f32 if dt == np.float32 else (bf16 if dt == np.uint16 else f16)
 
 
 def compress(x: np.ndarray, k: int):
@@ -73,7 +88,8 @@ def compress(x: np.ndarray, k: int):
     idx = np.empty(k, dtype=np.int32)
     val = np.empty(k, dtype=x.dtype)
     err = np.zeros(1, dtype=np.float32)
-    fn = _load().oracle_compress_f32 if x.dtype == np.float32 else _load().oracle_compress_bf16
+    L = _load()
+    fn = _by_dtype(x.dtype, L.oracle_compress_f32, L.oracle_compress_bf16, L.oracle_compress_f16)
     rc = fn(_ptr(x), x.size, k, _ptr(idx), _ptr(val), _ptr(err))
     if rc != 0:
         raise ValueError("oracle_compress: bad arguments (n=%d, k=%d)" % (x.size, k))
@@ -91,6 +107,29 @@ def decompress(idx: np.ndarray, val: np.ndarray, n: int) -> np.ndarray:
     return y
 
 
+def decompress_accumulate(idx: np.ndarray, val: np.ndarray, y: np.ndarray) -> np.ndarray:
+    """Returns a copy of y with y[idx[j]] += val[j] (exact sum rounded once to the type)."""
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    val = _flat(val)
+    out = _flat(y).copy()
+    if out.dtype != val.dtype:
+        raise TypeError("y and val must have one dtype")
+    L = _load()
+    fn = _by_dtype(val.dtype, L.oracle_decompress_accumulate_f32, L.oracle_decompress_accumulate_bf16,
+                   L.oracle_decompress_accumulate_f16)
+    if fn(_ptr(idx), _ptr(val), idx.size, _ptr(out), out.size) != 0:
+        raise ValueError("oracle_decompress_accumulate: index out of range or bad sizes")
+    return out
+
+
+def round_bf16(s: float) -> int:
+    return int(_load().oracle_round_bf16(float(s)))
+
+
+def round_f16(s: float) -> int:
+    return int(_load().oracle_round_f16(float(s)))
+
+
 def compress_segmented(xs, ks):
     """Per-tensor compress of a list of tensors.  Returns (idx, val, out_offset, err[S])."""
     xs = [_flat(x) for x in xs]
@@ -106,11 +145,18 @@ def compress_segmented(xs, ks):
     idx = np.empty(int(out_off[S]), dtype=np.int32)
     val = np.empty(int(out_off[S]), dtype=dt)
     err = np.zeros(max(S, 1), dtype=np.float32)
-    fn = _load().oracle_compress_segmented_f32 if dt == np.float32 else _load().oracle_compress_segmented_bf16
+    L = _load()
+    fn = _by_dtype(dt, L.oracle_compress_segmented_f32, L.oracle_compress_segmented_bf16,
+                   L.oracle_compress_segmented_f16)
     rc = fn(_ptr(cat), _ptr(in_off), _ptr(ks), S, _ptr(idx), _ptr(val), _ptr(out_off), _ptr(err))
     if rc != 0:
         raise ValueError("oracle_compress_segmented: bad arguments")
     return idx, val, out_off, err[:S]
+
+
+def f16_to_f32(bits: int) -> float:
+    """IEEE binary16 pattern -> fp32 value, as the oracle widens it for the error norm."""
+    return float(_load().oracle_f16_to_f32(int(bits) & 0xFFFF))
 
 
 def adaptive_ratios(R, r: float, coeff: float = 3.0) -> np.ndarray:

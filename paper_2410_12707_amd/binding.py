@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # different launch-shape constants); the default is the in-tree library.
 LIB_PATH = os.environ.get("ADATOPK_LIBRARY") or os.path.join(_HERE, "libadatopk.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 OK, EINVAL, EWORKSPACE, ERUNTIME, ENOTIMPL = 0, 1, 2, 3, 4
 _STATUS = {OK: "ADATOPK_OK", EINVAL: "ADATOPK_EINVAL", EWORKSPACE: "ADATOPK_EWORKSPACE",
            ERUNTIME: "ADATOPK_ERUNTIME", ENOTIMPL: "ADATOPK_ENOTIMPL"}
@@ -48,6 +48,8 @@ def load_library() -> ctypes.CDLL:
     lib.adatopk_decompress.restype = i32
     lib.adatopk_decompress_sorted.argtypes = [p, p, i64, i32, p, i64, p]
     lib.adatopk_decompress_sorted.restype = i32
+    lib.adatopk_decompress_accumulate.argtypes = [p, p, i64, i32, p, i64, p]
+    lib.adatopk_decompress_accumulate.restype = i32
     lib.adatopk_compress_segmented.argtypes = [p, p, p, i32, i32, p, p, p, p, p, sz, p]
     lib.adatopk_compress_segmented.restype = i32
     lib.adatopk_adaptive_ratios.argtypes = [p, i32, ctypes.c_double, ctypes.c_double, p]
@@ -90,7 +92,9 @@ def _dtype_code(t: torch.dtype) -> int:
         return F32
     if t == torch.bfloat16:
         return BF16
-    raise TypeError("adatopk supports float32 and bfloat16 tensors, got %s" % t)
+    if t == torch.float16:
+        return F16
+    raise TypeError("adatopk supports float32, bfloat16 and float16 tensors, got %s" % t)
 
 
 def _stream() -> int:
@@ -133,6 +137,14 @@ def adatopk_decompress_sorted(idx: torch.Tensor, val: torch.Tensor, k: int, dens
     lib = load_library()
     _check(lib.adatopk_decompress_sorted(_dev(idx), _dev(val), int(k), _dtype_code(dense_out.dtype),
                                          _dev(dense_out), dense_out.numel(), _stream()), "adatopk_decompress_sorted")
+
+
+def adatopk_decompress_accumulate(idx: torch.Tensor, val: torch.Tensor, k: int, dense_inout: torch.Tensor) -> None:
+    """dense_inout[idx[j]] += val[j] for unique indices; every other entry is left alone."""
+    lib = load_library()
+    _check(lib.adatopk_decompress_accumulate(_dev(idx), _dev(val), int(k), _dtype_code(dense_inout.dtype),
+                                             _dev(dense_inout), dense_inout.numel(), _stream()),
+           "adatopk_decompress_accumulate")
 
 
 def adatopk_compress_segmented(dense: Sequence[torch.Tensor], ks: Sequence[int], idx_out: torch.Tensor,

@@ -36,6 +36,7 @@
 // both in one kernel, every workgroup filling its own span and writing the entries that fall in it.
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
+#include <hip/hip_fp16.h>
 
 #include <stdint.h>
 
@@ -125,20 +126,25 @@ struct Launch {
 };
 
 // ------------------------------------------------------------------ element access
-// VEC tags the dtype: 4 = fp32 (one element per dword), 8 = bf16 (two per dword, low half first).
+// VEC tags the dtype: 4 = fp32 (one element per dword), 8 = bf16 and 9 = fp16 (two per dword, low
+// half first).  VEC / 4 is the number of elements in a dword; the two 16-bit types differ only in
+// how a pattern widens to fp32 (for the error norm): both order by their low 15 bits.
+constexpr int TAG_F32 = 4, TAG_BF16 = 8, TAG_F16 = 9;
 template <int VEC> struct Raw;
-template <> struct Raw<4> { using type = uint32_t; };
-template <> struct Raw<8> { using type = uint16_t; };
+template <> struct Raw<TAG_F32> { using type = uint32_t; };
+template <> struct Raw<TAG_BF16> { using type = uint16_t; };
+template <> struct Raw<TAG_F16> { using type = uint16_t; };
 
 template <int VEC> __device__ __forceinline__ uint32_t key_of(uint32_t raw) {
-    return VEC == 4 ? (raw & 0x7FFFFFFFu) : ((raw & 0x7FFFu) << 16);
+    return VEC == TAG_F32 ? (raw & 0x7FFFFFFFu) : ((raw & 0x7FFFu) << 16);
 }
 template <int VEC> __device__ __forceinline__ float value_of(uint32_t raw) {
-    return __uint_as_float(VEC == 4 ? raw : (raw << 16));
+    if (VEC == TAG_F16) return __half2float(__ushort_as_half(static_cast<unsigned short>(raw)));  // exact
+    return __uint_as_float(VEC == TAG_F32 ? raw : (raw << 16));
 }
 // Element h of a loaded dword, as the raw pattern of one element.
 template <int VEC> __device__ __forceinline__ uint32_t elem_of(uint32_t dword, int h) {
-    return VEC == 4 ? dword : ((dword >> (16 * h)) & 0xFFFFu);
+    return VEC == TAG_F32 ? dword : ((dword >> (16 * h)) & 0xFFFFu);
 }
 
 // Streaming layout of the two full-input kernels.  A tile is TILE consecutive elements; wave w
@@ -836,7 +842,8 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
             if (b < B3 || B3 >= NB3) dropped = my_bins[j];
             else if (b == B3) dropped = my_bins[j] - q;
             if (dropped) {
-                const double v = static_cast<double>(__uint_as_float((P << BITS3) | b));
+                const uint32_t key = (P << BITS3) | b;  // 16-bit types carry their pattern in the key's upper half
+                const double v = static_cast<double>(value_of<VEC>(VEC == TAG_F32 ? key : (key >> 16)));
                 part = fma(static_cast<double>(dropped) * v, v, part);
             }
         }
@@ -934,6 +941,30 @@ __global__ __launch_bounds__(BLOCK) void k_scatter(const int32_t *idx, const R *
     if (j >= k) return;
     const int64_t i = idx[j];
     if (i >= 0 && i < n) y[i] = val[j];
+}
+
+// Round an fp32 value to the 16-bit type of the tag, to nearest, ties to even.
+template <int VEC> __device__ __forceinline__ uint32_t narrow_rne(float f) {
+    if (VEC == TAG_F16) return __half_as_ushort(__float2half_rn(f));
+    const uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;  // bf16: add half an ulp of the kept part, less one when it is even
+}
+
+// Accumulating decompress: y[idx[j]] += val[j], one entry per thread.  16-bit types: both operands
+// widened to fp32, added, rounded to nearest even; fp32 is wide enough (24 >= 2 * 11 + 2 bits) for
+// this to be the correctly rounded sum of the two 16-bit values.  Entries of one call must have
+// distinct indices: the read-modify-write is not atomic.
+template <int VEC>
+__global__ __launch_bounds__(BLOCK) void k_scatter_add(const int32_t *idx, const typename Raw<VEC>::type *val, int64_t k,
+                                                       typename Raw<VEC>::type *y, int64_t n) {
+    using R = typename Raw<VEC>::type;
+    const int64_t j = static_cast<int64_t>(blockIdx.x) * BLOCK + threadIdx.x;
+    if (j >= k) return;
+    const int64_t i = idx[j];
+    if (i < 0 || i >= n) return;
+    const float sum = value_of<VEC>(y[i]) + value_of<VEC>(val[j]);
+    y[i] = VEC == TAG_F32 ? static_cast<R>(__float_as_uint(sum)) : static_cast<R>(narrow_rne<VEC>(sum));
 }
 
 // Lower bound by one wavefront: the first j in [0, k) with idx[j] >= value (k if none), for
@@ -1071,7 +1102,7 @@ __global__ __launch_bounds__(BLOCK) void k_read16(const uint4 *src, size_t n16, 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 inline int elem_size(adatopk_dtype dt) { return dt == ADATOPK_F32 ? 4 : 2; }
-inline bool dtype_ok(adatopk_dtype dt) { return dt == ADATOPK_F32 || dt == ADATOPK_BF16; }
+inline bool dtype_ok(adatopk_dtype dt) { return dt == ADATOPK_F32 || dt == ADATOPK_BF16 || dt == ADATOPK_F16; }
 
 int64_t chunk_elems(int64_t n_total, adatopk_dtype dt) {
     (void)dt;
@@ -1248,8 +1279,9 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
             l_base += n[s];
         }
         if (chunks > max_chunks || lbs > max_lb) return ADATOPK_ERUNTIME;  // planner invariant
-        const adatopk_status rc = (dt == ADATOPK_F32) ? launch_batch<4>(a, chunks, lbs, st)
-                                                      : launch_batch<8>(a, chunks, lbs, st);
+        const adatopk_status rc = (dt == ADATOPK_F32)    ? launch_batch<TAG_F32>(a, chunks, lbs, st)
+                                  : (dt == ADATOPK_BF16) ? launch_batch<TAG_BF16>(a, chunks, lbs, st)
+                                                         : launch_batch<TAG_F16>(a, chunks, lbs, st);
         if (rc != ADATOPK_OK) return rc;
     }
     return ADATOPK_OK;
@@ -1320,6 +1352,30 @@ adatopk_status adatopk_decompress(const int32_t *idx, const void *val, int64_t k
             launch(ST_SCATTER, k_scatter<uint16_t>, dim3(grid), st, idx, static_cast<const uint16_t *>(val), k,
                    static_cast<uint16_t *>(dense_out), n);
     }
+    return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
+}
+
+adatopk_status adatopk_decompress_accumulate(const int32_t *idx, const void *val, int64_t k, adatopk_dtype dt,
+                                             void *dense_inout, int64_t n, void *hip_stream) {
+    if (!dtype_ok(dt) || n < 0 || k < 0 || n >= (static_cast<int64_t>(1) << 31)) return ADATOPK_EINVAL;
+    const int es = elem_size(dt);
+    if (n > 0 && (!dense_inout || reinterpret_cast<uintptr_t>(dense_inout) % es)) return ADATOPK_EINVAL;
+    if (k > 0 && (!idx || !val || reinterpret_cast<uintptr_t>(idx) % 4 || reinterpret_cast<uintptr_t>(val) % es))
+        return ADATOPK_EINVAL;
+    if (n == 0 || k == 0) return ADATOPK_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int64_t blocks = (k + BLOCK - 1) / BLOCK;
+    if (blocks > 0x7FFFFFFF) return ADATOPK_EINVAL;
+    const dim3 grid(static_cast<unsigned>(blocks));
+    if (dt == ADATOPK_F32)
+        launch(ST_SCATTER, k_scatter_add<TAG_F32>, grid, st, idx, static_cast<const uint32_t *>(val), k,
+               static_cast<uint32_t *>(dense_inout), n);
+    else if (dt == ADATOPK_BF16)
+        launch(ST_SCATTER, k_scatter_add<TAG_BF16>, grid, st, idx, static_cast<const uint16_t *>(val), k,
+               static_cast<uint16_t *>(dense_inout), n);
+    else
+        launch(ST_SCATTER, k_scatter_add<TAG_F16>, grid, st, idx, static_cast<const uint16_t *>(val), k,
+               static_cast<uint16_t *>(dense_inout), n);
     return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
 }
 

@@ -74,7 +74,7 @@ double adatopk_pipeline_time_compressed(const double *C, const double *R, int32_
 adatopk_status adatopk_plan_keep_counts(const double *alpha, const double *beta, const int64_t *n, int32_t m,
                                         adatopk_dtype dt, double r_user, double coeff, double *r_out,
                                         int64_t *k_out) {
-    if (!alpha || !beta || !n || !k_out || m <= 0 || (dt != ADATOPK_F32 && dt != ADATOPK_BF16))
+    if (!alpha || !beta || !n || !k_out || m <= 0 || (dt != ADATOPK_F32 && dt != ADATOPK_BF16 && dt != ADATOPK_F16))
         return ADATOPK_EINVAL;
     if (!(r_user > 0.0) || !(coeff > 0.0)) return ADATOPK_EINVAL;
     const double bytes_per_value = dt == ADATOPK_F32 ? 4.0 : 2.0;

@@ -6,8 +6,8 @@ The tensors stand in for the ResNet-101 and GPT-2 activations and activation gra
 that cross pipeline cuts in the paper's experiments (Sec. 7, model settings table);
 the datasets and trained weights themselves are not used.
 
-Every generator returns host numpy arrays: float32, or uint16 holding bf16 bit
-patterns.  Seeds are ``12707 + config number`` (config 4 adds ``100 * segment``).
+Every generator returns host numpy arrays: float32, uint16 holding bf16 bit
+patterns, or float16.  Seeds are ``12707 + config number`` (config 4 adds ``100 * segment``).
 """
 from __future__ import annotations
 
@@ -67,12 +67,16 @@ def normal_bf16(n: int, seed: int) -> np.ndarray:
     return f32_to_bf16_bits(normal_f32(n, seed))
 
 
+def normal_f16(n: int, seed: int) -> np.ndarray:
+    return normal_f32(n, seed).astype(np.float16)
+
+
 @dataclass
 class Workload:
     """One benchmark configuration: a list of tensors with one k each."""
 
     name: str
-    dtype: str  # "f32" | "bf16"
+    dtype: str  # "f32" | "bf16" | "f16"
     shape: tuple
     tensors: List[np.ndarray] = field(default_factory=list)
     ks: List[int] = field(default_factory=list)
@@ -165,4 +169,16 @@ def small_case(kind: str, n: int, seed: int, dtype: str = "f32") -> np.ndarray:
         if kind in ("nonfinite", "random_bits"):
             return (x.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
         return f32_to_bf16_bits(x)
+    if dtype == "f16":  # IEEE binary16 as numpy float16 (bf16 travels as uint16, so the two stay apart)
+        if kind == "random_bits":
+            return (x.view(np.uint32) >> np.uint32(16)).astype(np.uint16).view(np.float16)
+        with np.errstate(over="ignore"):
+            h = x.astype(np.float16)  # values past 65504 become Inf: one more tie class
+        if kind == "nonfinite":  # fp32 denormals round to 0 in binary16: plant binary16 denormals and NaN payloads
+            u = h.view(np.uint16)
+            pick = _rng(seed + 1).random(n)
+            u[pick < 0.02] = _rng(seed + 2).integers(1, 1 << 10, size=n, dtype=np.uint16)[pick < 0.02]
+            u[(pick >= 0.02) & (pick < 0.03)] = 0x7E00
+            u[(pick >= 0.03) & (pick < 0.04)] = 0xFD55
+        return h
     return x

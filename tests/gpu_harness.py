@@ -5,11 +5,17 @@ import torch
 from paper_2410_12707_amd import binding as B
 
 
+def torch_dtype(np_dtype) -> torch.dtype:
+    """float32 -> float32, float16 -> float16, uint16 (bf16 bit patterns) -> bfloat16."""
+    return {np.dtype(np.float32): torch.float32, np.dtype(np.float16): torch.float16,
+            np.dtype(np.uint16): torch.bfloat16}[np.dtype(np_dtype)]
+
+
 def to_device(x: np.ndarray, offset_elems: int = 0) -> torch.Tensor:
-    """float32 stays float32; uint16 bit patterns become a bfloat16 tensor.  offset_elems > 0
-    places the tensor that many elements past a fresh allocation (a misaligned base)."""
+    """float32 and float16 keep their type; uint16 bit patterns become a bfloat16 tensor.
+    offset_elems > 0 places the tensor that many elements past a fresh allocation (a misaligned base)."""
     x = np.ascontiguousarray(x).reshape(-1)
-    tdt = torch.float32 if x.dtype == np.float32 else torch.bfloat16
+    tdt = torch_dtype(x.dtype)
     host = torch.from_numpy(x.view(np.int16)).view(torch.bfloat16) if x.dtype == np.uint16 else torch.from_numpy(x)
     buf = torch.empty(x.size + offset_elems, dtype=tdt, device="cuda")
     view = buf[offset_elems:]
@@ -44,7 +50,7 @@ def gpu_compress(x: np.ndarray, k: int, offset_elems: int = 0, want_err: bool = 
 def gpu_decompress(idx: np.ndarray, val: np.ndarray, n: int, offset_elems: int = 0, sorted_call: bool = False) -> np.ndarray:
     k = int(idx.size)
     di = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)).cuda() if k else torch.zeros(1, dtype=torch.int32, device="cuda")
-    dv = to_device(val) if k else torch.zeros(1, dtype=torch.float32 if val.dtype == np.float32 else torch.bfloat16, device="cuda")
+    dv = to_device(val) if k else torch.zeros(1, dtype=torch_dtype(val.dtype), device="cuda")
     buf = torch.full((n + offset_elems + 8,), 7.0, dtype=dv.dtype, device="cuda")  # poisoned; 8 guard elements
     out = buf[offset_elems:offset_elems + n]
     (B.adatopk_decompress_sorted if sorted_call else B.adatopk_decompress)(di, dv, k, out)

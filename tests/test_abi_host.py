@@ -43,6 +43,7 @@ def test_workspace_bytes(lib):
     assert 0 < small < big
     assert big >= 25_165_824 * 8  # the candidate list can hold every element (all-equal input)
     assert lib.adatopk_workspace_bytes(25_165_824, 1, 1) < big  # bf16 values are half the size
+    assert lib.adatopk_workspace_bytes(25_165_824, 1, 2) == lib.adatopk_workspace_bytes(25_165_824, 1, 1)  # fp16 too
     assert lib.adatopk_workspace_bytes(201_326_592, 24, 0) >= 201_326_592 * 8
 
 
@@ -60,6 +61,7 @@ def test_compress_rejects_bad_arguments_before_touching_the_device(lib):
     assert c(fake, 1000, 0, 10, None, fake, None, ws, need, None) == EINVAL
     assert c(fake + 2, 1000, 0, 10, fake, fake, None, ws, need, None) == EINVAL  # fp32 at 2 mod 4
     assert c(fake + 1, 1000, 1, 10, fake, fake, None, ws, need, None) == EINVAL  # bf16 at odd address
+    assert c(fake + 1, 1000, 2, 10, fake, fake, None, ws, need, None) == EINVAL  # fp16 at odd address
     assert c(fake, 1000, 0, 10, fake, fake, None, None, need, None) == EINVAL
     assert c(fake, 1000, 0, 10, fake, fake, None, ws + 8, need, None) == EINVAL  # workspace alignment
     assert c(fake, 1000, 0, 10, fake, fake, None, ws, need - 1, None) == EWORKSPACE

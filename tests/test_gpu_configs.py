@@ -70,3 +70,10 @@ def test_config5_bf16_ties_at_threshold():
     taken = int(np.count_nonzero((rv & np.uint16(0x7FFF)) == kmin))
     print("config5: %d elements tie at the threshold key 0x%04x, %d of them kept" % (tied, kmin, taken))
     assert tied > 1000 and 0 < taken < tied
+
+
+def test_config5_shape_in_fp16():
+    # the GPT-2-XL hidden activation of config 5 in IEEE binary16: 10 fraction bits, so fewer ties than bf16
+    n = 16 * 1024 * 1600
+    x = wl.normal_f16(n, wl.BASE_SEED + 5)
+    full_check(x, wl.keep_count(n, 5, 1000))

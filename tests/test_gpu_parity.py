@@ -34,7 +34,7 @@ def ks_for(n):
     return sorted({0, 1, n // 100, n // 3, n - 1, n} & set(range(0, n + 1)))
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("kind", ["normal", "few_levels", "all_equal", "all_zero", "signed_zero_mix", "sparse",
                                   "nonfinite", "random_bits", "descending"])
 def test_small_and_ragged_sizes(kind, dtype):
@@ -46,7 +46,7 @@ def test_small_and_ragged_sizes(kind, dtype):
             check_one(x, k, label="%s %s n=%d k=%d" % (kind, dtype, n, k))
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_many_chunks_and_tiles(dtype):
     # 3.3M elements: hundreds of chunks, several tiles each, ragged last chunk
     n = 3_300_017
@@ -54,7 +54,7 @@ def test_many_chunks_and_tiles(dtype):
         check_one(wl.small_case(kind, n, seed=77, dtype=dtype), k, label="%s %s" % (kind, dtype))
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_misaligned_base_pointer(dtype):
     n = 40_003
     x = wl.small_case("normal", n, seed=5, dtype=dtype)
@@ -142,9 +142,72 @@ def test_segmented_more_segments_than_one_launch_holds():
 
     rng = np.random.Generator(np.random.PCG64(17))
     lens = rng.integers(1, 30_000, size=70).tolist()
-    xs = [wl.small_case("normal", n, seed=500 + i, dtype="bf16") for i, n in enumerate(lens)]
-    ks = [max(1, n // 13) for n in lens]
-    gi, gv, off, ge = H.gpu_compress_segmented(xs, ks)
-    ri, rv, roff, re = orc.compress_segmented(xs, ks)
-    assert np.array_equal(gi, ri) and np.array_equal(H.bits(gv), H.bits(rv))
-    assert all(H.same_err(ge[s], re[s], ERR_RTOL) for s in range(len(xs)))
+    for dtype in ("bf16", "f16"):
+        xs = [wl.small_case("normal", n, seed=500 + i, dtype=dtype) for i, n in enumerate(lens)]
+        ks = [max(1, n // 13) for n in lens]
+        gi, gv, off, ge = H.gpu_compress_segmented(xs, ks)
+        ri, rv, roff, re = orc.compress_segmented(xs, ks)
+        assert np.array_equal(gi, ri) and np.array_equal(H.bits(gv), H.bits(rv))
+        assert all(H.same_err(ge[s], re[s], ERR_RTOL) for s in range(len(xs)))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_decompress_accumulate(dtype):
+    import torch
+
+    import gpu_harness as H
+    from paper_2410_12707_amd import binding as B
+
+    rng = np.random.Generator(np.random.PCG64(71))
+    for n, k, kind in ((1, 1, "normal"), (70_001, 700, "normal"), (1_000_003, 1_000_003, "normal"),
+                       (300_000, 40_000, "few_levels"), (50_000, 5_000, "nonfinite")):
+        y = wl.small_case(kind, n, seed=72 + n, dtype=dtype)
+        val = wl.small_case(kind, k, seed=73 + n, dtype=dtype)
+        idx = rng.permutation(n)[:k].astype(np.int32)
+        ref = orc.decompress_accumulate(idx, val, y)
+        dy, dv = H.to_device(y, 1), H.to_device(val)
+        B.adatopk_decompress_accumulate(torch.from_numpy(idx).cuda(), dv, k, dy)
+        torch.cuda.synchronize()
+        got = H.to_host(dy)
+        if dtype == "f32":
+            nan = np.isnan(ref)
+            gnan = np.isnan(got)
+        else:  # 16-bit: exponent all ones and a non-zero fraction
+            frac = np.uint16(0x007F if dtype == "bf16" else 0x03FF)
+            expo = np.uint16(0x7F80 if dtype == "bf16" else 0x7C00)
+            nan = ((H.bits(ref) & expo) == expo) & ((H.bits(ref) & frac) != 0)
+            gnan = ((H.bits(got) & expo) == expo) & ((H.bits(got) & frac) != 0)
+        assert np.array_equal(nan, gnan), (dtype, n, k, kind)  # a NaN sum may carry any payload
+        assert np.array_equal(H.bits(got)[~nan], H.bits(ref)[~nan]), (dtype, n, k, kind)
+    # out-of-range indices are skipped, k = 0 is a no-op
+    y = wl.small_case("normal", 1000, seed=1, dtype=dtype)
+    dy = H.to_device(y)
+    bad = np.array([-1, 1000, 5, 2_000_000_000], dtype=np.int32)
+    val = wl.small_case("normal", 4, seed=2, dtype=dtype)
+    B.adatopk_decompress_accumulate(torch.from_numpy(bad).cuda(), H.to_device(val), 4, dy)
+    B.adatopk_decompress_accumulate(torch.from_numpy(bad).cuda(), H.to_device(val), 0, dy)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.bits(H.to_host(dy)), H.bits(orc.decompress_accumulate(bad[2:3], val[2:3], y)))
+
+
+def test_two_incoming_gradients_sum_like_the_oracle():
+    # a node with two users (backward pass): compress each incoming gradient, accumulate both
+    import torch
+
+    import gpu_harness as H
+    from paper_2410_12707_amd import binding as B
+
+    n, k = 2_000_003, 20_000
+    gs = [wl.small_case("normal", n, seed=80 + i) for i in range(2)]
+    acc_ref = np.zeros(n, dtype=np.float32)
+    acc = torch.zeros(n, dtype=torch.float32, device="cuda")
+    ws = B.new_workspace(n, 1, torch.float32)
+    for g in gs:
+        ri, rv, _ = orc.compress(g, k)
+        acc_ref = orc.decompress_accumulate(ri, rv, acc_ref)
+        idx = torch.empty(k, dtype=torch.int32, device="cuda")
+        val = torch.empty(k, dtype=torch.float32, device="cuda")
+        B.adatopk_compress(H.to_device(g), k, idx, val, None, ws)
+        B.adatopk_decompress_accumulate(idx, val, k, acc)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.bits(H.to_host(acc)), H.bits(acc_ref))

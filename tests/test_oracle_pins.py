@@ -24,7 +24,7 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 # ----------------------------------------------------------------------------- helpers
 def magnitudes(x):
-    """|x| as float64 for finite inputs (fp32 array, or uint16 bf16 bit patterns)."""
+    """|x| as float64 for finite inputs (fp32 or fp16 array, or uint16 bf16 bit patterns)."""
     if x.dtype == np.uint16:
         x = wl.bf16_bits_to_f32(x)
     return np.abs(x.astype(np.float64))
@@ -53,7 +53,7 @@ KINDS = ["normal", "few_levels", "all_equal", "sparse", "signed_zero_mix", "desc
 
 
 # ----------------------------------------------------------------------- brute force
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("kind", KINDS)
 def test_selection_matches_repeated_argmax(kind, dtype):
     for n in (1, 2, 7, 64, 193):
@@ -67,7 +67,7 @@ def test_selection_matches_repeated_argmax(kind, dtype):
             assert np.array_equal(bits(val), bits(x)[idx])
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_selection_is_optimal_and_lexicographically_first_over_all_subsets(dtype):
     # For n <= 10 enumerate every k-subset: the chosen one must have the largest multiset
     # of magnitudes (compared as sorted-descending tuples) and, among those, the smallest
@@ -87,7 +87,7 @@ def test_selection_is_optimal_and_lexicographically_first_over_all_subsets(dtype
 
 
 # ------------------------------------------------------------------------- invariants
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("kind", ["normal", "few_levels", "sparse", "nonfinite", "random_bits"])
 def test_selection_invariants(kind, dtype):
     n = 50_021
@@ -127,7 +127,7 @@ def test_distinct_magnitudes_agree_with_numpy_and_torch():
         assert np.array_equal(idx, ref_t)
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_lexsort_statement_of_the_definition(dtype):
     # Same definition through numpy's lexsort (key descending, index ascending), with ties.
     for kind in ("few_levels", "normal", "sparse"):
@@ -141,7 +141,7 @@ def test_lexsort_statement_of_the_definition(dtype):
 
 
 # ---------------------------------------------------------------------- closed forms
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_closed_forms(dtype):
     n = 1000
     eq = wl.small_case("all_equal", n, 0, dtype)
@@ -184,8 +184,29 @@ def test_nonfinite_ordering_and_bit_exact_values():
     assert val.view(np.uint32)[3] == 1  # denormal kept bit-exact (no flush to zero)
 
 
+def test_fp16_widening_matches_numpy_for_every_pattern():
+    # The oracle widens binary16 by the format's definition; numpy's float16 is the independent reading.
+    pats = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+    ref = pats.view(np.float16).astype(np.float32)
+    got = np.array([orc.f16_to_f32(int(p)) for p in pats], dtype=np.float32)
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), ref[~nan].view(np.uint32))
+
+
+def test_fp16_denormals_extremes_and_hand_error():
+    # 2^-24 (smallest denormal), 2^-14 (smallest normal), 65504 (largest finite), -Inf, -2^-24
+    u = np.array([0x0001, 0x0400, 0x7BFF, 0xFC00, 0x8001], dtype=np.uint16)
+    x = u.view(np.float16)
+    idx, val, err = orc.compress(x, 2)
+    assert idx.tolist() == [2, 3] and val.view(np.uint16).tolist() == [0x7BFF, 0xFC00]
+    assert math.isclose(float(err), math.sqrt(2.0 ** -48 + 2.0 ** -28 + 2.0 ** -48), rel_tol=1e-7)
+    idx, _, err = orc.compress(x, 4)  # the two denormals tie: lowest index
+    assert idx.tolist() == [0, 1, 2, 3] and math.isclose(float(err), 2.0 ** -24, rel_tol=1e-7)
+
+
 # -------------------------------------------------------------------- reconstruction
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("kind", ["normal", "few_levels", "nonfinite"])
 def test_decompress_is_the_masked_input(kind, dtype):
     n = 10_007
@@ -211,8 +232,89 @@ def test_decompress_accepts_any_order_and_rejects_out_of_range():
         orc.decompress(np.array([6], dtype=np.int32), val[:1], 6)
 
 
+# ---------------------------------------------------------------- accumulating decompress
+def test_rounding_to_fp16_matches_numpy_on_ties_and_random_values():
+    pats = np.arange(0x7C00, dtype=np.uint32).astype(np.uint16)  # every non-negative finite value, ascending
+    v = pats.view(np.float16).astype(np.float64)
+    mids = (v[:-1] + v[1:]) / 2  # exact in fp64: the ties between neighbours
+    rng = np.random.Generator(np.random.PCG64(61))
+    rnd = rng.standard_normal(20000) * np.exp(rng.uniform(-20, 12, 20000))
+    probe = np.concatenate([v, mids, np.nextafter(mids, 0), np.nextafter(mids, np.inf), rnd, [65519.9, 65520.0, 1e9]])
+    probe = np.concatenate([probe, -probe])
+    with np.errstate(over="ignore"):
+        ref = probe.astype(np.float16).view(np.uint16)
+    got = np.array([orc.round_f16(float(t)) for t in probe], dtype=np.uint16)
+    assert np.array_equal(got, ref)
+
+
+def test_rounding_to_bf16_matches_torch_on_ties_and_random_values():
+    import torch
+
+    rng = np.random.Generator(np.random.PCG64(62))
+    pats = rng.integers(0, 0x7F7F, size=4000, dtype=np.uint32).astype(np.uint16)  # finite bf16 values
+    lo = wl.bf16_bits_to_f32(pats).astype(np.float64)
+    hi = wl.bf16_bits_to_f32(pats + np.uint16(1)).astype(np.float64)
+    mids = ((lo + hi) / 2).astype(np.float32)  # ties are fp32 values: one more bit than bf16
+    rnd = (rng.standard_normal(20000) * np.exp(rng.uniform(-80, 80, 20000))).astype(np.float32)
+    probe = np.concatenate([mids, np.nextafter(mids, np.float32(0)), np.nextafter(mids, np.float32(np.inf)), rnd,
+                            np.array([3.3895e38, 3.4e38, 1e-40, 4.6e-41, 0.0], dtype=np.float32)])
+    probe = np.concatenate([probe, -probe])
+    ref = torch.from_numpy(probe).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = np.array([orc.round_bf16(float(t)) for t in probe], dtype=np.uint16)
+    assert np.array_equal(got, ref)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_accumulate_matches_library_addition(dtype):
+    import torch
+
+    n, k = 20_011, 3_000
+    rng = np.random.Generator(np.random.PCG64(63))
+    y = wl.small_case("normal", n, seed=64, dtype=dtype)
+    val = wl.small_case("normal", k, seed=65, dtype=dtype)
+    idx = rng.permutation(n)[:k].astype(np.int32)
+    got = orc.decompress_accumulate(idx, val, y)
+    if dtype == "bf16":
+        t = torch.from_numpy(y.view(np.int16).copy()).view(torch.bfloat16)
+        t[torch.from_numpy(idx.astype(np.int64))] += torch.from_numpy(val.view(np.int16).copy()).view(torch.bfloat16)
+        ref = t.view(torch.int16).numpy().view(np.uint16)
+    else:
+        ref = y.copy()
+        ref[idx] += val  # numpy's own addition in the type
+    assert np.array_equal(bits(got), bits(ref))
+    untouched = np.ones(n, dtype=bool)
+    untouched[idx] = False
+    assert np.array_equal(bits(got)[untouched], bits(y)[untouched])
+
+
+def test_accumulate_hand_examples_and_sum_of_two_messages():
+    # bf16 has 8 significand bits: 1 + 2^-8 is a tie and goes to even (1.0); 1 + 2^-7 + 2^-8 goes up to 1 + 2^-6
+    y = np.array([0x3F80, 0x3F81, 0x7F7F, 0x0001, 0x3F80], dtype=np.uint16)  # 1, 1+2^-7, max finite, min denormal, 1
+    v = np.array([0x3B80, 0x3B80, 0x7F7F, 0x0001, 0xBF80], dtype=np.uint16)  # 2^-8, 2^-8, max finite, min denormal, -1
+    out = orc.decompress_accumulate(np.arange(5, dtype=np.int32), v, y)
+    assert out.tolist() == [0x3F80, 0x3F82, 0x7F80, 0x0002, 0x0000]
+    # fp16: 2048 + 1 is a tie (spacing 2 there) and goes to even 2048; 2050 + 1 goes up to 2052; 65504 + 32 overflows
+    yh = np.array([2048.0, 2050.0, 65504.0, 6e-8], dtype=np.float16)
+    vh = np.array([1.0, 1.0, 32.0, 6e-8], dtype=np.float16)
+    outh = orc.decompress_accumulate(np.arange(4, dtype=np.int32), vh, yh)
+    assert outh[:2].tolist() == [2048.0, 2052.0] and np.isinf(outh[2]) and outh.view(np.uint16)[3] == 2
+    # a node with two users: the two compressed gradients add up where both kept an entry
+    n = 1000
+    g1 = np.zeros(n, dtype=np.float32)
+    g2 = np.zeros(n, dtype=np.float32)
+    g1[[3, 500, 999]] = [4.0, -2.0, 8.0]
+    g2[[3, 7, 999]] = [0.5, 16.0, -8.0]
+    acc = np.zeros(n, dtype=np.float32)
+    for g in (g1, g2):
+        idx, val, _ = orc.compress(g, 3)
+        acc = orc.decompress_accumulate(idx, val, acc)
+    assert np.array_equal(acc, g1 + g2)
+    with pytest.raises(ValueError):
+        orc.decompress_accumulate(np.array([n], dtype=np.int32), np.ones(1, np.float32), acc)
+
+
 # ------------------------------------------------------------------------ error norm
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_error_norm_identity_in_fp64(dtype):
     n = 200_003
     x = wl.small_case("normal", n, seed=33, dtype=dtype)
