@@ -86,7 +86,7 @@ adatopk_status adatopk_decompress_sorted(const int32_t *idx, const void *val, in
                                          void *dense_out, int64_t n, void *hip_stream);
 
 /* Accumulating decompression: dense_inout[idx[j]] += val[j], every other entry untouched.  A node
- * whose gradient is the sum of what several users send back (backward pass of Sec. 3.4: gradients
+ * whose gradient is the sum of what several users send back (backward pass of Sec. 3.3: gradients
  * return to the argument nodes) calls it once per incoming message on a zeroed or running buffer.
  *   fp32: the fp32 sum.  bf16 / fp16: the exact sum of the two values rounded once to the type,
  *   to nearest, ties to even.  A NaN sum is stored as some NaN pattern of the type.
@@ -112,6 +112,68 @@ adatopk_status adatopk_compress_segmented(const void *const *dense, const int64_
                                           int32_t S, adatopk_dtype dt, int32_t *idx_out, void *val_out,
                                           const int64_t *out_offset, float *err_norm_out,
                                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* ---- Wire message.  What one compressed tensor looks like on the link: the (index, value) pairs
+ * of Sec. 5.1 behind a fixed header that carries what the paper's message descriptor keeps for
+ * compression (its Compress_cfg field, Sec. 3.4: the algorithm, the ratio, further parameters).
+ * One contiguous buffer, little-endian:
+ *     [0, 64)                         adatopk_wire_header
+ *     [64, 64 + k * index_bytes)      indices, ascending; int32, or int64 as in the paper's own
+ *                                     accounting (fp32 value + int64 index = 3 x the kept values, Sec. 5.2)
+ *     padding with zeros to a multiple of 16
+ *     [val_offset, val_offset + k * sizeof(value))   values
+ * so the message of k pairs is adatopk_wire_bytes(k, dt, index_bytes) long and k follows from the
+ * length (adatopk_wire_keep_count). */
+#define ADATOPK_WIRE_MAGIC 0x314B5441u /* "ATK1" */
+#define ADATOPK_WIRE_VERSION 1
+#define ADATOPK_WIRE_TOPK 1 /* algorithm: top-k by magnitude */
+
+typedef struct {
+    uint32_t magic;
+    uint16_t version;
+    uint8_t algorithm;
+    uint8_t dtype;       /* adatopk_dtype of the values */
+    uint8_t index_bytes; /* 4 or 8 */
+    uint8_t reserved0[3];
+    float err_norm;      /* L2 norm of the dropped part, written by the compress kernels */
+    int64_t n;           /* elements of the dense tensor */
+    int64_t k;           /* pairs in the message */
+    double ratio;        /* the link's ratio r_i (Eq. "adacompress") that k was derived from; informational */
+    int64_t idx_offset;  /* = 64 */
+    int64_t val_offset;
+    uint8_t reserved1[8];
+} adatopk_wire_header; /* 64 bytes */
+
+/* Host-only.  Message length for k pairs; 0 for invalid arguments (k < 0, k >= 2^31, unknown dt,
+ * index_bytes not 4 or 8). */
+size_t adatopk_wire_bytes(int64_t k, adatopk_dtype dt, int32_t index_bytes);
+
+/* Host-only.  The k whose message is exactly wire_bytes long, or -1 if there is none. */
+int64_t adatopk_wire_keep_count(size_t wire_bytes, adatopk_dtype dt, int32_t index_bytes);
+
+/* Host-only.  Checks the first 64 bytes of a message held in HOST memory (a receiver has them
+ * there before it uploads the message) against the message length and copies them to *out.
+ * EINVAL: wrong magic / version / algorithm / dtype / index width, k > n, offsets or length that
+ * do not fit k. */
+adatopk_status adatopk_wire_parse_header(const void *host_bytes, size_t wire_bytes, adatopk_wire_header *out);
+
+/* adatopk_compress with the outputs laid out as one wire message.
+ *   wire_out       device, 16-byte aligned, wire_capacity >= adatopk_wire_bytes(k, dt, index_bytes) bytes
+ *   index_bytes    4, or 8 for int64 indices
+ *   ratio          stored in the header as given
+ * Everything else as adatopk_compress; EINVAL also for a buffer that is too small or misaligned. */
+adatopk_status adatopk_compress_wire(const void *dense, int64_t n, adatopk_dtype dt, int64_t k, int32_t index_bytes,
+                                     double ratio, void *wire_out, size_t wire_capacity, void *workspace,
+                                     size_t workspace_bytes, void *hip_stream);
+
+/* Decompression of a wire message in device memory.  The receiver knows dt, index_bytes and n (the
+ * tensor's shape is part of the graph); k follows from wire_bytes.  The device-side header is not
+ * read: parse it on the host before the upload if it is to be checked.
+ *   accumulate == 0   dense = decompress(message)  (as adatopk_decompress_sorted)
+ *   accumulate != 0   dense += decompress(message) (as adatopk_decompress_accumulate)
+ * EINVAL: no k fits wire_bytes, k > n, misaligned or NULL buffers. */
+adatopk_status adatopk_decompress_wire(const void *wire, size_t wire_bytes, adatopk_dtype dt, int32_t index_bytes,
+                                       int64_t n, int32_t accumulate, void *dense, void *hip_stream);
 
 /* Host-only: the adaptive ratio rule, Sec. 5.2, Eq. "adacompress":
  *   r_out[i] = max(1, coeff * r_user * R[i] / max_p R[p])

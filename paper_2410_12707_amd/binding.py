@@ -50,6 +50,16 @@ def load_library() -> ctypes.CDLL:
     lib.adatopk_decompress_sorted.restype = i32
     lib.adatopk_decompress_accumulate.argtypes = [p, p, i64, i32, p, i64, p]
     lib.adatopk_decompress_accumulate.restype = i32
+    lib.adatopk_wire_bytes.argtypes = [i64, i32, i32]
+    lib.adatopk_wire_bytes.restype = sz
+    lib.adatopk_wire_keep_count.argtypes = [sz, i32, i32]
+    lib.adatopk_wire_keep_count.restype = i64
+    lib.adatopk_wire_parse_header.argtypes = [p, sz, p]
+    lib.adatopk_wire_parse_header.restype = i32
+    lib.adatopk_compress_wire.argtypes = [p, i64, i32, i64, i32, ctypes.c_double, p, sz, p, sz, p]
+    lib.adatopk_compress_wire.restype = i32
+    lib.adatopk_decompress_wire.argtypes = [p, sz, i32, i32, i64, i32, p, p]
+    lib.adatopk_decompress_wire.restype = i32
     lib.adatopk_compress_segmented.argtypes = [p, p, p, i32, i32, p, p, p, p, p, sz, p]
     lib.adatopk_compress_segmented.restype = i32
     lib.adatopk_adaptive_ratios.argtypes = [p, i32, ctypes.c_double, ctypes.c_double, p]
@@ -145,6 +155,48 @@ def adatopk_decompress_accumulate(idx: torch.Tensor, val: torch.Tensor, k: int, 
     _check(lib.adatopk_decompress_accumulate(_dev(idx), _dev(val), int(k), _dtype_code(dense_inout.dtype),
                                              _dev(dense_inout), dense_inout.numel(), _stream()),
            "adatopk_decompress_accumulate")
+
+
+class WireHeader(ctypes.Structure):
+    """Mirror of adatopk_wire_header (64 bytes)."""
+    _fields_ = [("magic", ctypes.c_uint32), ("version", ctypes.c_uint16), ("algorithm", ctypes.c_uint8),
+                ("dtype", ctypes.c_uint8), ("index_bytes", ctypes.c_uint8), ("reserved0", ctypes.c_uint8 * 3),
+                ("err_norm", ctypes.c_float), ("n", ctypes.c_int64), ("k", ctypes.c_int64),
+                ("ratio", ctypes.c_double), ("idx_offset", ctypes.c_int64), ("val_offset", ctypes.c_int64),
+                ("reserved1", ctypes.c_uint8 * 8)]
+
+
+def adatopk_wire_bytes(k: int, dtype_code: int, index_bytes: int) -> int:
+    return int(load_library().adatopk_wire_bytes(int(k), int(dtype_code), int(index_bytes)))
+
+
+def adatopk_wire_keep_count(wire_bytes: int, dtype_code: int, index_bytes: int) -> int:
+    return int(load_library().adatopk_wire_keep_count(int(wire_bytes), int(dtype_code), int(index_bytes)))
+
+
+def adatopk_wire_parse_header(host_bytes: bytes, wire_bytes: int) -> WireHeader:
+    """Checks the first 64 bytes of a message held in host memory; raises AdaTopKError if they do not fit."""
+    h = WireHeader()
+    buf = ctypes.create_string_buffer(bytes(host_bytes[:64]), 64) if len(host_bytes) >= 64 else None
+    _check(load_library().adatopk_wire_parse_header(buf, int(wire_bytes), ctypes.byref(h)), "adatopk_wire_parse_header")
+    return h
+
+
+def adatopk_compress_wire(dense: torch.Tensor, k: int, index_bytes: int, ratio: float, wire_out: torch.Tensor,
+                          workspace: torch.Tensor) -> None:
+    """adatopk_compress writing one wire message into the uint8 tensor wire_out."""
+    lib = load_library()
+    _check(lib.adatopk_compress_wire(_dev(dense), dense.numel(), _dtype_code(dense.dtype), int(k), int(index_bytes),
+                                     float(ratio), _dev(wire_out), wire_out.numel() * wire_out.element_size(),
+                                     _dev(workspace), workspace.numel(), _stream()), "adatopk_compress_wire")
+
+
+def adatopk_decompress_wire(wire: torch.Tensor, wire_bytes: int, index_bytes: int, dense: torch.Tensor,
+                            accumulate: bool = False) -> None:
+    lib = load_library()
+    _check(lib.adatopk_decompress_wire(_dev(wire), int(wire_bytes), _dtype_code(dense.dtype), int(index_bytes),
+                                       dense.numel(), 1 if accumulate else 0, _dev(dense), _stream()),
+           "adatopk_decompress_wire")
 
 
 def adatopk_compress_segmented(dense: Sequence[torch.Tensor], ks: Sequence[int], idx_out: torch.Tensor,

@@ -39,6 +39,8 @@
 #include <hip/hip_fp16.h>
 
 #include <stdint.h>
+#include <stddef.h>
+#include <string.h>
 
 #include "adatopk.h"
 #include "adatopk_measure.h"
@@ -120,9 +122,10 @@ struct Launch {
     double *lerr;                              // [list blocks] squares of list entries below the 21-bit prefix
     int32_t *L_idx;
     void *L_val;
-    int32_t *idx_out;
+    void *idx_out;     // int32 entries, or int64 when idx64 is set (the paper's index width, Sec. 5.2)
     void *val_out;
     float *err_out;
+    uint32_t idx64;
 };
 
 // ------------------------------------------------------------------ element access
@@ -874,7 +877,9 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
 
     const int32_t *Li = a.L_idx + sg.l_base;
     const R *Lv = static_cast<const R *>(a.L_val) + sg.l_base;
-    int32_t *oi = a.idx_out + sg.out_off;
+    int32_t *oi = static_cast<int32_t *>(a.idx_out) + sg.out_off;
+    int64_t *oi64 = static_cast<int64_t *>(a.idx_out) + sg.out_off;
+    const bool wide = a.idx64 != 0;
     R *ov = static_cast<R *>(a.val_out) + sg.out_off;
 
     int buf = 0;
@@ -911,7 +916,8 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
             if (cls[j] == 2u || (cls[j] == 1u && eq_before < q)) {
                 const uint32_t pos = gt_before + (eq_before < q ? eq_before : q);
                 if (pos < kout) {
-                    oi[pos] = id[j];
+                    if (wide) oi64[pos] = id[j];
+                    else oi[pos] = id[j];
                     ov[pos] = static_cast<R>(raw[j]);
                 }
             }
@@ -935,8 +941,8 @@ __global__ __launch_bounds__(BLOCK) void k_fill(unsigned char *dst, size_t bytes
     }
 }
 
-template <typename R>
-__global__ __launch_bounds__(BLOCK) void k_scatter(const int32_t *idx, const R *val, int64_t k, R *y, int64_t n) {
+template <typename R, typename I>
+__global__ __launch_bounds__(BLOCK) void k_scatter(const I *idx, const R *val, int64_t k, R *y, int64_t n) {
     const int64_t j = static_cast<int64_t>(blockIdx.x) * BLOCK + threadIdx.x;
     if (j >= k) return;
     const int64_t i = idx[j];
@@ -955,8 +961,8 @@ template <int VEC> __device__ __forceinline__ uint32_t narrow_rne(float f) {
 // widened to fp32, added, rounded to nearest even; fp32 is wide enough (24 >= 2 * 11 + 2 bits) for
 // this to be the correctly rounded sum of the two 16-bit values.  Entries of one call must have
 // distinct indices: the read-modify-write is not atomic.
-template <int VEC>
-__global__ __launch_bounds__(BLOCK) void k_scatter_add(const int32_t *idx, const typename Raw<VEC>::type *val, int64_t k,
+template <int VEC, typename I>
+__global__ __launch_bounds__(BLOCK) void k_scatter_add(const I *idx, const typename Raw<VEC>::type *val, int64_t k,
                                                        typename Raw<VEC>::type *y, int64_t n) {
     using R = typename Raw<VEC>::type;
     const int64_t j = static_cast<int64_t>(blockIdx.x) * BLOCK + threadIdx.x;
@@ -972,7 +978,8 @@ __global__ __launch_bounds__(BLOCK) void k_scatter_add(const int32_t *idx, const
 // narrows [lo, hi] 64-fold per round (4 rounds for k = 250 000).  Wave-synchronous: no barrier,
 // so the other wavefronts of the workgroup can do something else meanwhile.  With idx not
 // ascending the result is some position in [0, k]: memory-safe, meaningless.
-__device__ __forceinline__ uint32_t wave_lower_bound(const int32_t *idx, uint32_t k, int64_t value) {
+template <typename I>
+__device__ __forceinline__ uint32_t wave_lower_bound(const I *idx, uint32_t k, int64_t value) {
     const uint32_t lane = threadIdx.x & 63;
     uint32_t lo = 0, hi = k;  // invariant: idx[j] < value for j < lo, idx[hi] >= value or hi == k
     while (lo < hi) {         // lo, hi are wave-uniform; the width shrinks to below width / 64 every round
@@ -995,8 +1002,8 @@ __device__ __forceinline__ uint32_t wave_lower_bound(const int32_t *idx, uint32_
 // others already zero-fill it with 16-byte stores; after a barrier the entries are written.
 // Every output byte is written by one workgroup only; an entry whose index lies outside the span
 // that the search assigned it to (possible only when idx is not ascending) is skipped.
-template <typename R>
-__global__ __launch_bounds__(BLOCK) void k_merge(const int32_t *idx, const R *val, uint32_t k, unsigned char *y,
+template <typename R, typename I>
+__global__ __launch_bounds__(BLOCK) void k_merge(const I *idx, const R *val, uint32_t k, unsigned char *y,
                                                  size_t total, size_t head, size_t span) {
     __shared__ uint32_t s_range[2];
     const size_t byte_a = blockIdx.x == 0 ? 0 : head + static_cast<size_t>(blockIdx.x) * span;
@@ -1031,8 +1038,8 @@ __global__ __launch_bounds__(BLOCK) void k_merge(const int32_t *idx, const R *va
 // whose index lies outside the piece that the walk assigned it to (possible only when idx is not
 // ascending) is skipped: every store stays inside the span.
 constexpr int MERGE_PIECE = 32768;  // bytes of LDS per piece
-template <typename R>
-__global__ __launch_bounds__(BLOCK) void k_merge_lds(const int32_t *idx, const R *val, uint32_t k, unsigned char *y,
+template <typename R, typename I>
+__global__ __launch_bounds__(BLOCK) void k_merge_lds(const I *idx, const R *val, uint32_t k, unsigned char *y,
                                                      size_t total, size_t head, size_t span) {
     __shared__ __attribute__((aligned(16))) unsigned char piece[MERGE_PIECE];
     __shared__ uint32_t s_range[2];
@@ -1170,9 +1177,9 @@ void bounds_for(int64_t n_total, int32_t S, adatopk_dtype dt, int64_t *max_chunk
 
 // ---- stage timing (measurement hook): in measuring mode every kernel is launched with its own
 // start / stop events, whose timestamps are those of the dispatch itself (as a profiler sees it)
-enum Stage { ST_HIST1, ST_GATHER, ST_HIST3, ST_EMIT, ST_FILL, ST_SCATTER, ST_MERGE, NSTAGE };
+enum Stage { ST_HIST1, ST_GATHER, ST_HIST3, ST_EMIT, ST_FILL, ST_SCATTER, ST_MERGE, ST_HEADER, NSTAGE };
 const char *const kStageNames[NSTAGE] = {"k_hist1", "k_gather", "k_hist3", "k_emit",
-                                         "k_fill",  "k_scatter", "k_merge"};
+                                         "k_fill",  "k_scatter", "k_merge", "k_wire_header"};
 bool g_measure = false;
 bool g_events_made = false;
 hipEvent_t g_start[NSTAGE], g_stop[NSTAGE];
@@ -1199,8 +1206,9 @@ template <int VEC> adatopk_status launch_batch(const Launch &a, int total_chunks
 }
 
 adatopk_status compress_impl(const void *const *dense, const int64_t *n, const int64_t *k, int32_t S,
-                             adatopk_dtype dt, int32_t *idx_out, void *val_out, const int64_t *out_offset,
-                             float *err_out, void *workspace, size_t workspace_bytes, hipStream_t st) {
+                             adatopk_dtype dt, void *idx_out, int idx_bytes, void *val_out, const int64_t *out_offset,
+                             float *err_out, void *workspace, size_t workspace_bytes, hipStream_t st,
+                             bool validate_only = false) {
     if (!dtype_ok(dt) || S < 0) return ADATOPK_EINVAL;
     if (S == 0) return ADATOPK_OK;
     if (!dense || !n || !k || !out_offset) return ADATOPK_EINVAL;
@@ -1215,12 +1223,13 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
         k_total += k[s];
     }
     if (k_total > 0 && (!idx_out || !val_out)) return ADATOPK_EINVAL;
-    if (reinterpret_cast<uintptr_t>(idx_out) % 4 || reinterpret_cast<uintptr_t>(val_out) % es ||
+    if (reinterpret_cast<uintptr_t>(idx_out) % idx_bytes || reinterpret_cast<uintptr_t>(val_out) % es ||
         reinterpret_cast<uintptr_t>(err_out) % 4)
         return ADATOPK_EINVAL;
     const size_t need = adatopk_workspace_bytes(n_total, S, dt);
     if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return ADATOPK_EINVAL;
     if (workspace_bytes < need) return ADATOPK_EWORKSPACE;
+    if (validate_only) return ADATOPK_OK;
 
     int64_t max_chunks, max_lb;
     bounds_for(n_total, S, dt, &max_chunks, &max_lb);
@@ -1257,6 +1266,7 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
         a.L_idx = reinterpret_cast<int32_t *>(ws + cv.L_idx);
         a.L_val = ws + cv.L_val;
         a.idx_out = idx_out;
+        a.idx64 = idx_bytes == 8 ? 1u : 0u;
         a.val_out = val_out;
         a.err_out = err_out ? err_out + s0 : nullptr;
         int32_t chunks = 0, lbs = 0;
@@ -1303,6 +1313,118 @@ adatopk_status fill_impl(void *dst, size_t bytes, hipStream_t st) {  // the k_fi
     return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
 }
 
+// ---- decompress, for either index width
+adatopk_status check_pairs(const void *idx, int ib, const void *val, int64_t k, adatopk_dtype dt, const void *dense,
+                           int64_t n) {
+    if (!dtype_ok(dt) || n < 0 || k < 0 || n >= (static_cast<int64_t>(1) << 31) || k >= (static_cast<int64_t>(1) << 31))
+        return ADATOPK_EINVAL;
+    const int es = elem_size(dt);
+    if (n > 0 && (!dense || reinterpret_cast<uintptr_t>(dense) % es)) return ADATOPK_EINVAL;
+    if (k > 0 && (!idx || !val || reinterpret_cast<uintptr_t>(idx) % ib || reinterpret_cast<uintptr_t>(val) % es))
+        return ADATOPK_EINVAL;
+    return ADATOPK_OK;
+}
+
+template <typename I>
+void launch_scatter(const I *idx, const void *val, int64_t k, adatopk_dtype dt, void *y, int64_t n, hipStream_t st) {
+    const dim3 grid(static_cast<unsigned>((k + BLOCK - 1) / BLOCK));
+    if (dt == ADATOPK_F32)
+        launch(ST_SCATTER, k_scatter<uint32_t, I>, grid, st, idx, static_cast<const uint32_t *>(val), k,
+               static_cast<uint32_t *>(y), n);
+    else
+        launch(ST_SCATTER, k_scatter<uint16_t, I>, grid, st, idx, static_cast<const uint16_t *>(val), k,
+               static_cast<uint16_t *>(y), n);
+}
+
+adatopk_status decompress_impl(const void *idx, int ib, const void *val, int64_t k, adatopk_dtype dt, void *dense_out,
+                               int64_t n, hipStream_t st) {
+    const adatopk_status ok = check_pairs(idx, ib, val, k, dt, dense_out, n);
+    if (ok != ADATOPK_OK) return ok;
+    if (n == 0) return ADATOPK_OK;
+    const adatopk_status rc = fill_impl(dense_out, static_cast<size_t>(n) * elem_size(dt), st);
+    if (rc != ADATOPK_OK) return rc;
+    if (k > 0) {
+        if (ib == 4) launch_scatter(static_cast<const int32_t *>(idx), val, k, dt, dense_out, n, st);
+        else launch_scatter(static_cast<const int64_t *>(idx), val, k, dt, dense_out, n, st);
+    }
+    return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
+}
+
+template <typename I>
+void launch_scatter_add(const I *idx, const void *val, int64_t k, adatopk_dtype dt, void *y, int64_t n, hipStream_t st) {
+    const dim3 grid(static_cast<unsigned>((k + BLOCK - 1) / BLOCK));
+    if (dt == ADATOPK_F32)
+        launch(ST_SCATTER, k_scatter_add<TAG_F32, I>, grid, st, idx, static_cast<const uint32_t *>(val), k,
+               static_cast<uint32_t *>(y), n);
+    else if (dt == ADATOPK_BF16)
+        launch(ST_SCATTER, k_scatter_add<TAG_BF16, I>, grid, st, idx, static_cast<const uint16_t *>(val), k,
+               static_cast<uint16_t *>(y), n);
+    else
+        launch(ST_SCATTER, k_scatter_add<TAG_F16, I>, grid, st, idx, static_cast<const uint16_t *>(val), k,
+               static_cast<uint16_t *>(y), n);
+}
+
+adatopk_status accumulate_impl(const void *idx, int ib, const void *val, int64_t k, adatopk_dtype dt, void *dense_inout,
+                               int64_t n, hipStream_t st) {
+    const adatopk_status ok = check_pairs(idx, ib, val, k, dt, dense_inout, n);
+    if (ok != ADATOPK_OK) return ok;
+    if (n == 0 || k == 0) return ADATOPK_OK;
+    if (ib == 4) launch_scatter_add(static_cast<const int32_t *>(idx), val, k, dt, dense_inout, n, st);
+    else launch_scatter_add(static_cast<const int64_t *>(idx), val, k, dt, dense_inout, n, st);
+    return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
+}
+
+template <typename R, typename I>
+void launch_merge(bool dense, unsigned grid, hipStream_t st, const I *idx, const R *val, uint32_t k, unsigned char *y,
+                  size_t total, size_t head, size_t span) {
+    if (dense) launch(ST_MERGE, k_merge_lds<R, I>, dim3(grid), st, idx, val, k, y, total, head, span);
+    else launch(ST_MERGE, k_merge<R, I>, dim3(grid), st, idx, val, k, y, total, head, span);
+}
+
+adatopk_status decompress_sorted_impl(const void *idx, int ib, const void *val, int64_t k, adatopk_dtype dt,
+                                      void *dense_out, int64_t n, hipStream_t st) {
+    const adatopk_status ok = check_pairs(idx, ib, val, k, dt, dense_out, n);
+    if (ok != ADATOPK_OK) return ok;
+    if (n == 0) return ADATOPK_OK;
+    const int es = elem_size(dt);
+    const size_t total = static_cast<size_t>(n) * es;
+    size_t head = (16 - reinterpret_cast<uintptr_t>(dense_out) % 16) % 16;
+    if (head > total) head = total;
+    const size_t body = total - head;
+    size_t span = (body / MERGE_SPANS + 15) / 16 * 16;
+    if (span < MERGE_MIN_SPAN) span = MERGE_MIN_SPAN;
+    const unsigned grid = static_cast<unsigned>(body / span + 1);  // the last workgroup takes the remainder
+    const bool dense = k > n / MERGE_DENSE_RATIO;  // more than one entry per few lines: build the lines in LDS
+    const uint32_t ku = static_cast<uint32_t>(k);
+    unsigned char *yb = static_cast<unsigned char *>(dense_out);
+    if (es == 4) {
+        const uint32_t *v = static_cast<const uint32_t *>(val);
+        if (ib == 4) launch_merge(dense, grid, st, static_cast<const int32_t *>(idx), v, ku, yb, total, head, span);
+        else launch_merge(dense, grid, st, static_cast<const int64_t *>(idx), v, ku, yb, total, head, span);
+    } else {
+        const uint16_t *v = static_cast<const uint16_t *>(val);
+        if (ib == 4) launch_merge(dense, grid, st, static_cast<const int32_t *>(idx), v, ku, yb, total, head, span);
+        else launch_merge(dense, grid, st, static_cast<const int64_t *>(idx), v, ku, yb, total, head, span);
+    }
+    return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
+}
+
+// ---- wire message: header | indices, padded to 16 bytes | values
+inline size_t wire_val_offset(int64_t k, int index_bytes) {
+    return sizeof(adatopk_wire_header) + align_up(static_cast<size_t>(k) * index_bytes, 16);
+}
+struct WireWords {
+    uint32_t w[sizeof(adatopk_wire_header) / 4];
+};
+// Stores the header words (all but the error norm, which k_emit writes) and zeroes the padding
+// bytes [pad_a, pad_b) between the index and the value section (at most 15).
+__global__ __launch_bounds__(BLOCK) void k_wire_header(uint32_t *dst, WireWords words, uint32_t skip_word,
+                                                       unsigned char *base, size_t pad_a, size_t pad_b) {
+    const uint32_t t = threadIdx.x;
+    if (t < sizeof(adatopk_wire_header) / 4 && t != skip_word) dst[t] = words.w[t];
+    if (pad_a + t < pad_b) base[pad_a + t] = 0;
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ C ABI
@@ -1320,7 +1442,7 @@ adatopk_status adatopk_compress(const void *dense, int64_t n, adatopk_dtype dt, 
                                 void *hip_stream) {
     const void *ptrs[1] = {dense};
     const int64_t off[2] = {0, k};
-    return compress_impl(ptrs, &n, &k, 1, dt, idx_out, val_out, off, err_norm_out, workspace, workspace_bytes,
+    return compress_impl(ptrs, &n, &k, 1, dt, idx_out, 4, val_out, off, err_norm_out, workspace, workspace_bytes,
                          static_cast<hipStream_t>(hip_stream));
 }
 
@@ -1328,87 +1450,111 @@ adatopk_status adatopk_compress_segmented(const void *const *dense, const int64_
                                           adatopk_dtype dt, int32_t *idx_out, void *val_out,
                                           const int64_t *out_offset, float *err_norm_out, void *workspace,
                                           size_t workspace_bytes, void *hip_stream) {
-    return compress_impl(dense, n, k, S, dt, idx_out, val_out, out_offset, err_norm_out, workspace, workspace_bytes,
+    return compress_impl(dense, n, k, S, dt, idx_out, 4, val_out, out_offset, err_norm_out, workspace, workspace_bytes,
                          static_cast<hipStream_t>(hip_stream));
 }
 
 adatopk_status adatopk_decompress(const int32_t *idx, const void *val, int64_t k, adatopk_dtype dt, void *dense_out,
                                   int64_t n, void *hip_stream) {
-    if (!dtype_ok(dt) || n < 0 || k < 0 || n >= (static_cast<int64_t>(1) << 31)) return ADATOPK_EINVAL;
-    const int es = elem_size(dt);
-    if (n > 0 && (!dense_out || reinterpret_cast<uintptr_t>(dense_out) % es)) return ADATOPK_EINVAL;
-    if (k > 0 && (!idx || !val || reinterpret_cast<uintptr_t>(idx) % 4 || reinterpret_cast<uintptr_t>(val) % es))
-        return ADATOPK_EINVAL;
-    if (n == 0) return ADATOPK_OK;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const adatopk_status rc = fill_impl(dense_out, static_cast<size_t>(n) * es, st);
-    if (rc != ADATOPK_OK) return rc;
-    if (k > 0) {
-        const int grid = static_cast<int>((k + BLOCK - 1) / BLOCK);
-        if (dt == ADATOPK_F32)
-            launch(ST_SCATTER, k_scatter<uint32_t>, dim3(grid), st, idx, static_cast<const uint32_t *>(val), k,
-                   static_cast<uint32_t *>(dense_out), n);
-        else
-            launch(ST_SCATTER, k_scatter<uint16_t>, dim3(grid), st, idx, static_cast<const uint16_t *>(val), k,
-                   static_cast<uint16_t *>(dense_out), n);
-    }
-    return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
+    return decompress_impl(idx, 4, val, k, dt, dense_out, n, static_cast<hipStream_t>(hip_stream));
 }
 
 adatopk_status adatopk_decompress_accumulate(const int32_t *idx, const void *val, int64_t k, adatopk_dtype dt,
                                              void *dense_inout, int64_t n, void *hip_stream) {
-    if (!dtype_ok(dt) || n < 0 || k < 0 || n >= (static_cast<int64_t>(1) << 31)) return ADATOPK_EINVAL;
-    const int es = elem_size(dt);
-    if (n > 0 && (!dense_inout || reinterpret_cast<uintptr_t>(dense_inout) % es)) return ADATOPK_EINVAL;
-    if (k > 0 && (!idx || !val || reinterpret_cast<uintptr_t>(idx) % 4 || reinterpret_cast<uintptr_t>(val) % es))
-        return ADATOPK_EINVAL;
-    if (n == 0 || k == 0) return ADATOPK_OK;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const int64_t blocks = (k + BLOCK - 1) / BLOCK;
-    if (blocks > 0x7FFFFFFF) return ADATOPK_EINVAL;
-    const dim3 grid(static_cast<unsigned>(blocks));
-    if (dt == ADATOPK_F32)
-        launch(ST_SCATTER, k_scatter_add<TAG_F32>, grid, st, idx, static_cast<const uint32_t *>(val), k,
-               static_cast<uint32_t *>(dense_inout), n);
-    else if (dt == ADATOPK_BF16)
-        launch(ST_SCATTER, k_scatter_add<TAG_BF16>, grid, st, idx, static_cast<const uint16_t *>(val), k,
-               static_cast<uint16_t *>(dense_inout), n);
-    else
-        launch(ST_SCATTER, k_scatter_add<TAG_F16>, grid, st, idx, static_cast<const uint16_t *>(val), k,
-               static_cast<uint16_t *>(dense_inout), n);
-    return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
+    return accumulate_impl(idx, 4, val, k, dt, dense_inout, n, static_cast<hipStream_t>(hip_stream));
 }
 
 adatopk_status adatopk_decompress_sorted(const int32_t *idx, const void *val, int64_t k, adatopk_dtype dt,
                                          void *dense_out, int64_t n, void *hip_stream) {
-    if (!dtype_ok(dt) || n < 0 || k < 0 || n >= (static_cast<int64_t>(1) << 31) || k >= (static_cast<int64_t>(1) << 31))
+    return decompress_sorted_impl(idx, 4, val, k, dt, dense_out, n, static_cast<hipStream_t>(hip_stream));
+}
+
+// ---- wire format
+size_t adatopk_wire_bytes(int64_t k, adatopk_dtype dt, int32_t index_bytes) {
+    if (k < 0 || k >= (static_cast<int64_t>(1) << 31) || !dtype_ok(dt) || (index_bytes != 4 && index_bytes != 8)) return 0;
+    return wire_val_offset(k, index_bytes) + static_cast<size_t>(k) * elem_size(dt);
+}
+
+int64_t adatopk_wire_keep_count(size_t wire_bytes, adatopk_dtype dt, int32_t index_bytes) {
+    if (!dtype_ok(dt) || (index_bytes != 4 && index_bytes != 8) || wire_bytes < sizeof(adatopk_wire_header)) return -1;
+    // bytes(k) grows by index_bytes + element size per pair plus padding of at most 15: start from
+    // the estimate without padding and walk down to the k whose size matches
+    const size_t per = static_cast<size_t>(index_bytes) + elem_size(dt);
+    int64_t k = static_cast<int64_t>((wire_bytes - sizeof(adatopk_wire_header)) / per);
+    if (k >= (static_cast<int64_t>(1) << 31)) return -1;
+    for (int step = 0; step < 16 && k >= 0; ++step, --k)
+        if (adatopk_wire_bytes(k, dt, index_bytes) == wire_bytes) return k;
+    return -1;
+}
+
+adatopk_status adatopk_wire_parse_header(const void *host_bytes, size_t wire_bytes, adatopk_wire_header *out) {
+    if (!host_bytes || !out || wire_bytes < sizeof(adatopk_wire_header)) return ADATOPK_EINVAL;
+    adatopk_wire_header h;
+    memcpy(&h, host_bytes, sizeof h);
+    if (h.magic != ADATOPK_WIRE_MAGIC || h.version != ADATOPK_WIRE_VERSION || h.algorithm != ADATOPK_WIRE_TOPK)
         return ADATOPK_EINVAL;
-    const int es = elem_size(dt);
-    if (n > 0 && (!dense_out || reinterpret_cast<uintptr_t>(dense_out) % es)) return ADATOPK_EINVAL;
-    if (k > 0 && (!idx || !val || reinterpret_cast<uintptr_t>(idx) % 4 || reinterpret_cast<uintptr_t>(val) % es))
+    const adatopk_dtype dt = static_cast<adatopk_dtype>(h.dtype);
+    if (!dtype_ok(dt) || (h.index_bytes != 4 && h.index_bytes != 8)) return ADATOPK_EINVAL;
+    if (h.n < 0 || h.n >= (static_cast<int64_t>(1) << 31) || h.k < 0 || h.k > h.n) return ADATOPK_EINVAL;
+    if (h.idx_offset != static_cast<int64_t>(sizeof(adatopk_wire_header)) ||
+        h.val_offset != static_cast<int64_t>(wire_val_offset(h.k, h.index_bytes)) ||
+        adatopk_wire_bytes(h.k, dt, h.index_bytes) != wire_bytes)
         return ADATOPK_EINVAL;
-    if (n == 0) return ADATOPK_OK;
+    *out = h;
+    return ADATOPK_OK;
+}
+
+adatopk_status adatopk_compress_wire(const void *dense, int64_t n, adatopk_dtype dt, int64_t k, int32_t index_bytes,
+                                     double ratio, void *wire_out, size_t wire_capacity, void *workspace,
+                                     size_t workspace_bytes, void *hip_stream) {
+    if (index_bytes != 4 && index_bytes != 8) return ADATOPK_EINVAL;
+    if (!dtype_ok(dt) || n < 0 || k < 0 || k > n || n >= (static_cast<int64_t>(1) << 31)) return ADATOPK_EINVAL;
+    if (!wire_out || reinterpret_cast<uintptr_t>(wire_out) % 16) return ADATOPK_EINVAL;
+    const size_t bytes = adatopk_wire_bytes(k, dt, index_bytes);
+    if (bytes == 0 || wire_capacity < bytes) return ADATOPK_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const size_t total = static_cast<size_t>(n) * es;
-    size_t head = (16 - reinterpret_cast<uintptr_t>(dense_out) % 16) % 16;
-    if (head > total) head = total;
-    const size_t body = total - head;
-    size_t span = (body / MERGE_SPANS + 15) / 16 * 16;
-    if (span < MERGE_MIN_SPAN) span = MERGE_MIN_SPAN;
-    const unsigned grid = static_cast<unsigned>(body / span + 1);  // the last workgroup takes the remainder
-    const bool dense = k > n / MERGE_DENSE_RATIO;  // more than one entry per few lines: build the lines in LDS
-    const uint32_t ku = static_cast<uint32_t>(k);
-    unsigned char *yb = static_cast<unsigned char *>(dense_out);
-    if (dt == ADATOPK_F32) {
-        const uint32_t *v = static_cast<const uint32_t *>(val);
-        if (dense) launch(ST_MERGE, k_merge_lds<uint32_t>, dim3(grid), st, idx, v, ku, yb, total, head, span);
-        else launch(ST_MERGE, k_merge<uint32_t>, dim3(grid), st, idx, v, ku, yb, total, head, span);
-    } else {
-        const uint16_t *v = static_cast<const uint16_t *>(val);
-        if (dense) launch(ST_MERGE, k_merge_lds<uint16_t>, dim3(grid), st, idx, v, ku, yb, total, head, span);
-        else launch(ST_MERGE, k_merge<uint16_t>, dim3(grid), st, idx, v, ku, yb, total, head, span);
-    }
-    return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
+    adatopk_wire_header h;
+    memset(&h, 0, sizeof h);
+    h.magic = ADATOPK_WIRE_MAGIC;
+    h.version = ADATOPK_WIRE_VERSION;
+    h.algorithm = ADATOPK_WIRE_TOPK;
+    h.dtype = static_cast<uint8_t>(dt);
+    h.index_bytes = static_cast<uint8_t>(index_bytes);
+    h.n = n;
+    h.k = k;
+    h.ratio = ratio;
+    h.idx_offset = sizeof(adatopk_wire_header);
+    h.val_offset = static_cast<int64_t>(wire_val_offset(k, index_bytes));
+    char *w = static_cast<char *>(wire_out);
+    const void *ptrs[1] = {dense};
+    const int64_t off[2] = {0, k};
+    // validate everything (workspace included) before the header kernel is enqueued
+    const adatopk_status pre = compress_impl(ptrs, &n, &k, 1, dt, w + h.idx_offset, index_bytes, w + h.val_offset, off,
+                                             reinterpret_cast<float *>(w + offsetof(adatopk_wire_header, err_norm)),
+                                             workspace, workspace_bytes, st, /*validate_only=*/true);
+    if (pre != ADATOPK_OK) return pre;
+    WireWords words;
+    memcpy(&words, &h, sizeof h);
+    const size_t pad_a = static_cast<size_t>(h.idx_offset + k * index_bytes), pad_b = static_cast<size_t>(h.val_offset);
+    launch(ST_HEADER, k_wire_header, dim3(1), st, reinterpret_cast<uint32_t *>(w), words,
+           static_cast<uint32_t>(offsetof(adatopk_wire_header, err_norm) / 4), reinterpret_cast<unsigned char *>(w),
+           pad_a, pad_b);
+    if (hipGetLastError() != hipSuccess) return ADATOPK_ERUNTIME;
+    return compress_impl(ptrs, &n, &k, 1, dt, w + h.idx_offset, index_bytes, w + h.val_offset, off,
+                         reinterpret_cast<float *>(w + offsetof(adatopk_wire_header, err_norm)), workspace,
+                         workspace_bytes, st, false);
+}
+
+adatopk_status adatopk_decompress_wire(const void *wire, size_t wire_bytes, adatopk_dtype dt, int32_t index_bytes,
+                                       int64_t n, int32_t accumulate, void *dense, void *hip_stream) {
+    const int64_t k = adatopk_wire_keep_count(wire_bytes, dt, index_bytes);
+    if (k < 0 || n < 0 || k > n || !wire || reinterpret_cast<uintptr_t>(wire) % 16) return ADATOPK_EINVAL;
+    const char *w = static_cast<const char *>(wire);
+    const void *idx = w + sizeof(adatopk_wire_header);
+    const void *val = w + wire_val_offset(k, index_bytes);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (accumulate) return accumulate_impl(idx, index_bytes, val, k, dt, dense, n, st);
+    return decompress_sorted_impl(idx, index_bytes, val, k, dt, dense, n, st);
 }
 
 // ---- measurement hooks

@@ -166,3 +166,23 @@ def test_link_and_pipeline_estimates(lib):
         B.adatopk_plan_keep_counts([0.0], [0.0], [10], B.F32, 10.0, 3.0)  # no link takes any time
     with pytest.raises(B.AdaTopKError):
         B.adatopk_plan_keep_counts([0.1], [1e-6], [-1], B.F32, 10.0, 3.0)
+
+
+def test_wire_calls_reject_bad_arguments_before_touching_the_device(lib):
+    EINVAL, EWORKSPACE = 1, 2
+    fake, ws = 0x1000, 0x100000  # never dereferenced
+    need = lib.adatopk_workspace_bytes(1000, 1, 0)
+    cap = lib.adatopk_wire_bytes(10, 0, 4)
+    c = lib.adatopk_compress_wire
+    assert c(fake, 1000, 0, 10, 3, 100.0, fake, cap, ws, need, None) == EINVAL      # index width
+    assert c(fake, 1000, 0, 10, 4, 100.0, fake, cap - 1, ws, need, None) == EINVAL  # message does not fit
+    assert c(fake, 1000, 0, 10, 8, 100.0, fake, cap, ws, need, None) == EINVAL      # int64 indices need more
+    assert c(fake, 1000, 0, 10, 4, 100.0, fake + 8, cap, ws, need, None) == EINVAL  # 16-byte alignment
+    assert c(fake, 1000, 0, 10, 4, 100.0, None, cap, ws, need, None) == EINVAL
+    assert c(fake, 1000, 0, 1001, 4, 100.0, fake, 1 << 20, ws, need, None) == EINVAL
+    assert c(fake, 1000, 0, 10, 4, 100.0, fake, cap, ws, need - 1, None) == EWORKSPACE
+    d = lib.adatopk_decompress_wire
+    assert d(fake, cap + 1, 0, 4, 1000, 0, fake, None) == EINVAL  # no k has this length
+    assert d(fake, cap, 0, 4, 9, 0, fake, None) == EINVAL         # k = 10 > n
+    assert d(fake + 4, cap, 0, 4, 1000, 0, fake, None) == EINVAL
+    assert d(fake, cap, 0, 4, 1000, 1, None, None) == EINVAL
