@@ -70,7 +70,7 @@ constexpr int SH2 = BITS3;
 constexpr int NC1 = 64;             // coarse boundaries of the top digit: every (NB1 / NC1)-th suffix sum
 constexpr int FINE1 = NB1 / NC1;    // fine bins per coarse interval
 constexpr int NC2 = 32;             // the same for the second digit
-constexpr int MAXSEG = 32;          // segments per launch (the table travels as kernel arguments)
+constexpr int MAXSEG = 64;          // segments per launch (the table travels as kernel arguments)
 constexpr int CTARGET = ADATOPK_CTARGET;  // chunks aimed at per launch
 constexpr int LB_ELEMS = 8192;      // input elements per list block when sizing the list grid
 constexpr int LB_TOTAL = 4096;      // list blocks aimed at per launch, all segments together
@@ -127,6 +127,7 @@ struct Launch {
     float *err_out;
     uint32_t idx64;
 };
+static_assert(sizeof(Launch) <= 4096, "kernel arguments stay within 4 KB");
 
 // ------------------------------------------------------------------ element access
 // VEC tags the dtype: 4 = fp32 (one element per dword), 8 = bf16 and 9 = fp16 (two per dword, low
@@ -292,13 +293,17 @@ template <int NB> __device__ __forceinline__ void flush_bins(const uint32_t *h, 
         if (c) __hip_atomic_fetch_add(&G[b], c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
+// Segment that owns workgroup g: the last one whose first chunk (or list block) is <= g.  One
+// lane per table entry and one ballot instead of a loop of dependent scalar loads, which costs
+// about 0.1 us per segment.
+static_assert(MAXSEG <= 64, "one lane per segment");
 __device__ __forceinline__ int find_segment_by(const Launch &a, int g, bool by_chunk) {
-    int s = 0;
-    for (int i = 1; i < a.S; ++i) {
-        const int begin = by_chunk ? a.seg[i].chunk_begin : a.seg[i].lb_begin;
-        if (g >= begin) s = i;
-    }
-    return s;
+    if (a.S == 1) return 0;
+    const int lane = threadIdx.x & 63;
+    int begin = 0x7FFFFFFF;
+    if (lane < a.S) begin = by_chunk ? a.seg[lane].chunk_begin : a.seg[lane].lb_begin;
+    const uint64_t owner_or_before = __ballot(g >= begin);  // begins never decrease and the first is 0
+    return 63 - __builtin_clzll(owner_or_before | 1ull);
 }
 
 // Global histogram G[NB] (complete: written by an earlier kernel) -> bucket B holding the
@@ -927,6 +932,158 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     }
 }
 
+// ------------------------------------------------------------------ small tensors: one launch
+// Many small messages (a few thousand elements each) are bound by launch latency in the
+// four-kernel path: about 5 us per kernel whatever the size.  Here one workgroup does the whole
+// selection of one tensor that fits its registers: one read, three histogram rounds (the same
+// 11/10/10-bit digits, LDS histograms, the same bucket search) that fix the threshold key T and
+// the tie quota q, then one ordered round that writes the kept pairs in ascending index order and
+// sums the squares of the dropped ones.  Same results as the big path.  One compute unit works
+// through about 3 elements per ns in the ordered round, so tensors beyond one register tile stay
+// with the four-kernel path, which spreads them over many compute units.
+constexpr int SMALL_EPT = 16;                  // elements per thread
+constexpr int SMALL_N = BLOCK * SMALL_EPT;     // largest tensor this path takes
+constexpr int SMALL_MAXSEG = 128;              // tensors per launch (the table travels as kernel arguments)
+struct SmallDesc {
+    const void *x;
+    int64_t out_off;
+    int32_t n, k;
+};
+struct SmallLaunch {
+    SmallDesc seg[SMALL_MAXSEG];
+    void *idx_out;
+    void *val_out;
+    float *err_out;
+    uint32_t idx64;
+};
+static_assert(sizeof(SmallLaunch) <= 3584, "kernel arguments stay below 4 KB");
+static_assert(SMALL_EPT * NW <= 128, "the (slot, wave) counts are scanned two per lane");
+static_assert(SMALL_N < 65536, "two 16-bit counts travel in one word");
+
+// One histogram round over the tensor in registers: counts digit (key >> shift) & (NB - 1) of the
+// keys whose bits above the digit equal `prefix` (every key when use_prefix is false), then picks
+// the bucket holding the krem-th largest.  Returns the bucket (NB when krem == 0) and the count
+// above it.  Slot e of thread t is element e * BLOCK + t; slots past the end are skipped by a
+// uniform branch.
+template <int VEC, int NB>
+__device__ __forceinline__ void small_round(const uint32_t (&raw)[SMALL_EPT], int n, int shift, int prefix_shift,
+                                            uint32_t prefix, bool use_prefix, uint32_t krem, uint32_t *h, uint32_t *sm,
+                                            uint32_t *s_pick, uint32_t &B, uint32_t &above) {
+    for (int b = threadIdx.x; b < NB; b += BLOCK) h[b] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < SMALL_EPT; ++e) {
+        if (e * BLOCK < n) {  // uniform
+            const int i = e * BLOCK + static_cast<int>(threadIdx.x);
+            const uint32_t key = key_of<VEC>(raw[e]);
+            const bool in = i < n && (!use_prefix || (key >> prefix_shift) == prefix);
+            if (in) atomicAdd(&h[(key >> shift) & (NB - 1)], 1u);
+        }
+    }
+    __syncthreads();
+    block_suffix_inplace<NB>(h, sm);
+    block_pick_bucket<NB>(h, krem, s_pick);
+    __syncthreads();
+    B = s_pick[0];
+    above = s_pick[1];
+    __syncthreads();
+}
+
+template <int VEC> __global__ __launch_bounds__(BLOCK) void k_small(const SmallLaunch a) {
+    using R = typename Raw<VEC>::type;
+    __shared__ uint32_t h[NB1];
+    __shared__ uint32_t sm[NW];
+    __shared__ double smd[NW];
+    __shared__ uint32_t s_pick[2];
+    __shared__ uint32_t wcnt[SMALL_EPT * NW];  // (#above T) | (#equal to T) << 16 of every (slot, wave)
+
+    const SmallDesc &sg = a.seg[blockIdx.x];
+    const int n = sg.n;
+    const uint32_t kout = static_cast<uint32_t>(sg.k);
+    const R *x = static_cast<const R *>(sg.x);
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+
+    uint32_t raw[SMALL_EPT];
+#pragma unroll
+    for (int e = 0; e < SMALL_EPT; ++e) {
+        const int i = e * BLOCK + static_cast<int>(threadIdx.x);
+        raw[e] = (i < n) ? static_cast<uint32_t>(x[i]) : 0u;
+    }
+
+    // threshold key T, number of keys above it, tie quota q
+    uint32_t T = 0xFFFFFFFFu, c_gt = 0;
+    if (kout != 0) {
+        uint32_t B1, a1, B2, a2, B3, a3;
+        small_round<VEC, NB1>(raw, n, SH1, 0, 0u, false, kout, h, sm, s_pick, B1, a1);
+        small_round<VEC, NB2>(raw, n, SH2, SH1, B1, true, kout - a1, h, sm, s_pick, B2, a2);
+        const uint32_t P = (B1 << BITS2) | B2;
+        small_round<VEC, NB3>(raw, n, 0, SH2, P, true, kout - a1 - a2, h, sm, s_pick, B3, a3);
+        T = (P << BITS3) | B3;
+        c_gt = a1 + a2 + a3;
+    }
+    const uint32_t q = kout - c_gt;
+
+    // Ordered round.  Index order is (slot, wave, lane): per slot the rank of every lane among the
+    // wave's keys above / equal to T (two 16-bit fields of one register; the lane masks themselves
+    // are not kept), the counts to LDS (lane e writes slot e's), one barrier, then every wavefront
+    // scans the SMALL_EPT * NW counts in index order, two entries per lane.
+    uint32_t rk[SMALL_EPT];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int e = 0; e < SMALL_EPT; ++e) {
+        rk[e] = 0;
+        uint32_t c = 0;
+        if (e * BLOCK < n) {  // uniform
+            const int i = e * BLOCK + static_cast<int>(threadIdx.x);
+            const uint32_t key = key_of<VEC>(raw[e]);
+            const uint64_t bg = __ballot(i < n && key > T);
+            const uint64_t be = __ballot(i < n && key == T);
+            rk[e] = lanes_below(bg) | (lanes_below(be) << 16);
+            c = static_cast<uint32_t>(__popcll(bg)) | (static_cast<uint32_t>(__popcll(be)) << 16);
+        }
+        mine = (lane == e) ? c : mine;
+    }
+    if (lane < SMALL_EPT) wcnt[lane * NW + w] = mine;
+    __syncthreads();
+    const uint32_t c0 = (2 * lane < SMALL_EPT * NW) ? wcnt[2 * lane] : 0u;
+    const uint32_t c1 = (2 * lane + 1 < SMALL_EPT * NW) ? wcnt[2 * lane + 1] : 0u;
+    const uint32_t inc = wave_incl_scan(c0 + c1);
+    const uint32_t ex0 = inc - c0 - c1, ex1 = inc - c1;  // counts before entry 2 * lane and before 2 * lane + 1
+
+    int32_t *oi = static_cast<int32_t *>(a.idx_out) + sg.out_off;
+    int64_t *oi64 = static_cast<int64_t *>(a.idx_out) + sg.out_off;
+    R *ov = static_cast<R *>(a.val_out) + sg.out_off;
+    const bool wide = a.idx64 != 0;
+    double acc = 0.0;
+#pragma unroll
+    for (int e = 0; e < SMALL_EPT; ++e) {
+        if (e * BLOCK < n) {  // uniform
+            const int i = e * BLOCK + static_cast<int>(threadIdx.x);
+            const int entry = e * NW + w;
+            const uint32_t before = __shfl((entry & 1) ? ex1 : ex0, entry >> 1);  // one entry for the whole wave
+            const uint32_t key = key_of<VEC>(raw[e]);
+            const bool valid = i < n;
+            const uint32_t gt_before = (before & 0xFFFFu) + (rk[e] & 0xFFFFu);
+            const uint32_t eq_before = (before >> 16) + (rk[e] >> 16);
+            const bool keep = valid && (key > T || (key == T && eq_before < q));
+            if (keep) {
+                const uint32_t pos = gt_before + (eq_before < q ? eq_before : q);
+                if (pos < kout) {
+                    if (wide) oi64[pos] = i;
+                    else oi[pos] = i;
+                    ov[pos] = static_cast<R>(raw[e]);
+                }
+            }
+            const double v = static_cast<double>((valid && !keep) ? value_of<VEC>(raw[e]) : 0.0f);
+            acc = fma(v, v, acc);
+        }
+    }
+    if (a.err_out != nullptr) {
+        const double tot = block_sum_f64(acc, smd);
+        if (threadIdx.x == 0) a.err_out[blockIdx.x] = static_cast<float>(sqrt(tot));
+    }
+}
+
 // ------------------------------------------------------------------ decompress / streaming kernels
 // Zero `bytes` bytes at dst.  [head, head + 16 * body16) is the 16-byte aligned body.
 __global__ __launch_bounds__(BLOCK) void k_fill(unsigned char *dst, size_t bytes, size_t head, size_t body16) {
@@ -1177,9 +1334,9 @@ void bounds_for(int64_t n_total, int32_t S, adatopk_dtype dt, int64_t *max_chunk
 
 // ---- stage timing (measurement hook): in measuring mode every kernel is launched with its own
 // start / stop events, whose timestamps are those of the dispatch itself (as a profiler sees it)
-enum Stage { ST_HIST1, ST_GATHER, ST_HIST3, ST_EMIT, ST_FILL, ST_SCATTER, ST_MERGE, ST_HEADER, NSTAGE };
+enum Stage { ST_HIST1, ST_GATHER, ST_HIST3, ST_EMIT, ST_FILL, ST_SCATTER, ST_MERGE, ST_HEADER, ST_SMALL, NSTAGE };
 const char *const kStageNames[NSTAGE] = {"k_hist1", "k_gather", "k_hist3", "k_emit",
-                                         "k_fill",  "k_scatter", "k_merge", "k_wire_header"};
+                                         "k_fill",  "k_scatter", "k_merge", "k_wire_header", "k_small"};
 bool g_measure = false;
 bool g_events_made = false;
 hipEvent_t g_start[NSTAGE], g_stop[NSTAGE];
@@ -1230,6 +1387,31 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
     if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return ADATOPK_EINVAL;
     if (workspace_bytes < need) return ADATOPK_EWORKSPACE;
     if (validate_only) return ADATOPK_OK;
+
+    // Only small tensors: one launch, one workgroup per tensor, no workspace traffic.
+    bool all_small = true;
+    for (int32_t s = 0; s < S; ++s) all_small = all_small && n[s] <= SMALL_N;
+    if (all_small) {
+        for (int32_t s0 = 0; s0 < S; s0 += SMALL_MAXSEG) {
+            SmallLaunch sl{};
+            const int32_t cnt = (S - s0 < SMALL_MAXSEG) ? S - s0 : SMALL_MAXSEG;
+            for (int32_t i = 0; i < cnt; ++i) {
+                sl.seg[i].x = dense[s0 + i];
+                sl.seg[i].out_off = out_offset[s0 + i];
+                sl.seg[i].n = static_cast<int32_t>(n[s0 + i]);
+                sl.seg[i].k = static_cast<int32_t>(k[s0 + i]);
+            }
+            sl.idx_out = idx_out;
+            sl.idx64 = idx_bytes == 8 ? 1u : 0u;
+            sl.val_out = val_out;
+            sl.err_out = err_out ? err_out + s0 : nullptr;
+            if (dt == ADATOPK_F32) launch(ST_SMALL, k_small<TAG_F32>, dim3(cnt), st, sl);
+            else if (dt == ADATOPK_BF16) launch(ST_SMALL, k_small<TAG_BF16>, dim3(cnt), st, sl);
+            else launch(ST_SMALL, k_small<TAG_F16>, dim3(cnt), st, sl);
+            if (hipGetLastError() != hipSuccess) return ADATOPK_ERUNTIME;
+        }
+        return ADATOPK_OK;
+    }
 
     int64_t max_chunks, max_lb;
     bounds_for(n_total, S, dt, &max_chunks, &max_lb);

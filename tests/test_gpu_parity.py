@@ -211,3 +211,34 @@ def test_two_incoming_gradients_sum_like_the_oracle():
         B.adatopk_decompress_accumulate(idx, val, k, acc)
     torch.cuda.synchronize()
     assert np.array_equal(H.bits(H.to_host(acc)), H.bits(acc_ref))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("limit", [8192, 65_536])
+def test_many_small_tensors_in_one_call(dtype, limit):
+    # the launch-bound regime: hundreds of small messages in one call.  With every tensor within
+    # 8192 elements the one-launch path takes them (more than one of its launches holds); with
+    # larger ones in the mix the four-kernel path batches them, several launches as well
+    import gpu_harness as H
+
+    rng = np.random.Generator(np.random.PCG64(23))
+    lens = [1, 63, 64, 65, 511, 512, 513, 1023, 1024, 1025, 4095, 4096, 4097, 8191, 8192, 0]
+    if limit > 8192:
+        lens += [8193, 16384, 32768, 65535, 65536]
+    lens += rng.integers(1, limit + 1, size=300 - len(lens)).tolist()
+    kinds = ["normal", "few_levels", "sparse", "all_equal", "nonfinite", "random_bits", "signed_zero_mix"]
+    xs = [wl.small_case(kinds[i % len(kinds)], n, seed=900 + i, dtype=dtype) for i, n in enumerate(lens)]
+    ks = [int(rng.integers(0, n + 1)) if i % 3 else max(0, n // 100) for i, n in enumerate(lens)]
+    gi, gv, off, ge = H.gpu_compress_segmented(xs, ks)
+    ri, rv, roff, re = orc.compress_segmented(xs, ks)
+    assert np.array_equal(off, roff) and np.array_equal(gi, ri) and np.array_equal(H.bits(gv), H.bits(rv))
+    for s in range(len(xs)):
+        assert H.same_err(ge[s], re[s], ERR_RTOL), (s, lens[s], ks[s], ge[s], re[s])
+
+
+def test_small_tensor_limit_and_one_past_it():
+    for n in (8192, 8193):  # the last size of the one-launch path and the first of the four-kernel path
+        for kind in ("few_levels", "normal"):
+            x = wl.small_case(kind, n, seed=n)
+            for k in (1, n // 7, n - 1, n):
+                check_one(x, k, label="%s n=%d k=%d" % (kind, n, k))
