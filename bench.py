@@ -34,6 +34,71 @@ TRAFFIC_BYTES = {
 }
 
 
+def micro_batch_pipeline(B, torch, xs, k, tdt, n, esize, ws, n_b=4, rounds=25):
+    """Sender side of pipeline parallelism with n_b micro-batches (paper Sec. 3.6): every micro-batch's
+    activation is compressed straight into a wire message, and the message is copied to pinned host
+    memory, where a network stack would pick it up.  Serial: both on one stream.  Overlapped: the copy
+    of micro-batch j runs on a second stream while micro-batch j + 1 is compressed (two message buffers).
+    Returns microseconds per micro-batch for both."""
+    dt_code = B._dtype_code(tdt)
+    nbytes = B.adatopk_wire_bytes(k, dt_code, 4)
+    wire = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    host = [torch.empty(nbytes, dtype=torch.uint8, pin_memory=True) for _ in range(2)]
+    comp, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    done = [torch.cuda.Event() for _ in range(2)]
+    freed = [torch.cuda.Event() for _ in range(2)]
+
+    def run(overlap: bool) -> float:
+        torch.cuda.synchronize()
+        for e in freed:
+            e.record(comp)
+        t0 = time.perf_counter()
+        for j in range(n_b * rounds):
+            b = j % 2
+            with torch.cuda.stream(comp):
+                comp.wait_event(freed[b])
+                B.adatopk_compress_wire(xs[j % len(xs)][0], k, 4, float(n) / max(k, 1), wire[b], ws)
+                done[b].record(comp)
+            with torch.cuda.stream(copy if overlap else comp):
+                if overlap:
+                    copy.wait_event(done[b])
+                host[b].copy_(wire[b], non_blocking=True)
+                freed[b].record(copy if overlap else comp)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / (n_b * rounds) * 1e6
+
+    run(True)  # warm-up of both paths
+    serial, overlapped = run(False), run(True)
+    return {"n_b": n_b, "message_bytes": nbytes, "serial_us_per_micro_batch": round(serial, 2),
+            "overlapped_us_per_micro_batch": round(overlapped, 2),
+            "what": "compress into a wire message + copy of the message to pinned host memory"}
+
+
+def concurrent_streams(B, torch, xs, k, tdt, n, esize, streams=4, rounds=50):
+    """Independent compress + decompress steps on several streams, each with its own workspace and
+    outputs: what the GPU sustains when the tensors of several pipeline edges are in flight at once."""
+    sts = [torch.cuda.Stream() for _ in range(streams)]
+    bufs = [(torch.empty(max(k, 1), dtype=torch.int32, device="cuda"), torch.empty(max(k, 1), dtype=tdt, device="cuda"),
+             torch.empty(1, dtype=torch.float32, device="cuda"), torch.empty(n, dtype=tdt, device="cuda"),
+             B.new_workspace(n, 1, tdt)) for _ in range(streams)]
+
+    def run() -> float:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(rounds):
+            for s_, st in enumerate(sts):
+                idx, val, err, y, ws = bufs[s_]
+                with torch.cuda.stream(st):
+                    B.adatopk_compress(xs[(i * streams + s_) % len(xs)][0], k, idx, val, err, ws)
+                    B.adatopk_decompress_sorted(idx, val, k, y)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / (rounds * streams)
+
+    run()
+    sec = run()
+    return {"streams": streams, "us_per_step": round(sec * 1e6, 2), "value": round(n * esize / sec / 1e9, 1), "unit": "GB/s"}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -43,6 +108,8 @@ def main() -> int:
     ap.add_argument("--config", default="2", choices=["1", "2a", "2", "2c", "3", "4", "5"],
                     help="workload: 2 (default, the headline: GELU tensor at k = 1 %%), 2a / 2c = the same tensor at "
                          "k = 0.1 %% / 10 %%, 1, 3, 4 (segmented batch), 5 (bf16) = the other parity configurations")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the side measurements (micro-batch pipeline, concurrent streams)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run the library's plain copy kernel on the workload-sized buffer (the known-size "
                          "kernel that hardware-counter readings are scaled by)")
@@ -172,6 +239,10 @@ def main() -> int:
         "stage_us": {nm: (round(v, 2) if v is not None else None) for nm, v in stage_us.items()},
         "roofline": roofline,
     }
+
+    if S == 1 and not args.no_extras:
+        out["micro_batch_pipeline"] = micro_batch_pipeline(B, torch, xs, k, tdt, n, esize, ws)
+        out["concurrent_streams"] = concurrent_streams(B, torch, xs, k, tdt, n, esize)
 
     if not args.no_cpu_baseline:
         from oracle import adatopk_oracle as orc

@@ -75,3 +75,59 @@ def test_two_streams_with_their_own_workspaces():
         assert np.array_equal(val.cpu().numpy().view(np.uint32), rv.view(np.uint32))
         assert abs(float(err.cpu()[0]) - float(re)) <= 1e-5 * float(re)
         assert np.array_equal(y.cpu().numpy().view(np.uint32), orc.decompress(ri, rv, n).view(np.uint32))
+
+
+def test_micro_batch_pipeline_overlapping_compress_and_message_copy():
+    # Sender side of pipeline parallelism with several micro-batches (paper Sec. 3.6): micro-batch j + 1
+    # is compressed into a wire message while the message of micro-batch j is copied to pinned host
+    # memory on a second stream; two message buffers, events in both directions.  Every message that
+    # arrives on the host must be the oracle's message of that micro-batch; the receiver side
+    # (upload, accumulate into a running gradient) must give the oracle's sum.
+    import struct
+
+    import torch
+
+    import gpu_harness as H
+    from oracle import wire_format as wf
+    from paper_2410_12707_amd import binding as B
+
+    n, k, n_b = 600_011, 6_000, 5
+    xs = [wl.small_case(kind, n, seed=300 + j) for j, kind in enumerate(["normal", "few_levels", "sparse", "normal", "normal"])]
+    refs = [orc.compress(x, k) for x in xs]
+    dev = [H.to_device(x) for x in xs]
+    nbytes = wf.message_bytes(k, np.float32, 4)
+    wire = [torch.full((nbytes,), 0xEE, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    host = [torch.empty(nbytes, dtype=torch.uint8, pin_memory=True) for _ in range(n_b)]
+    ws = B.new_workspace(n, 1, torch.float32)
+    comp, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    done = [torch.cuda.Event() for _ in range(2)]
+    freed = [torch.cuda.Event() for _ in range(2)]
+    torch.cuda.synchronize()
+    for e in freed:
+        e.record(comp)
+    for j in range(n_b):
+        b = j % 2
+        with torch.cuda.stream(comp):
+            comp.wait_event(freed[b])
+            B.adatopk_compress_wire(dev[j], k, 4, n / k, wire[b], ws)
+            done[b].record(comp)
+        with torch.cuda.stream(copy):
+            copy.wait_event(done[b])
+            host[j].copy_(wire[b], non_blocking=True)
+            freed[b].record(copy)
+    torch.cuda.synchronize()
+    acc_ref = np.zeros(n, dtype=np.float32)
+    acc = torch.zeros(n, dtype=torch.float32, device="cuda")
+    for j in range(n_b):
+        ri, rv, re = refs[j]
+        got = host[j].numpy().tobytes()
+        ref = wf.pack(ri, rv, n, float(re), n / k, 4)
+        assert got[:12] == ref[:12] and got[16:] == ref[16:], j
+        assert H.same_err(struct.unpack("<f", got[12:16])[0], re, 1e-5)
+        h = B.adatopk_wire_parse_header(got, len(got))
+        assert (h.n, h.k) == (n, k)
+        up = host[j].cuda()  # the receiver uploads the message and adds it to its running gradient
+        B.adatopk_decompress_wire(up, nbytes, 4, acc, accumulate=True)
+        acc_ref = orc.decompress_accumulate(ri, rv, acc_ref)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.bits(H.to_host(acc)), H.bits(acc_ref))
