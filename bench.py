@@ -165,8 +165,7 @@ def main() -> int:
             B.adatopk_decompress_sorted(idx, val, k, y)
         else:
             B.adatopk_compress_segmented(xs[i % NBUF], ks, idx, val, off, err, ws)
-            for s_ in range(S):
-                B.adatopk_decompress_sorted(idx[off[s_]:off[s_ + 1]], val[off[s_]:off[s_ + 1]], ks[s_], ys[s_])
+            B.adatopk_decompress_segmented(idx, val, off, ys)
 
     for i in range(args.warmup):
         step(i)
@@ -210,12 +209,12 @@ def main() -> int:
     stage_us = {nm: (1e3 * acc[j] / cnt[j] if cnt[j] else None) for j, nm in enumerate(names)}
 
     # algorithmic bytes per launch of the full-size kernels (b bytes per value, n elements, k kept);
-    # in the segmented workload k_merge runs once per tensor, so its launch moves 1/S of the bytes
+    # the segmented workload decompresses all its tensors in one k_merge launch as well
     b = esize
     algo = {
         "k_hist1": b * n,                          # one read of the input
         "k_gather": b * n + (4 + b) * k,           # second read of the input + the (index, value) pairs
-        "k_merge": (b * n + (4 + b) * k) // S,     # one write of the dense output + the pairs read
+        "k_merge": b * n + (4 + b) * k,            # one write of the dense output + the pairs read
     }
     dom = max(algo, key=lambda nm: stage_us[nm] or 0.0)
     dom_s = stage_us[dom] * 1e-6

@@ -113,6 +113,20 @@ adatopk_status adatopk_compress_segmented(const void *const *dense, const int64_
                                           const int64_t *out_offset, float *err_norm_out,
                                           void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Segmented decompress, the counterpart of adatopk_compress_segmented: S tensors in as few
+ * launches as fit, tensor s from the pairs [out_offset[s], out_offset[s+1]) of idx / val, which
+ * must be strictly ascending within each tensor (as adatopk_compress_segmented writes them; the
+ * same promise, and the same memory safety without it, as adatopk_decompress_sorted).
+ *   idx, val    device, out_offset[S] entries
+ *   out_offset  host array of S+1 entries, out_offset[0] = 0, non-decreasing
+ *   dense_out   host array of S device pointers; tensor s has n[s] values of type dt
+ *   n           host array of S entries
+ * The host arrays are read before the call returns.  EINVAL: S < 0, offsets that decrease or give
+ * more pairs than elements, n[s] outside [0, 2^31), NULL or misaligned buffers. */
+adatopk_status adatopk_decompress_segmented(const int32_t *idx, const void *val, const int64_t *out_offset, int32_t S,
+                                            adatopk_dtype dt, void *const *dense_out, const int64_t *n,
+                                            void *hip_stream);
+
 /* ---- Wire message.  What one compressed tensor looks like on the link: the (index, value) pairs
  * of Sec. 5.1 behind a fixed header that carries what the paper's message descriptor keeps for
  * compression (its Compress_cfg field, Sec. 3.4: the algorithm, the ratio, further parameters).

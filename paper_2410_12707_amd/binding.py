@@ -50,6 +50,8 @@ def load_library() -> ctypes.CDLL:
     lib.adatopk_decompress_sorted.restype = i32
     lib.adatopk_decompress_accumulate.argtypes = [p, p, i64, i32, p, i64, p]
     lib.adatopk_decompress_accumulate.restype = i32
+    lib.adatopk_decompress_segmented.argtypes = [p, p, p, i32, i32, p, p, p]
+    lib.adatopk_decompress_segmented.restype = i32
     lib.adatopk_wire_bytes.argtypes = [i64, i32, i32]
     lib.adatopk_wire_bytes.restype = sz
     lib.adatopk_wire_keep_count.argtypes = [sz, i32, i32]
@@ -155,6 +157,19 @@ def adatopk_decompress_accumulate(idx: torch.Tensor, val: torch.Tensor, k: int, 
     _check(lib.adatopk_decompress_accumulate(_dev(idx), _dev(val), int(k), _dtype_code(dense_inout.dtype),
                                              _dev(dense_inout), dense_inout.numel(), _stream()),
            "adatopk_decompress_accumulate")
+
+
+def adatopk_decompress_segmented(idx: torch.Tensor, val: torch.Tensor, out_offset: Sequence[int],
+                                 dense_out: Sequence[torch.Tensor]) -> None:
+    """Decompress of S tensors from the concatenated, per-tensor ascending pairs in few launches."""
+    lib = load_library()
+    S = len(dense_out)
+    dt = _dtype_code(dense_out[0].dtype) if S else F32
+    ptrs = (ctypes.c_void_p * max(S, 1))(*[_dev(t) for t in dense_out])
+    ns = (ctypes.c_int64 * max(S, 1))(*[t.numel() for t in dense_out])
+    off = (ctypes.c_int64 * (S + 1))(*[int(v) for v in out_offset])
+    _check(lib.adatopk_decompress_segmented(_dev(idx), _dev(val), off, S, dt, ptrs, ns, _stream()),
+           "adatopk_decompress_segmented")
 
 
 class WireHeader(ctypes.Structure):

@@ -1160,18 +1160,17 @@ __device__ __forceinline__ uint32_t wave_lower_bound(const I *idx, uint32_t k, i
 // Every output byte is written by one workgroup only; an entry whose index lies outside the span
 // that the search assigned it to (possible only when idx is not ascending) is skipped.
 template <typename R, typename I>
-__global__ __launch_bounds__(BLOCK) void k_merge(const I *idx, const R *val, uint32_t k, unsigned char *y,
-                                                 size_t total, size_t head, size_t span) {
-    __shared__ uint32_t s_range[2];
-    const size_t byte_a = blockIdx.x == 0 ? 0 : head + static_cast<size_t>(blockIdx.x) * span;
-    const size_t byte_b = blockIdx.x + 1 == gridDim.x ? total : head + static_cast<size_t>(blockIdx.x + 1) * span;
+__device__ __forceinline__ void merge_span(const I *idx, const R *val, uint32_t k, unsigned char *y, size_t total,
+                                           size_t head, size_t span, uint32_t blk, uint32_t nblk, uint32_t *s_range) {
+    const size_t byte_a = blk == 0 ? 0 : head + static_cast<size_t>(blk) * span;
+    const size_t byte_b = blk + 1 == nblk ? total : head + static_cast<size_t>(blk + 1) * span;
     const int64_t ea = static_cast<int64_t>(byte_a / sizeof(R)), eb = static_cast<int64_t>(byte_b / sizeof(R));
     const int w = threadIdx.x >> 6;
     if (w < 2) {
         const uint32_t pos = wave_lower_bound(idx, k, w == 0 ? ea : eb);
         if ((threadIdx.x & 63) == 0) s_range[w] = pos;
     }
-    const size_t va = blockIdx.x == 0 ? (head < byte_b ? head : byte_b) : byte_a;  // aligned start
+    const size_t va = blk == 0 ? (head < byte_b ? head : byte_b) : byte_a;  // aligned start
     const size_t nvec = (byte_b - va) / 16;
     uint4 *body = reinterpret_cast<uint4 *>(y + va);
     const uint4 z = make_uint4(0, 0, 0, 0);
@@ -1196,12 +1195,11 @@ __global__ __launch_bounds__(BLOCK) void k_merge(const I *idx, const R *val, uin
 // ascending) is skipped: every store stays inside the span.
 constexpr int MERGE_PIECE = 32768;  // bytes of LDS per piece
 template <typename R, typename I>
-__global__ __launch_bounds__(BLOCK) void k_merge_lds(const I *idx, const R *val, uint32_t k, unsigned char *y,
-                                                     size_t total, size_t head, size_t span) {
-    __shared__ __attribute__((aligned(16))) unsigned char piece[MERGE_PIECE];
-    __shared__ uint32_t s_range[2];
-    const size_t byte_a = blockIdx.x == 0 ? 0 : head + static_cast<size_t>(blockIdx.x) * span;
-    const size_t byte_b = blockIdx.x + 1 == gridDim.x ? total : head + static_cast<size_t>(blockIdx.x + 1) * span;
+__device__ __forceinline__ void merge_span_lds(const I *idx, const R *val, uint32_t k, unsigned char *y, size_t total,
+                                               size_t head, size_t span, uint32_t blk, uint32_t nblk,
+                                               unsigned char *piece, uint32_t *s_range) {
+    const size_t byte_a = blk == 0 ? 0 : head + static_cast<size_t>(blk) * span;
+    const size_t byte_b = blk + 1 == nblk ? total : head + static_cast<size_t>(blk + 1) * span;
     const int w = threadIdx.x >> 6;
     if (w < 2) {
         const int64_t bound = static_cast<int64_t>((w == 0 ? byte_a : byte_b) / sizeof(R));
@@ -1210,7 +1208,7 @@ __global__ __launch_bounds__(BLOCK) void k_merge_lds(const I *idx, const R *val,
     }
     // unaligned head of the whole tensor (workgroup 0 only, < 16 bytes): entries there are written
     // after the zeros by the same thread order below, so handle it as part of the first piece
-    const size_t va = blockIdx.x == 0 ? (head < byte_b ? head : byte_b) : byte_a;  // 16-byte aligned start
+    const size_t va = blk == 0 ? (head < byte_b ? head : byte_b) : byte_a;  // 16-byte aligned start
     __syncthreads();
     uint32_t j = s_range[0] + threadIdx.x;  // this thread's next entry
     const uint32_t jb = s_range[1];
@@ -1245,6 +1243,59 @@ __global__ __launch_bounds__(BLOCK) void k_merge_lds(const I *idx, const R *val,
         for (size_t i = p0 + nvec * 16 + threadIdx.x; i < p1; i += BLOCK) y[i] = piece[i - p0];  // ragged end of the tensor
         __syncthreads();
     }
+}
+
+template <typename R, typename I>
+__global__ __launch_bounds__(BLOCK) void k_merge(const I *idx, const R *val, uint32_t k, unsigned char *y,
+                                                 size_t total, size_t head, size_t span) {
+    __shared__ uint32_t s_range[2];
+    merge_span<R, I>(idx, val, k, y, total, head, span, blockIdx.x, gridDim.x, s_range);
+}
+
+template <typename R, typename I>
+__global__ __launch_bounds__(BLOCK) void k_merge_lds(const I *idx, const R *val, uint32_t k, unsigned char *y,
+                                                     size_t total, size_t head, size_t span) {
+    __shared__ __attribute__((aligned(16))) unsigned char piece[MERGE_PIECE];
+    __shared__ uint32_t s_range[2];
+    merge_span_lds<R, I>(idx, val, k, y, total, head, span, blockIdx.x, gridDim.x, piece, s_range);
+}
+
+// Decompress of several tensors in one launch: the spans of all tensors form one grid, a table in
+// the kernel arguments says which workgroups belong to which tensor, and every workgroup runs the
+// one-tensor code above on its span (the sparse or the LDS-built variant, per tensor).
+constexpr int MERGE_MAXSEG = 48;
+struct MergeSeg {
+    unsigned char *y;
+    const int32_t *idx;
+    const void *val;
+    size_t total, head, span;
+    uint32_t k;
+    uint32_t first_block, nblocks;
+    uint32_t dense;
+};
+struct MergeLaunch {
+    MergeSeg seg[MERGE_MAXSEG];
+    int32_t S;
+};
+static_assert(sizeof(MergeLaunch) <= 4096, "kernel arguments stay within 4 KB");
+static_assert(MERGE_MAXSEG <= 64, "one lane per segment");
+
+template <typename R> __global__ __launch_bounds__(BLOCK) void k_merge_seg(const MergeLaunch a) {
+    __shared__ __attribute__((aligned(16))) unsigned char piece[MERGE_PIECE];
+    __shared__ uint32_t s_range[2];
+    const int lane = threadIdx.x & 63;
+    uint32_t first = 0xFFFFFFFFu;
+    if (lane < a.S) first = a.seg[lane].first_block;
+    const uint64_t owner_or_before = __ballot(blockIdx.x >= first);  // first blocks never decrease, the first is 0
+    const int s = 63 - __builtin_clzll(owner_or_before | 1ull);
+    const MergeSeg &sg = a.seg[s];
+    const uint32_t blk = blockIdx.x - sg.first_block;
+    if (sg.dense)
+        merge_span_lds<R, int32_t>(sg.idx, static_cast<const R *>(sg.val), sg.k, sg.y, sg.total, sg.head, sg.span, blk,
+                                   sg.nblocks, piece, s_range);
+    else
+        merge_span<R, int32_t>(sg.idx, static_cast<const R *>(sg.val), sg.k, sg.y, sg.total, sg.head, sg.span, blk,
+                               sg.nblocks, s_range);
 }
 
 __global__ __launch_bounds__(BLOCK) void k_copy16(uint4 *dst, const uint4 *src, size_t n16) {
@@ -1591,6 +1642,56 @@ adatopk_status decompress_sorted_impl(const void *idx, int ib, const void *val, 
     return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
 }
 
+// ---- decompress of several tensors (ascending indices per tensor) in as few launches as the table allows
+adatopk_status decompress_segmented_impl(const int32_t *idx, const void *val, const int64_t *out_offset, int32_t S,
+                                         adatopk_dtype dt, void *const *dense_out, const int64_t *n, hipStream_t st) {
+    if (!dtype_ok(dt) || S < 0) return ADATOPK_EINVAL;
+    if (S == 0) return ADATOPK_OK;
+    if (!out_offset || !dense_out || !n || out_offset[0] != 0) return ADATOPK_EINVAL;
+    const int es = elem_size(dt);
+    size_t bytes_all = 0;
+    for (int32_t s = 0; s < S; ++s) {
+        const int64_t k = out_offset[s + 1] - out_offset[s];
+        if (n[s] < 0 || n[s] >= (static_cast<int64_t>(1) << 31) || k < 0 || k > n[s]) return ADATOPK_EINVAL;
+        if (n[s] > 0 && (!dense_out[s] || reinterpret_cast<uintptr_t>(dense_out[s]) % es)) return ADATOPK_EINVAL;
+        bytes_all += static_cast<size_t>(n[s]) * es;
+    }
+    if (out_offset[S] > 0 && (!idx || !val || reinterpret_cast<uintptr_t>(idx) % 4 || reinterpret_cast<uintptr_t>(val) % es))
+        return ADATOPK_EINVAL;
+    // one span size for the call: about 2 * MERGE_SPANS workgroups over all tensors
+    size_t span = (bytes_all / (2 * MERGE_SPANS) + 15) / 16 * 16;
+    if (span < MERGE_MIN_SPAN) span = MERGE_MIN_SPAN;
+    for (int32_t s0 = 0; s0 < S; s0 += MERGE_MAXSEG) {
+        MergeLaunch a{};
+        a.S = (S - s0 < MERGE_MAXSEG) ? S - s0 : MERGE_MAXSEG;
+        uint64_t blocks = 0;
+        for (int32_t i = 0; i < a.S; ++i) {
+            const int32_t s = s0 + i;
+            MergeSeg &g = a.seg[i];
+            const int64_t k = out_offset[s + 1] - out_offset[s];
+            g.y = static_cast<unsigned char *>(dense_out[s]);
+            g.idx = idx + out_offset[s];
+            g.val = static_cast<const char *>(val) + static_cast<size_t>(out_offset[s]) * es;
+            g.total = static_cast<size_t>(n[s]) * es;
+            g.head = (16 - reinterpret_cast<uintptr_t>(dense_out[s]) % 16) % 16;
+            if (g.head > g.total) g.head = g.total;
+            g.span = span;
+            g.k = static_cast<uint32_t>(k);
+            g.first_block = static_cast<uint32_t>(blocks);
+            g.nblocks = n[s] > 0 ? static_cast<uint32_t>((g.total - g.head) / span + 1) : 0u;
+            g.dense = k > n[s] / MERGE_DENSE_RATIO ? 1u : 0u;
+            blocks += g.nblocks;
+        }
+        if (blocks == 0) continue;
+        if (blocks > 0x7FFFFFFFull) return ADATOPK_EINVAL;
+        const dim3 grid(static_cast<unsigned>(blocks));
+        if (es == 4) launch(ST_MERGE, k_merge_seg<uint32_t>, grid, st, a);
+        else launch(ST_MERGE, k_merge_seg<uint16_t>, grid, st, a);
+        if (hipGetLastError() != hipSuccess) return ADATOPK_ERUNTIME;
+    }
+    return ADATOPK_OK;
+}
+
 // ---- wire message: header | indices, padded to 16 bytes | values
 inline size_t wire_val_offset(int64_t k, int index_bytes) {
     return sizeof(adatopk_wire_header) + align_up(static_cast<size_t>(k) * index_bytes, 16);
@@ -1649,6 +1750,12 @@ adatopk_status adatopk_decompress_accumulate(const int32_t *idx, const void *val
 adatopk_status adatopk_decompress_sorted(const int32_t *idx, const void *val, int64_t k, adatopk_dtype dt,
                                          void *dense_out, int64_t n, void *hip_stream) {
     return decompress_sorted_impl(idx, 4, val, k, dt, dense_out, n, static_cast<hipStream_t>(hip_stream));
+}
+
+adatopk_status adatopk_decompress_segmented(const int32_t *idx, const void *val, const int64_t *out_offset, int32_t S,
+                                            adatopk_dtype dt, void *const *dense_out, const int64_t *n,
+                                            void *hip_stream) {
+    return decompress_segmented_impl(idx, val, out_offset, S, dt, dense_out, n, static_cast<hipStream_t>(hip_stream));
 }
 
 // ---- wire format

@@ -79,6 +79,24 @@ def gpu_compress_segmented(xs, ks, want_err: bool = True):
     return to_host(idx)[:tot], to_host(val)[:tot], off, (to_host(err)[:S] if want_err else None)
 
 
+def gpu_decompress_segmented(idx: np.ndarray, val: np.ndarray, off, ns):
+    """One segmented decompress call into poisoned buffers with guard elements; returns the S tensors."""
+    S = len(ns)
+    tot = int(off[S])
+    tdt = torch_dtype(val.dtype)
+    di = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)).cuda() if tot else torch.zeros(1, dtype=torch.int32, device="cuda")
+    dv = to_device(val) if tot else torch.zeros(1, dtype=tdt, device="cuda")
+    bufs = [torch.full((n + 8,), 7.0, dtype=tdt, device="cuda") for n in ns]
+    B.adatopk_decompress_segmented(di, dv, [int(v) for v in off], [b[:n] for b, n in zip(bufs, ns)])
+    torch.cuda.synchronize()
+    poison = bits(to_host(torch.full((8,), 7.0, dtype=tdt)))
+    outs = []
+    for b, n in zip(bufs, ns):
+        assert np.all(bits(to_host(b[n:])) == poison), "segmented decompress wrote past a tensor"
+        outs.append(to_host(b[:n]))
+    return outs
+
+
 def same_err(e_gpu, e_ref, rtol=1e-5) -> bool:
     e_gpu, e_ref = float(e_gpu), float(e_ref)
     if np.isnan(e_ref) or np.isinf(e_ref):

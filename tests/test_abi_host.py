@@ -186,3 +186,23 @@ def test_wire_calls_reject_bad_arguments_before_touching_the_device(lib):
     assert d(fake, cap, 0, 4, 9, 0, fake, None) == EINVAL         # k = 10 > n
     assert d(fake + 4, cap, 0, 4, 1000, 0, fake, None) == EINVAL
     assert d(fake, cap, 0, 4, 1000, 1, None, None) == EINVAL
+
+
+def test_segmented_decompress_rejects_bad_tables(lib):
+    EINVAL = 1
+    fake = 0x1000
+    P = ctypes.c_void_p * 2
+    I = ctypes.c_int64 * 2
+    O = ctypes.c_int64 * 3
+    f = lib.adatopk_decompress_segmented
+    f.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                  ctypes.c_void_p, ctypes.c_void_p]
+    assert f(fake, fake, O(0, 10, 20), -1, 0, P(fake, fake), I(100, 100), None) == EINVAL
+    assert f(fake, fake, O(1, 10, 20), 2, 0, P(fake, fake), I(100, 100), None) == EINVAL   # offsets start at 0
+    assert f(fake, fake, O(0, 10, 5), 2, 0, P(fake, fake), I(100, 100), None) == EINVAL    # decreasing
+    assert f(fake, fake, O(0, 10, 120), 2, 0, P(fake, fake), I(100, 100), None) == EINVAL  # more pairs than elements
+    assert f(fake, fake, O(0, 10, 20), 2, 0, P(fake, None), I(100, 100), None) == EINVAL
+    assert f(fake, fake, O(0, 10, 20), 2, 0, P(fake, fake + 2), I(100, 100), None) == EINVAL
+    assert f(None, fake, O(0, 10, 20), 2, 0, P(fake, fake), I(100, 100), None) == EINVAL
+    assert f(fake, fake, O(0, 10, 20), 2, 7, P(fake, fake), I(100, 100), None) == EINVAL
+    assert f(fake, fake, O(0, 0, 0), 0, 0, P(fake, fake), I(100, 100), None) == 0  # S = 0: nothing to do

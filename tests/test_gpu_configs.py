@@ -56,6 +56,9 @@ def test_config4_segmented_adaptive_ratios():
         assert np.array_equal(gi[off[s]:off[s + 1]], ri), s
         assert np.array_equal(H.bits(gv[off[s]:off[s + 1]]), H.bits(rv)), s
         assert H.same_err(ge[s], re, ERR_RTOL), (s, ge[s], re)
+    ys = H.gpu_decompress_segmented(gi, gv, off, [t.size for t in w.tensors])  # all 24 tensors in one launch
+    for s, (ri, rv, re) in enumerate(refs):
+        assert np.array_equal(H.bits(ys[s]), H.bits(orc.decompress(ri, rv, w.tensors[s].size))), s
 
 
 def test_config5_bf16_ties_at_threshold():

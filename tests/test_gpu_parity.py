@@ -135,6 +135,16 @@ def test_segmented_mixed_lengths():
     assert np.array_equal(off, roff) and np.array_equal(gi, ri) and np.array_equal(H.bits(gv), H.bits(rv))
     for s in range(len(xs)):
         assert H.same_err(ge[s], re[s], ERR_RTOL), (s, ge[s], re[s])
+    check_segmented_decompress(gi, gv, off, lens)
+
+
+def check_segmented_decompress(gi, gv, off, lens):
+    import gpu_harness as H
+
+    ys = H.gpu_decompress_segmented(gi, gv, off, lens)
+    for s, n in enumerate(lens):
+        ref = orc.decompress(gi[off[s]:off[s + 1]], gv[off[s]:off[s + 1]], n)
+        assert np.array_equal(H.bits(ys[s]), H.bits(ref)), ("segmented decompress, tensor", s, n)
 
 
 def test_segmented_more_segments_than_one_launch_holds():
@@ -149,6 +159,7 @@ def test_segmented_more_segments_than_one_launch_holds():
         ri, rv, roff, re = orc.compress_segmented(xs, ks)
         assert np.array_equal(gi, ri) and np.array_equal(H.bits(gv), H.bits(rv))
         assert all(H.same_err(ge[s], re[s], ERR_RTOL) for s in range(len(xs)))
+        check_segmented_decompress(gi, gv, off, lens)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
@@ -234,6 +245,7 @@ def test_many_small_tensors_in_one_call(dtype, limit):
     assert np.array_equal(off, roff) and np.array_equal(gi, ri) and np.array_equal(H.bits(gv), H.bits(rv))
     for s in range(len(xs)):
         assert H.same_err(ge[s], re[s], ERR_RTOL), (s, lens[s], ks[s], ge[s], re[s])
+    check_segmented_decompress(gi, gv, off, lens)
 
 
 def test_small_tensor_limit_and_one_past_it():
