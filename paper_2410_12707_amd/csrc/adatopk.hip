@@ -80,6 +80,10 @@ constexpr int LB_TOTAL = 4096;      // list blocks aimed at per launch, all segm
 constexpr size_t MERGE_SPANS = ADATOPK_MERGE_SPANS;  // output spans aimed at by the one-kernel decompress
 constexpr int64_t MERGE_DENSE_RATIO = 32;  // k > n / 32 takes the LDS-built variant of the one-kernel decompress
 constexpr size_t MERGE_MIN_SPAN = 16384;  // bytes; smaller outputs use fewer workgroups
+#ifndef ADATOPK_MERGE_MAX_SPAN
+#define ADATOPK_MERGE_MAX_SPAN 98304
+#endif
+constexpr size_t MERGE_MAX_SPAN = ADATOPK_MERGE_MAX_SPAN;  // bytes; larger outputs use more workgroups
 static_assert(LU * NW <= 64, "per-tile wave counts must fit one wavefront scan");
 static_assert(HREP == 1 || HREP == 2 || HREP == 4 || HREP == 8, "histogram copies");
 static_assert(NB1 % BLOCK == 0 && NB2 % BLOCK == 0 && NB3 % BLOCK == 0, "bins split evenly over threads");
@@ -1546,6 +1550,16 @@ adatopk_status fill_impl(void *dst, size_t bytes, hipStream_t st) {  // the k_fi
     return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
 }
 
+// Bytes of output per workgroup of the one-kernel decompress: about MERGE_SPANS workgroups, but
+// spans neither so small that the search dominates nor so large that big outputs get too few
+// workgroups (a multiple of 16).
+inline size_t merge_span_bytes(size_t bytes) {
+    size_t span = (bytes / MERGE_SPANS + 15) / 16 * 16;
+    if (span < MERGE_MIN_SPAN) span = MERGE_MIN_SPAN;
+    if (span > MERGE_MAX_SPAN) span = MERGE_MAX_SPAN;
+    return span;
+}
+
 // ---- decompress, for either index width
 adatopk_status check_pairs(const void *idx, int ib, const void *val, int64_t k, adatopk_dtype dt, const void *dense,
                            int64_t n) {
@@ -1624,8 +1638,7 @@ adatopk_status decompress_sorted_impl(const void *idx, int ib, const void *val, 
     size_t head = (16 - reinterpret_cast<uintptr_t>(dense_out) % 16) % 16;
     if (head > total) head = total;
     const size_t body = total - head;
-    size_t span = (body / MERGE_SPANS + 15) / 16 * 16;
-    if (span < MERGE_MIN_SPAN) span = MERGE_MIN_SPAN;
+    const size_t span = merge_span_bytes(body);
     const unsigned grid = static_cast<unsigned>(body / span + 1);  // the last workgroup takes the remainder
     const bool dense = k > n / MERGE_DENSE_RATIO;  // more than one entry per few lines: build the lines in LDS
     const uint32_t ku = static_cast<uint32_t>(k);
@@ -1658,9 +1671,7 @@ adatopk_status decompress_segmented_impl(const int32_t *idx, const void *val, co
     }
     if (out_offset[S] > 0 && (!idx || !val || reinterpret_cast<uintptr_t>(idx) % 4 || reinterpret_cast<uintptr_t>(val) % es))
         return ADATOPK_EINVAL;
-    // one span size for the call: about 2 * MERGE_SPANS workgroups over all tensors
-    size_t span = (bytes_all / (2 * MERGE_SPANS) + 15) / 16 * 16;
-    if (span < MERGE_MIN_SPAN) span = MERGE_MIN_SPAN;
+    const size_t span = merge_span_bytes(bytes_all);  // one span size for the call
     for (int32_t s0 = 0; s0 < S; s0 += MERGE_MAXSEG) {
         MergeLaunch a{};
         a.S = (S - s0 < MERGE_MAXSEG) ? S - s0 : MERGE_MAXSEG;
