@@ -131,6 +131,33 @@ def config5() -> Workload:
                     "GPT-2-XL hidden activation rounded to bf16: many ties at the threshold")
 
 
+def config5_f16() -> Workload:
+    n = 16 * 1024 * 1600
+    return Workload("cfg5h_gpt2xl_hidden_16x1024x1600_f16_k0.5pct", "f16", (16, 1024, 1600),
+                    [normal_f16(n, BASE_SEED + 5)], [keep_count(n, 5, 1000)],
+                    "GPT-2-XL hidden activation rounded to IEEE binary16")
+
+
+def config_small(num_tensors: int = 128) -> Workload:
+    """Many small messages in one call: the launch-bound regime of small models on small inputs
+    (the paper's ResNet-18 runs on 3x32x32 images, Sec. 7.1): 1024 to 8192 elements each, k = 1 %."""
+    sizes = [8192, 4096, 2048, 1024]  # 512x4x4, 256x4x4, 128x4x4, 64x4x4
+    ns = [sizes[i % len(sizes)] for i in range(num_tensors)]
+    tensors = [normal_f32(n, BASE_SEED + 6 + 100 * s) for s, n in enumerate(ns)]
+    return Workload("small_%dx_1k_to_8k_f32_k1pct" % num_tensors, "f32", (num_tensors,), tensors,
+                    [keep_count(n, 1, 100) for n in ns], "many small messages, N(0,1)")
+
+
+def config_resnet18_samples(num_tensors: int = 64) -> Workload:
+    """Per-sample stage outputs of a ResNet-18 on 32x32 inputs (64x32x32, 128x16x16, 256x8x8, 512x4x4),
+    many of them in one call, k = 1 %."""
+    sizes = [65536, 32768, 16384, 8192]
+    ns = [sizes[i % len(sizes)] for i in range(num_tensors)]
+    tensors = [normal_f32(n, BASE_SEED + 7 + 100 * s) for s, n in enumerate(ns)]
+    return Workload("resnet18_samples_%dx_8k_to_64k_f32_k1pct" % num_tensors, "f32", (num_tensors,), tensors,
+                    [keep_count(n, 1, 100) for n in ns], "per-sample ResNet-18 stage outputs, N(0,1)")
+
+
 def small_case(kind: str, n: int, seed: int, dtype: str = "f32") -> np.ndarray:
     """Small adversarial inputs for parity tests.  ``kind`` picks the value structure."""
     rng = _rng(seed)
