@@ -5,8 +5,8 @@
 // back into zeros.  Sec. 5.2 (Eq. "adacompress") gives every slow link its own ratio, so
 // the launch is segmented: S tensors, each with its own k, one launch per pass for all.
 //
-// Method.  key(x) = bits(x) with the sign cleared (bf16 is widened to the fp32 pattern, so
-// both types share one 31-bit key).  The exact k-th largest key T is found by a 3-level
+// Method.  key(x) = bits(x) with the sign cleared (a 16-bit pattern, bf16 or fp16, is moved to
+// the upper half, so all types share one 31-bit key).  The exact k-th largest key T is found by a 3-level
 // MSD radix select with digits of 11 / 10 / 10 bits:
 //   k_hist1   one read of the input: per-chunk LDS histogram of the top digit; every chunk stores
 //             the suffix sums of its histogram (one row per chunk, plus every 32nd entry of it
@@ -33,7 +33,15 @@
 // is the same from run to run.
 //
 // Decompress: k_fill (16-byte zero stores) then k_scatter; for ascending indices k_merge does
-// both in one kernel, every workgroup filling its own span and writing the entries that fall in it.
+// both in one kernel, every workgroup filling its own span and writing the entries that fall in it
+// (k_merge_seg: the same for all tensors of a segmented batch in one launch); k_scatter_add adds
+// the pairs into an existing tensor.
+//
+// Tensors of at most one register tile (8192 elements) skip all of the above: k_small selects
+// and writes one tensor per workgroup in a single launch.
+//
+// Outputs can be laid out as one wire message (header, indices, values); indices are stored as
+// int32 or, for the paper's own accounting (Sec. 5.2), int64.
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 #include <hip/hip_fp16.h>
