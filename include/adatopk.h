@@ -19,7 +19,7 @@
  * Conventions for every call:
  *   - "device" pointers are HIP device memory of the current device; "host" pointers
  *     are ordinary process memory.  The caller owns every buffer.  The library never
- *     allocates, frees or synchronises, and copies nothing back to the host: all
+ *     allocates or frees device memory, never synchronises, and copies nothing back to the host: all
  *     work is enqueued on `hip_stream` (a hipStream_t, NULL = the default stream)
  *     and the call returns at once.  Output sizes are known beforehand (exactly k).
  *   - a tensor is its flat contiguous buffer; indices are int32 and local to the
@@ -179,6 +179,20 @@ adatopk_status adatopk_wire_parse_header(const void *host_bytes, size_t wire_byt
 adatopk_status adatopk_compress_wire(const void *dense, int64_t n, adatopk_dtype dt, int64_t k, int32_t index_bytes,
                                      double ratio, void *wire_out, size_t wire_capacity, void *workspace,
                                      size_t workspace_bytes, void *hip_stream);
+
+/* adatopk_compress_segmented with every tensor written as its own wire message into one buffer:
+ * a node that feeds several links compresses all its outgoing tensors in one call and hands each
+ * link its message.
+ *   ratio        host array of S entries stored in the headers, or NULL to store n[s] / k[s]
+ *   wire_out     device, 16-byte aligned
+ *   wire_offset  host array of S entries: message s starts at byte wire_offset[s] (a multiple of
+ *                16) and is adatopk_wire_bytes(k[s], dt, index_bytes) long; ascending, no overlap,
+ *                the last one ends within wire_capacity
+ * Everything else as adatopk_compress_segmented. */
+adatopk_status adatopk_compress_wire_segmented(const void *const *dense, const int64_t *n, const int64_t *k, int32_t S,
+                                               adatopk_dtype dt, int32_t index_bytes, const double *ratio,
+                                               void *wire_out, const int64_t *wire_offset, size_t wire_capacity,
+                                               void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Decompression of a wire message in device memory.  The receiver knows dt, index_bytes and n (the
  * tensor's shape is part of the graph); k follows from wire_bytes.  The device-side header is not

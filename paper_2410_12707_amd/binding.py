@@ -60,6 +60,8 @@ def load_library() -> ctypes.CDLL:
     lib.adatopk_wire_parse_header.restype = i32
     lib.adatopk_compress_wire.argtypes = [p, i64, i32, i64, i32, ctypes.c_double, p, sz, p, sz, p]
     lib.adatopk_compress_wire.restype = i32
+    lib.adatopk_compress_wire_segmented.argtypes = [p, p, p, i32, i32, i32, p, p, p, sz, p, sz, p]
+    lib.adatopk_compress_wire_segmented.restype = i32
     lib.adatopk_decompress_wire.argtypes = [p, sz, i32, i32, i64, i32, p, p]
     lib.adatopk_decompress_wire.restype = i32
     lib.adatopk_compress_segmented.argtypes = [p, p, p, i32, i32, p, p, p, p, p, sz, p]
@@ -204,6 +206,23 @@ def adatopk_compress_wire(dense: torch.Tensor, k: int, index_bytes: int, ratio: 
     _check(lib.adatopk_compress_wire(_dev(dense), dense.numel(), _dtype_code(dense.dtype), int(k), int(index_bytes),
                                      float(ratio), _dev(wire_out), wire_out.numel() * wire_out.element_size(),
                                      _dev(workspace), workspace.numel(), _stream()), "adatopk_compress_wire")
+
+
+def adatopk_compress_wire_segmented(dense: Sequence[torch.Tensor], ks: Sequence[int], index_bytes: int,
+                                    ratios: Optional[Sequence[float]], wire_out: torch.Tensor,
+                                    wire_offset: Sequence[int], workspace: torch.Tensor) -> None:
+    """One wire message per tensor, message s at byte wire_offset[s] of the uint8 tensor wire_out."""
+    lib = load_library()
+    S = len(dense)
+    dt = _dtype_code(dense[0].dtype) if S else F32
+    ptrs = (ctypes.c_void_p * max(S, 1))(*[_dev(t) for t in dense])
+    ns = (ctypes.c_int64 * max(S, 1))(*[t.numel() for t in dense])
+    kk = (ctypes.c_int64 * max(S, 1))(*[int(v) for v in ks])
+    off = (ctypes.c_int64 * max(S, 1))(*[int(v) for v in wire_offset])
+    rr = _dbl_array(ratios) if ratios is not None else None
+    _check(lib.adatopk_compress_wire_segmented(ptrs, ns, kk, S, dt, int(index_bytes), rr, _dev(wire_out), off,
+                                               wire_out.numel() * wire_out.element_size(), _dev(workspace),
+                                               workspace.numel(), _stream()), "adatopk_compress_wire_segmented")
 
 
 def adatopk_decompress_wire(wire: torch.Tensor, wire_bytes: int, index_bytes: int, dense: torch.Tensor,

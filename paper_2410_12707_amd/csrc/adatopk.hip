@@ -48,6 +48,7 @@
 
 #include <stdint.h>
 #include <stddef.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include "adatopk.h"
@@ -110,7 +111,7 @@ static_assert(sizeof(SegState) == 64, "state record size");
 
 struct SegDesc {
     const void *x;       // device pointer of the tensor
-    int64_t out_off;     // first output slot of this segment
+    int64_t out_off;     // first output slot of this segment; in wire mode the byte offset of its index section
     int64_t l_base;      // first candidate-list slot of this segment
     int32_t n, k;
     int32_t chunk_begin, nchunks;
@@ -138,8 +139,34 @@ struct Launch {
     void *val_out;
     float *err_out;
     uint32_t idx64;
+    uint32_t wire;     // outputs are wire messages in one buffer (idx_out): values follow the padded index section
 };
 static_assert(sizeof(Launch) <= 4096, "kernel arguments stay within 4 KB");
+
+// Where a segment's k pairs go.  Plain mode: element out_off of the idx / val arrays.  Wire mode:
+// byte out_off of the message buffer holds the indices, the values start at the next multiple of
+// 16 bytes behind them.
+struct OutPtrs {
+    int32_t *i32;
+    int64_t *i64;
+    void *val;
+};
+__device__ __forceinline__ OutPtrs out_ptrs(void *idx_out, void *val_out, int64_t out_off, uint32_t k, bool idx64,
+                                            bool wire, int elem_bytes) {
+    OutPtrs o;
+    if (wire) {
+        char *base = static_cast<char *>(idx_out) + out_off;
+        const size_t idx_bytes = (static_cast<size_t>(k) * (idx64 ? 8 : 4) + 15) / 16 * 16;
+        o.i32 = reinterpret_cast<int32_t *>(base);
+        o.i64 = reinterpret_cast<int64_t *>(base);
+        o.val = base + idx_bytes;
+    } else {
+        o.i32 = static_cast<int32_t *>(idx_out) + out_off;
+        o.i64 = static_cast<int64_t *>(idx_out) + out_off;
+        o.val = static_cast<char *>(val_out) + out_off * elem_bytes;
+    }
+    return o;
+}
 
 // ------------------------------------------------------------------ element access
 // VEC tags the dtype: 4 = fp32 (one element per dword), 8 = bf16 and 9 = fp16 (two per dword, low
@@ -894,10 +921,11 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
 
     const int32_t *Li = a.L_idx + sg.l_base;
     const R *Lv = static_cast<const R *>(a.L_val) + sg.l_base;
-    int32_t *oi = static_cast<int32_t *>(a.idx_out) + sg.out_off;
-    int64_t *oi64 = static_cast<int64_t *>(a.idx_out) + sg.out_off;
     const bool wide = a.idx64 != 0;
-    R *ov = static_cast<R *>(a.val_out) + sg.out_off;
+    const OutPtrs op = out_ptrs(a.idx_out, a.val_out, sg.out_off, kout, wide, a.wire != 0, sizeof(R));
+    int32_t *oi = op.i32;
+    int64_t *oi64 = op.i64;
+    R *ov = static_cast<R *>(op.val);
 
     int buf = 0;
     for (uint32_t t0 = beg; t0 < end; t0 += BLOCK * LU, buf ^= 1) {
@@ -967,6 +995,7 @@ struct SmallLaunch {
     void *val_out;
     float *err_out;
     uint32_t idx64;
+    uint32_t wire;
 };
 static_assert(sizeof(SmallLaunch) <= 3584, "kernel arguments stay below 4 KB");
 static_assert(SMALL_EPT * NW <= 128, "the (slot, wave) counts are scanned two per lane");
@@ -1062,10 +1091,11 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_small(const SmallL
     const uint32_t inc = wave_incl_scan(c0 + c1);
     const uint32_t ex0 = inc - c0 - c1, ex1 = inc - c1;  // counts before entry 2 * lane and before 2 * lane + 1
 
-    int32_t *oi = static_cast<int32_t *>(a.idx_out) + sg.out_off;
-    int64_t *oi64 = static_cast<int64_t *>(a.idx_out) + sg.out_off;
-    R *ov = static_cast<R *>(a.val_out) + sg.out_off;
     const bool wide = a.idx64 != 0;
+    const OutPtrs op = out_ptrs(a.idx_out, a.val_out, sg.out_off, kout, wide, a.wire != 0, sizeof(R));
+    int32_t *oi = op.i32;
+    int64_t *oi64 = op.i64;
+    R *ov = static_cast<R *>(op.val);
     double acc = 0.0;
 #pragma unroll
     for (int e = 0; e < SMALL_EPT; ++e) {
@@ -1356,11 +1386,11 @@ int32_t list_blocks(int64_t n, int32_t S) {
 }
 
 struct Carve {
-    size_t state, G3, rows1, coarse1, rows2, coarse2, chunk_err, rows3, ldef, lerr, L_idx, L_val, total;
+    size_t state, G3, rows1, coarse1, rows2, coarse2, chunk_err, rows3, ldef, lerr, wire_err, L_idx, L_val, total;
 };
 
 // Workspace layout for up to max_chunks chunks, max_lb list blocks and n_total list slots.
-Carve carve(int64_t max_chunks, int64_t max_lb, int64_t n_total, adatopk_dtype dt) {
+Carve carve(int64_t max_chunks, int64_t max_lb, int64_t n_total, int32_t S, adatopk_dtype dt) {
     Carve c;
     size_t p = 0;
     auto take = [&](size_t bytes) {
@@ -1378,6 +1408,7 @@ Carve carve(int64_t max_chunks, int64_t max_lb, int64_t n_total, adatopk_dtype d
     c.rows3 = take(sizeof(uint32_t) * NB3 * max_lb);
     c.ldef = take(sizeof(uint32_t) * max_lb);
     c.lerr = take(sizeof(double) * max_lb);
+    c.wire_err = take(sizeof(float) * static_cast<size_t>(S < 1 ? 1 : S));  // error norms on their way into message headers
     c.L_idx = take(sizeof(int32_t) * static_cast<size_t>(n_total));
     c.L_val = take(static_cast<size_t>(elem_size(dt)) * static_cast<size_t>(n_total));
     c.total = p;
@@ -1425,31 +1456,51 @@ template <int VEC> adatopk_status launch_batch(const Launch &a, int total_chunks
     return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
 }
 
+// Where a compress call writes.  Plain: idx_out / val_out arrays, tensor s at element offset[s]
+// (offset = exclusive scan of k, S + 1 entries).  Wire: one message buffer (idx_out), tensor s's
+// index section at byte offset[s] (S entries), its values behind the padded indices, and the
+// error norms in the workspace (err_out is ignored) for the header kernel to pick up.
+struct OutSpec {
+    void *idx_out;
+    int idx_bytes;
+    void *val_out;
+    const int64_t *offset;
+    bool wire;
+};
+
 adatopk_status compress_impl(const void *const *dense, const int64_t *n, const int64_t *k, int32_t S,
-                             adatopk_dtype dt, void *idx_out, int idx_bytes, void *val_out, const int64_t *out_offset,
-                             float *err_out, void *workspace, size_t workspace_bytes, hipStream_t st,
-                             bool validate_only = false) {
+                             adatopk_dtype dt, const OutSpec &out, float *err_out, void *workspace,
+                             size_t workspace_bytes, hipStream_t st) {
     if (!dtype_ok(dt) || S < 0) return ADATOPK_EINVAL;
     if (S == 0) return ADATOPK_OK;
-    if (!dense || !n || !k || !out_offset) return ADATOPK_EINVAL;
+    if (!dense || !n || !k || !out.offset) return ADATOPK_EINVAL;
     const int es = elem_size(dt);
+    const int idx_bytes = out.idx_bytes;
+    void *const idx_out = out.idx_out;
+    void *const val_out = out.val_out;
+    const int64_t *const out_offset = out.offset;
     int64_t n_total = 0, k_total = 0;
-    if (out_offset[0] != 0) return ADATOPK_EINVAL;
+    if (!out.wire && out_offset[0] != 0) return ADATOPK_EINVAL;
     for (int32_t s = 0; s < S; ++s) {
         if (n[s] < 0 || n[s] >= (static_cast<int64_t>(1) << 31) || k[s] < 0 || k[s] > n[s]) return ADATOPK_EINVAL;
         if (n[s] > 0 && (!dense[s] || reinterpret_cast<uintptr_t>(dense[s]) % es)) return ADATOPK_EINVAL;
-        if (out_offset[s + 1] != out_offset[s] + k[s]) return ADATOPK_EINVAL;
+        if (!out.wire && out_offset[s + 1] != out_offset[s] + k[s]) return ADATOPK_EINVAL;
+        if (out.wire && (out_offset[s] < 0 || out_offset[s] % 16)) return ADATOPK_EINVAL;
         n_total += n[s];
         k_total += k[s];
     }
-    if (k_total > 0 && (!idx_out || !val_out)) return ADATOPK_EINVAL;
-    if (reinterpret_cast<uintptr_t>(idx_out) % idx_bytes || reinterpret_cast<uintptr_t>(val_out) % es ||
+    if (k_total > 0 && (!idx_out || (!out.wire && !val_out))) return ADATOPK_EINVAL;
+    if (reinterpret_cast<uintptr_t>(idx_out) % (out.wire ? 16 : idx_bytes) || reinterpret_cast<uintptr_t>(val_out) % es ||
         reinterpret_cast<uintptr_t>(err_out) % 4)
         return ADATOPK_EINVAL;
     const size_t need = adatopk_workspace_bytes(n_total, S, dt);
     if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return ADATOPK_EINVAL;
     if (workspace_bytes < need) return ADATOPK_EWORKSPACE;
-    if (validate_only) return ADATOPK_OK;
+    int64_t max_chunks, max_lb;
+    bounds_for(n_total, S, dt, &max_chunks, &max_lb);
+    const Carve cv = carve(max_chunks, max_lb, n_total, S, dt);
+    char *ws = static_cast<char *>(workspace);
+    if (out.wire) err_out = reinterpret_cast<float *>(ws + cv.wire_err);
 
     // Only small tensors: one launch, one workgroup per tensor, no workspace traffic.
     bool all_small = true;
@@ -1466,6 +1517,7 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
             }
             sl.idx_out = idx_out;
             sl.idx64 = idx_bytes == 8 ? 1u : 0u;
+            sl.wire = out.wire ? 1u : 0u;
             sl.val_out = val_out;
             sl.err_out = err_out ? err_out + s0 : nullptr;
             if (dt == ADATOPK_F32) launch(ST_SMALL, k_small<TAG_F32>, dim3(cnt), st, sl);
@@ -1475,11 +1527,6 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
         }
         return ADATOPK_OK;
     }
-
-    int64_t max_chunks, max_lb;
-    bounds_for(n_total, S, dt, &max_chunks, &max_lb);
-    const Carve cv = carve(max_chunks, max_lb, n_total, dt);
-    char *ws = static_cast<char *>(workspace);
 
     for (int32_t s0 = 0; s0 < S; s0 += MAXSEG) {
         Launch a{};
@@ -1512,6 +1559,7 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
         a.L_val = ws + cv.L_val;
         a.idx_out = idx_out;
         a.idx64 = idx_bytes == 8 ? 1u : 0u;
+        a.wire = out.wire ? 1u : 0u;
         a.val_out = val_out;
         a.err_out = err_out ? err_out + s0 : nullptr;
         int32_t chunks = 0, lbs = 0;
@@ -1718,13 +1766,92 @@ inline size_t wire_val_offset(int64_t k, int index_bytes) {
 struct WireWords {
     uint32_t w[sizeof(adatopk_wire_header) / 4];
 };
-// Stores the header words (all but the error norm, which k_emit writes) and zeroes the padding
-// bytes [pad_a, pad_b) between the index and the value section (at most 15).
-__global__ __launch_bounds__(BLOCK) void k_wire_header(uint32_t *dst, WireWords words, uint32_t skip_word,
-                                                       unsigned char *base, size_t pad_a, size_t pad_b) {
+// Headers of up to HDR_MAXSEG messages in one launch, after the compress kernels: workgroup s stores
+// the header words of message s (built on the host; the error norm comes from err[s], which the
+// compress kernels left in the workspace) and zeroes the padding between its index and value sections.
+constexpr int HDR_MAXSEG = 48;
+struct HeaderLaunch {
+    WireWords hdr[HDR_MAXSEG];
+    int64_t msg_off[HDR_MAXSEG];  // byte offset of the message in the buffer
+    unsigned char *base;
+    const float *err;
+};
+static_assert(sizeof(HeaderLaunch) <= 4096, "kernel arguments stay within 4 KB");
+__global__ __launch_bounds__(BLOCK) void k_wire_header(const HeaderLaunch a) {
+    const int s = blockIdx.x;
     const uint32_t t = threadIdx.x;
-    if (t < sizeof(adatopk_wire_header) / 4 && t != skip_word) dst[t] = words.w[t];
-    if (pad_a + t < pad_b) base[pad_a + t] = 0;
+    unsigned char *msg = a.base + a.msg_off[s];
+    constexpr uint32_t ERR_WORD = offsetof(adatopk_wire_header, err_norm) / 4;
+    if (t < sizeof(adatopk_wire_header) / 4)
+        reinterpret_cast<uint32_t *>(msg)[t] = (t == ERR_WORD) ? __float_as_uint(a.err[s]) : a.hdr[s].w[t];
+    const WireWords &h = a.hdr[s];
+    const uint64_t k = h.w[offsetof(adatopk_wire_header, k) / 4] |
+                       (static_cast<uint64_t>(h.w[offsetof(adatopk_wire_header, k) / 4 + 1]) << 32);
+    const uint64_t voff = h.w[offsetof(adatopk_wire_header, val_offset) / 4] |
+                          (static_cast<uint64_t>(h.w[offsetof(adatopk_wire_header, val_offset) / 4 + 1]) << 32);
+    const uint32_t ib = h.w[offsetof(adatopk_wire_header, index_bytes) / 4] & 0xFFu;
+    const uint64_t pad_a = sizeof(adatopk_wire_header) + k * ib;
+    if (pad_a + t < voff) msg[pad_a + t] = 0;  // at most 15 bytes
+}
+
+// Compress of S tensors into S wire messages in one buffer (message s at byte msg_off[s]).
+adatopk_status compress_wire_impl(const void *const *dense, const int64_t *n, const int64_t *k, int32_t S,
+                                  adatopk_dtype dt, int32_t index_bytes, const double *ratio, void *wire_out,
+                                  const int64_t *msg_off, size_t wire_capacity, void *workspace,
+                                  size_t workspace_bytes, hipStream_t st) {
+    if (index_bytes != 4 && index_bytes != 8) return ADATOPK_EINVAL;
+    if (!dtype_ok(dt) || S < 0) return ADATOPK_EINVAL;
+    if (S == 0) return ADATOPK_OK;
+    if (!dense || !n || !k || !msg_off || !wire_out || reinterpret_cast<uintptr_t>(wire_out) % 16) return ADATOPK_EINVAL;
+    // messages in ascending, non-overlapping positions inside the buffer
+    int64_t end_prev = 0;
+    for (int32_t s = 0; s < S; ++s) {
+        if (n[s] < 0 || k[s] < 0 || k[s] > n[s] || n[s] >= (static_cast<int64_t>(1) << 31)) return ADATOPK_EINVAL;
+        const size_t bytes = adatopk_wire_bytes(k[s], dt, index_bytes);
+        if (bytes == 0 || msg_off[s] % 16 || msg_off[s] < end_prev) return ADATOPK_EINVAL;
+        end_prev = msg_off[s] + static_cast<int64_t>(bytes);
+    }
+    if (static_cast<uint64_t>(end_prev) > wire_capacity) return ADATOPK_EINVAL;
+    int64_t *idx_off = static_cast<int64_t *>(malloc(sizeof(int64_t) * static_cast<size_t>(S)));
+    if (!idx_off) return ADATOPK_ERUNTIME;
+    for (int32_t s = 0; s < S; ++s) idx_off[s] = msg_off[s] + static_cast<int64_t>(sizeof(adatopk_wire_header));
+    const OutSpec out{wire_out, index_bytes, nullptr, idx_off, true};
+    adatopk_status rc = compress_impl(dense, n, k, S, dt, out, nullptr, workspace, workspace_bytes, st);
+    free(idx_off);
+    if (rc != ADATOPK_OK) return rc;
+    // the error norms are in the workspace now (stream order): write the headers around them
+    int64_t n_total = 0;
+    for (int32_t s = 0; s < S; ++s) n_total += n[s];
+    int64_t max_chunks, max_lb;
+    bounds_for(n_total, S, dt, &max_chunks, &max_lb);
+    const float *err = reinterpret_cast<const float *>(static_cast<char *>(workspace) +
+                                                       carve(max_chunks, max_lb, n_total, S, dt).wire_err);
+    for (int32_t s0 = 0; s0 < S; s0 += HDR_MAXSEG) {
+        HeaderLaunch a{};
+        const int32_t cnt = (S - s0 < HDR_MAXSEG) ? S - s0 : HDR_MAXSEG;
+        for (int32_t i = 0; i < cnt; ++i) {
+            const int32_t s = s0 + i;
+            adatopk_wire_header h;
+            memset(&h, 0, sizeof h);
+            h.magic = ADATOPK_WIRE_MAGIC;
+            h.version = ADATOPK_WIRE_VERSION;
+            h.algorithm = ADATOPK_WIRE_TOPK;
+            h.dtype = static_cast<uint8_t>(dt);
+            h.index_bytes = static_cast<uint8_t>(index_bytes);
+            h.n = n[s];
+            h.k = k[s];
+            h.ratio = ratio ? ratio[s] : (k[s] > 0 ? static_cast<double>(n[s]) / static_cast<double>(k[s]) : 0.0);
+            h.idx_offset = sizeof(adatopk_wire_header);
+            h.val_offset = static_cast<int64_t>(wire_val_offset(k[s], index_bytes));
+            memcpy(&a.hdr[i], &h, sizeof h);
+            a.msg_off[i] = msg_off[s];
+        }
+        a.base = static_cast<unsigned char *>(wire_out);
+        a.err = err + s0;
+        launch(ST_HEADER, k_wire_header, dim3(cnt), st, a);
+        if (hipGetLastError() != hipSuccess) return ADATOPK_ERUNTIME;
+    }
+    return ADATOPK_OK;
 }
 
 }  // namespace
@@ -1736,7 +1863,7 @@ size_t adatopk_workspace_bytes(int64_t n_total, int32_t num_segments, adatopk_dt
     if (n_total < 0 || num_segments < 1 || !dtype_ok(dt)) return 0;
     int64_t max_chunks, max_lb;
     bounds_for(n_total, num_segments, dt, &max_chunks, &max_lb);
-    return carve(max_chunks, max_lb, n_total, dt).total;
+    return carve(max_chunks, max_lb, n_total, num_segments, dt).total;
 }
 
 adatopk_status adatopk_compress(const void *dense, int64_t n, adatopk_dtype dt, int64_t k, int32_t *idx_out,
@@ -1744,7 +1871,8 @@ adatopk_status adatopk_compress(const void *dense, int64_t n, adatopk_dtype dt, 
                                 void *hip_stream) {
     const void *ptrs[1] = {dense};
     const int64_t off[2] = {0, k};
-    return compress_impl(ptrs, &n, &k, 1, dt, idx_out, 4, val_out, off, err_norm_out, workspace, workspace_bytes,
+    const OutSpec out{idx_out, 4, val_out, off, false};
+    return compress_impl(ptrs, &n, &k, 1, dt, out, err_norm_out, workspace, workspace_bytes,
                          static_cast<hipStream_t>(hip_stream));
 }
 
@@ -1752,7 +1880,8 @@ adatopk_status adatopk_compress_segmented(const void *const *dense, const int64_
                                           adatopk_dtype dt, int32_t *idx_out, void *val_out,
                                           const int64_t *out_offset, float *err_norm_out, void *workspace,
                                           size_t workspace_bytes, void *hip_stream) {
-    return compress_impl(dense, n, k, S, dt, idx_out, 4, val_out, out_offset, err_norm_out, workspace, workspace_bytes,
+    const OutSpec out{idx_out, 4, val_out, out_offset, false};
+    return compress_impl(dense, n, k, S, dt, out, err_norm_out, workspace, workspace_bytes,
                          static_cast<hipStream_t>(hip_stream));
 }
 
@@ -1815,42 +1944,18 @@ adatopk_status adatopk_wire_parse_header(const void *host_bytes, size_t wire_byt
 adatopk_status adatopk_compress_wire(const void *dense, int64_t n, adatopk_dtype dt, int64_t k, int32_t index_bytes,
                                      double ratio, void *wire_out, size_t wire_capacity, void *workspace,
                                      size_t workspace_bytes, void *hip_stream) {
-    if (index_bytes != 4 && index_bytes != 8) return ADATOPK_EINVAL;
-    if (!dtype_ok(dt) || n < 0 || k < 0 || k > n || n >= (static_cast<int64_t>(1) << 31)) return ADATOPK_EINVAL;
-    if (!wire_out || reinterpret_cast<uintptr_t>(wire_out) % 16) return ADATOPK_EINVAL;
-    const size_t bytes = adatopk_wire_bytes(k, dt, index_bytes);
-    if (bytes == 0 || wire_capacity < bytes) return ADATOPK_EINVAL;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    adatopk_wire_header h;
-    memset(&h, 0, sizeof h);
-    h.magic = ADATOPK_WIRE_MAGIC;
-    h.version = ADATOPK_WIRE_VERSION;
-    h.algorithm = ADATOPK_WIRE_TOPK;
-    h.dtype = static_cast<uint8_t>(dt);
-    h.index_bytes = static_cast<uint8_t>(index_bytes);
-    h.n = n;
-    h.k = k;
-    h.ratio = ratio;
-    h.idx_offset = sizeof(adatopk_wire_header);
-    h.val_offset = static_cast<int64_t>(wire_val_offset(k, index_bytes));
-    char *w = static_cast<char *>(wire_out);
     const void *ptrs[1] = {dense};
-    const int64_t off[2] = {0, k};
-    // validate everything (workspace included) before the header kernel is enqueued
-    const adatopk_status pre = compress_impl(ptrs, &n, &k, 1, dt, w + h.idx_offset, index_bytes, w + h.val_offset, off,
-                                             reinterpret_cast<float *>(w + offsetof(adatopk_wire_header, err_norm)),
-                                             workspace, workspace_bytes, st, /*validate_only=*/true);
-    if (pre != ADATOPK_OK) return pre;
-    WireWords words;
-    memcpy(&words, &h, sizeof h);
-    const size_t pad_a = static_cast<size_t>(h.idx_offset + k * index_bytes), pad_b = static_cast<size_t>(h.val_offset);
-    launch(ST_HEADER, k_wire_header, dim3(1), st, reinterpret_cast<uint32_t *>(w), words,
-           static_cast<uint32_t>(offsetof(adatopk_wire_header, err_norm) / 4), reinterpret_cast<unsigned char *>(w),
-           pad_a, pad_b);
-    if (hipGetLastError() != hipSuccess) return ADATOPK_ERUNTIME;
-    return compress_impl(ptrs, &n, &k, 1, dt, w + h.idx_offset, index_bytes, w + h.val_offset, off,
-                         reinterpret_cast<float *>(w + offsetof(adatopk_wire_header, err_norm)), workspace,
-                         workspace_bytes, st, false);
+    const int64_t off[1] = {0};
+    return compress_wire_impl(ptrs, &n, &k, 1, dt, index_bytes, &ratio, wire_out, off, wire_capacity, workspace,
+                              workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+adatopk_status adatopk_compress_wire_segmented(const void *const *dense, const int64_t *n, const int64_t *k, int32_t S,
+                                               adatopk_dtype dt, int32_t index_bytes, const double *ratio,
+                                               void *wire_out, const int64_t *wire_offset, size_t wire_capacity,
+                                               void *workspace, size_t workspace_bytes, void *hip_stream) {
+    return compress_wire_impl(dense, n, k, S, dt, index_bytes, ratio, wire_out, wire_offset, wire_capacity, workspace,
+                              workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
 adatopk_status adatopk_decompress_wire(const void *wire, size_t wire_bytes, adatopk_dtype dt, int32_t index_bytes,

@@ -206,3 +206,34 @@ def test_segmented_decompress_rejects_bad_tables(lib):
     assert f(None, fake, O(0, 10, 20), 2, 0, P(fake, fake), I(100, 100), None) == EINVAL
     assert f(fake, fake, O(0, 10, 20), 2, 7, P(fake, fake), I(100, 100), None) == EINVAL
     assert f(fake, fake, O(0, 0, 0), 0, 0, P(fake, fake), I(100, 100), None) == 0  # S = 0: nothing to do
+
+
+def test_segmented_wire_rejects_bad_message_tables(lib):
+    EINVAL, EWORKSPACE = 1, 2
+    fake, ws = 0x1000, 0x100000
+    P = ctypes.c_void_p * 2
+    I = ctypes.c_int64 * 2
+    f = lib.adatopk_compress_wire_segmented
+    f.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t,
+                  ctypes.c_void_p]
+    need = lib.adatopk_workspace_bytes(300, 2, 0)
+    m = lib.adatopk_wire_bytes(10, 0, 4)  # 64 + 48 + 40 = 152 -> next message at 160
+    ok_args = (P(fake, fake), I(100, 200), I(10, 10), 2, 0, 4, None, fake, I(0, 160), 160 + m, ws, need, None)
+
+    def call(**kw):
+        a = list(ok_args)
+        names = ["dense", "n", "k", "S", "dt", "ib", "ratio", "wire", "off", "cap", "ws", "need", "st"]
+        for key, v in kw.items():
+            a[names.index(key)] = v
+        return f(*a)
+
+    assert call(off=I(0, 144)) == EINVAL        # overlaps the first message
+    assert call(off=I(0, 168)) == EINVAL        # not a multiple of 16
+    assert call(off=I(160, 0)) == EINVAL        # not ascending
+    assert call(cap=160 + m - 1) == EINVAL      # last message does not fit
+    assert call(ib=2) == EINVAL
+    assert call(wire=fake + 8) == EINVAL
+    assert call(k=I(10, 201)) == EINVAL
+    assert call(need=need - 1) == EWORKSPACE
+    assert call(S=0) == 0

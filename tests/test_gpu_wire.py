@@ -92,3 +92,43 @@ def test_wire_round_trip_on_the_device_config1():
         torch.cuda.synchronize()
         ri, rv, _ = orc.compress(x, k)
         assert np.array_equal(H.bits(H.to_host(y)), H.bits(orc.decompress(ri, rv, x.size)))
+
+
+@pytest.mark.parametrize("ib", [4, 8])
+@pytest.mark.parametrize("dtype,small", [("f32", True), ("f32", False), ("bf16", False), ("f16", True)])
+def test_segmented_compress_into_one_message_per_tensor(dtype, ib, small):
+    # all outgoing tensors of a node in one call, one message each; both compress paths (every tensor
+    # within 8192 elements: one launch; otherwise the four-kernel path), more tensors than one header
+    # launch holds, gaps between the messages left untouched
+    import torch
+
+    import gpu_harness as H
+    from paper_2410_12707_amd import binding as B
+
+    rng = np.random.Generator(np.random.PCG64(41))
+    S = 60
+    lens = rng.integers(1, 8193 if small else 60_000, size=S).tolist()
+    lens[3], lens[7] = 0, 1
+    xs = [wl.small_case(["normal", "few_levels", "sparse"][i % 3], n, seed=700 + i, dtype=dtype) for i, n in enumerate(lens)]
+    ks = [int(rng.integers(0, n + 1)) if i % 4 == 0 else n // 50 for i, n in enumerate(lens)]
+    ratios = [float(i + 1) for i in range(S)]
+    offs, pos = [], 0
+    for i, k in enumerate(ks):
+        offs.append(pos)
+        pos += (wf.message_bytes(k, xs[i].dtype, ib) + 15) // 16 * 16 + (32 if i % 5 == 0 else 0)  # some gaps
+    buf = torch.full((pos + GUARD,), 0xAB, dtype=torch.uint8, device="cuda")
+    ds = [H.to_device(x) for x in xs]
+    ws = B.new_workspace(sum(lens), S, ds[0].dtype)
+    B.adatopk_compress_wire_segmented(ds, ks, ib, ratios, buf[:pos], offs, ws)
+    torch.cuda.synchronize()
+    raw = buf.cpu().numpy().tobytes()
+    covered = np.zeros(pos + GUARD, dtype=bool)
+    for i, (x, k) in enumerate(zip(xs, ks)):
+        ri, rv, re = orc.compress(x, k)
+        ref = wf.pack(ri, rv, lens[i], float(re), ratios[i], ib)
+        got = raw[offs[i]:offs[i] + len(ref)]
+        assert got[:12] == ref[:12] and got[16:] == ref[16:], (i, lens[i], k)
+        assert H.same_err(struct.unpack("<f", got[12:16])[0], re, ERR_RTOL), (i, lens[i], k)
+        covered[offs[i]:offs[i] + len(ref)] = True
+    rest = np.frombuffer(raw, dtype=np.uint8)[~covered]
+    assert np.all(rest == 0xAB), "bytes outside the messages were written"
