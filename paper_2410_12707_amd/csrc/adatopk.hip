@@ -1305,39 +1305,48 @@ __global__ __launch_bounds__(BLOCK) void k_merge_lds(const I *idx, const R *val,
 // Decompress of several tensors in one launch: the spans of all tensors form one grid, a table in
 // the kernel arguments says which workgroups belong to which tensor, and every workgroup runs the
 // one-tensor code above on its span (the sparse or the LDS-built variant, per tensor).
-constexpr int MERGE_MAXSEG = 48;
-struct MergeSeg {
+constexpr int MERGE_MAXSEG = 96;
+struct MergeSeg {   // 40 bytes
     unsigned char *y;
-    const int32_t *idx;
-    const void *val;
-    size_t total, head, span;
+    int64_t pair_off;      // first pair of this tensor in idx / val
+    int64_t n;             // elements
     uint32_t k;
-    uint32_t first_block, nblocks;
-    uint32_t dense;
+    uint32_t first_block;  // its spans are workgroups [first_block, first_block of the next tensor)
+    uint32_t dense;        // k > n / MERGE_DENSE_RATIO: build the lines in LDS
+    uint32_t pad;
 };
 struct MergeLaunch {
     MergeSeg seg[MERGE_MAXSEG];
+    const int32_t *idx;
+    const void *val;
+    size_t span;           // bytes of output per workgroup, the same for every tensor of the call
+    uint32_t blocks;       // workgroups of the launch
     int32_t S;
 };
 static_assert(sizeof(MergeLaunch) <= 4096, "kernel arguments stay within 4 KB");
-static_assert(MERGE_MAXSEG <= 64, "one lane per segment");
+static_assert(MERGE_MAXSEG <= 128, "two table entries per lane");
 
 template <typename R> __global__ __launch_bounds__(BLOCK) void k_merge_seg(const MergeLaunch a) {
     __shared__ __attribute__((aligned(16))) unsigned char piece[MERGE_PIECE];
     __shared__ uint32_t s_range[2];
+    // owner of this workgroup: the last tensor whose first workgroup is <= blockIdx.x (first workgroups
+    // never decrease and the first is 0); lane l looks at table entries l and l + 64
     const int lane = threadIdx.x & 63;
-    uint32_t first = 0xFFFFFFFFu;
-    if (lane < a.S) first = a.seg[lane].first_block;
-    const uint64_t owner_or_before = __ballot(blockIdx.x >= first);  // first blocks never decrease, the first is 0
-    const int s = 63 - __builtin_clzll(owner_or_before | 1ull);
+    uint32_t first_lo = 0xFFFFFFFFu, first_hi = 0xFFFFFFFFu;
+    if (lane < a.S) first_lo = a.seg[lane].first_block;
+    if (lane + 64 < a.S) first_hi = a.seg[lane + 64].first_block;
+    const uint64_t lo = __ballot(blockIdx.x >= first_lo), hi = __ballot(blockIdx.x >= first_hi);
+    const int s = hi ? 127 - __builtin_clzll(hi) : 63 - __builtin_clzll(lo | 1ull);
     const MergeSeg &sg = a.seg[s];
-    const uint32_t blk = blockIdx.x - sg.first_block;
-    if (sg.dense)
-        merge_span_lds<R, int32_t>(sg.idx, static_cast<const R *>(sg.val), sg.k, sg.y, sg.total, sg.head, sg.span, blk,
-                                   sg.nblocks, piece, s_range);
-    else
-        merge_span<R, int32_t>(sg.idx, static_cast<const R *>(sg.val), sg.k, sg.y, sg.total, sg.head, sg.span, blk,
-                               sg.nblocks, s_range);
+    const uint32_t next_first = (s + 1 < a.S) ? a.seg[s + 1].first_block : a.blocks;
+    const uint32_t blk = blockIdx.x - sg.first_block, nblk = next_first - sg.first_block;
+    const size_t total = static_cast<size_t>(sg.n) * sizeof(R);
+    size_t head = (16 - reinterpret_cast<uintptr_t>(sg.y) % 16) % 16;
+    if (head > total) head = total;
+    const int32_t *idx = a.idx + sg.pair_off;
+    const R *val = static_cast<const R *>(a.val) + sg.pair_off;
+    if (sg.dense) merge_span_lds<R, int32_t>(idx, val, sg.k, sg.y, total, head, a.span, blk, nblk, piece, s_range);
+    else merge_span<R, int32_t>(idx, val, sg.k, sg.y, total, head, a.span, blk, nblk, s_range);
 }
 
 __global__ __launch_bounds__(BLOCK) void k_copy16(uint4 *dst, const uint4 *src, size_t n16) {
@@ -1731,24 +1740,28 @@ adatopk_status decompress_segmented_impl(const int32_t *idx, const void *val, co
     for (int32_t s0 = 0; s0 < S; s0 += MERGE_MAXSEG) {
         MergeLaunch a{};
         a.S = (S - s0 < MERGE_MAXSEG) ? S - s0 : MERGE_MAXSEG;
+        a.idx = idx;
+        a.val = val;
+        a.span = span;
         uint64_t blocks = 0;
         for (int32_t i = 0; i < a.S; ++i) {
             const int32_t s = s0 + i;
             MergeSeg &g = a.seg[i];
             const int64_t k = out_offset[s + 1] - out_offset[s];
             g.y = static_cast<unsigned char *>(dense_out[s]);
-            g.idx = idx + out_offset[s];
-            g.val = static_cast<const char *>(val) + static_cast<size_t>(out_offset[s]) * es;
-            g.total = static_cast<size_t>(n[s]) * es;
-            g.head = (16 - reinterpret_cast<uintptr_t>(dense_out[s]) % 16) % 16;
-            if (g.head > g.total) g.head = g.total;
-            g.span = span;
+            g.pair_off = out_offset[s];
+            g.n = n[s];
             g.k = static_cast<uint32_t>(k);
             g.first_block = static_cast<uint32_t>(blocks);
-            g.nblocks = n[s] > 0 ? static_cast<uint32_t>((g.total - g.head) / span + 1) : 0u;
             g.dense = k > n[s] / MERGE_DENSE_RATIO ? 1u : 0u;
-            blocks += g.nblocks;
+            if (n[s] > 0) {  // same span count as the kernel derives: (bytes behind the unaligned head) / span + 1
+                const size_t total = static_cast<size_t>(n[s]) * es;
+                size_t head = (16 - reinterpret_cast<uintptr_t>(dense_out[s]) % 16) % 16;
+                if (head > total) head = total;
+                blocks += (total - head) / span + 1;
+            }
         }
+        a.blocks = static_cast<uint32_t>(blocks);
         if (blocks == 0) continue;
         if (blocks > 0x7FFFFFFFull) return ADATOPK_EINVAL;
         const dim3 grid(static_cast<unsigned>(blocks));
