@@ -254,3 +254,17 @@ def test_small_tensor_limit_and_one_past_it():
             x = wl.small_case(kind, n, seed=n)
             for k in (1, n // 7, n - 1, n):
                 check_one(x, k, label="%s n=%d k=%d" % (kind, n, k))
+
+
+def test_randomized_shapes_and_keep_counts():
+    # 160 seeded draws of (dtype, value structure, n, k): n log-uniform from 1 to 400 000, so both compress
+    # paths, one to several chunks and list blocks, k anywhere from 0 to n
+    rng = np.random.Generator(np.random.PCG64(2410_12707))
+    kinds = ["normal", "few_levels", "sparse", "all_equal", "random_bits", "signed_zero_mix", "nonfinite", "ascending"]
+    for case in range(160):
+        dtype = ["f32", "bf16", "f16"][case % 3]
+        kind = kinds[int(rng.integers(0, len(kinds)))]
+        n = int(np.exp(rng.uniform(0.0, np.log(400_000.0))))
+        k = int(rng.integers(0, n + 1)) if case % 2 else int(n * np.exp(rng.uniform(np.log(1e-3), 0.0)))
+        x = wl.small_case(kind, n, seed=5000 + case, dtype=dtype)
+        check_one(x, k, label="case %d: %s %s n=%d k=%d" % (case, kind, dtype, n, k))
