@@ -798,6 +798,16 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
     if (lb >= nactive) return;
     const uint32_t B1 = a.state[s].B1, c_gt1 = a.state[s].c_gt1;
 
+    // The first LU entries of every thread do not depend on the prologue: their loads are in flight
+    // while it runs (a typical list block has no more than these).
+    const R *Lv = static_cast<const R *>(a.L_val) + sg.l_base;
+    uint32_t first[LU];
+#pragma unroll
+    for (int j = 0; j < LU; ++j) {
+        const uint32_t i = beg + j * BLOCK + threadIdx.x;
+        first[j] = (i < end) ? static_cast<uint32_t>(Lv[i]) : 0u;
+    }
+
     // Prologue: bucket of the second digit among the members of bucket B1.
     const ColumnPick p2 = column_pick<NB2, NC2>(a.rows2 + static_cast<size_t>(sg.chunk_begin) * NB2,
                                                 a.coarse2 + static_cast<size_t>(sg.chunk_begin) * NC2, sg.nchunks, 0,
@@ -808,22 +818,24 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
         a.state[s].c_gt2 = c_gt1 + above2;
     }
     const uint32_t P = (B1 << BITS2) | B2;  // 21-bit prefix of the threshold
-    const R *Lv = static_cast<const R *>(a.L_val) + sg.l_base;
 
     uint32_t *h3 = h;
     for (int b = threadIdx.x; b < NB3; b += BLOCK) h3[b] = 0;
     __syncthreads();
     uint32_t def = 0;  // keys above the prefix: kept whatever the last digit is
     double acc = 0.0;  // squares of the keys below the prefix: dropped whatever the last digit is
-    for (uint32_t i = beg + threadIdx.x; i < end; i += BLOCK) {
-        const uint32_t raw = Lv[i];
+    auto count_entry = [&](uint32_t raw) {
         const uint32_t key = key_of<VEC>(raw);
         const uint32_t p = key >> SH2;
         def += (p > P) ? 1u : 0u;
         if (p == P) atomicAdd(&h3[key & (NB3 - 1)], 1u);
         const double xd = (p < P) ? static_cast<double>(value_of<VEC>(raw)) : 0.0;
         acc = fma(xd, xd, acc);
-    }
+    };
+#pragma unroll
+    for (int j = 0; j < LU; ++j)
+        if (beg + j * BLOCK + threadIdx.x < end) count_entry(first[j]);
+    for (uint32_t i = beg + LU * BLOCK + threadIdx.x; i < end; i += BLOCK) count_entry(Lv[i]);
     const double bsum = block_sum_f64(acc, smd);
     if (threadIdx.x == 0) a.lerr[g] = bsum;
     __syncthreads();
@@ -859,10 +871,31 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     uint32_t beg, end;
     int nactive;
     list_range(m, lb, sg.lb_count, beg, end, nactive);
-    if (lb >= nactive) return;
+    // The error norm is summed by a list block that has no list entries of its own when the grid
+    // has one (the first one past the active blocks), so that the sum is off the critical path;
+    // otherwise by the first block.
+    const int err_lb = (a.err_out != nullptr) ? (nactive < sg.lb_count ? nactive : 0) : -1;
+    if (lb >= nactive && lb != err_lb) return;
     const uint32_t P = (a.state[s].B1 << BITS2) | a.state[s].B2;
     const uint32_t c_gt2 = a.state[s].c_gt2;
     const uint32_t kout = static_cast<uint32_t>(sg.k);
+
+    // The block's first tile of list entries does not depend on the prologue: its loads are in
+    // flight while the prologue runs (a typical list block is one tile).
+    const int32_t *Li = a.L_idx + sg.l_base;
+    const R *Lv = static_cast<const R *>(a.L_val) + sg.l_base;
+    uint32_t raw[LU];
+    int32_t id[LU];
+    auto load_tile = [&](uint32_t t0) {
+#pragma unroll
+        for (int j = 0; j < LU; ++j) {
+            const uint32_t i = t0 + j * BLOCK + threadIdx.x;
+            const bool valid = i < end;
+            raw[j] = valid ? static_cast<uint32_t>(Lv[i]) : 0u;
+            id[j] = valid ? Li[i] : 0;
+        }
+    };
+    load_tile(beg);
 
     // Prologue: last digit -> threshold key T and tie quota q.
     uint32_t B3, above3;
@@ -873,12 +906,12 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     const uint32_t T = (B3 < NB3) ? ((P << BITS3) | B3) : 0xFFFFFFFFu;
     const uint32_t q = kout - (c_gt2 + above3);
 
-    // Error norm of the segment, by its first list block only.  Everything it needs was stored by
+    // Error norm of the segment, by one list block only.  Everything it needs was stored by
     // earlier kernels: per-chunk sums of squares below bucket B1 (k_gather), per-list-block sums of
     // squares below the 21-bit prefix (k_hist3), and the counts of the entries that match the
     // prefix: all entries of one third-digit bin share one key, hence one square, so the dropped
     // ones among them add count * value^2.  Fixed summation order.
-    if (lb == 0 && a.err_out != nullptr) {
+    if (lb == err_lb) {
         double part = 0.0;
         for (int cc = threadIdx.x; cc < sg.nchunks; cc += BLOCK) part += a.chunk_err[sg.chunk_begin + cc];
         for (int bb = threadIdx.x; bb < nactive; bb += BLOCK) part += a.lerr[sg.lb_begin + bb];
@@ -896,6 +929,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
         }
         const double tot = block_sum_f64(part, smd);
         if (threadIdx.x == 0) a.err_out[s] = static_cast<float>(sqrt(tot));
+        if (lb >= nactive) return;  // no list entries here (uniform for the workgroup)
     }
 
     // Output offsets of this list block = scan over the earlier list blocks of
@@ -919,8 +953,6 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     }
     uint32_t run_gt = s_off[0], run_eq = s_off[1];
 
-    const int32_t *Li = a.L_idx + sg.l_base;
-    const R *Lv = static_cast<const R *>(a.L_val) + sg.l_base;
     const bool wide = a.idx64 != 0;
     const OutPtrs op = out_ptrs(a.idx_out, a.val_out, sg.out_off, kout, wide, a.wire != 0, sizeof(R));
     int32_t *oi = op.i32;
@@ -929,15 +961,12 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
 
     int buf = 0;
     for (uint32_t t0 = beg; t0 < end; t0 += BLOCK * LU, buf ^= 1) {
-        uint32_t raw[LU];
-        int32_t id[LU];
+        if (t0 != beg) load_tile(t0);
         uint32_t pre_gt[LU], pre_eq[LU], cls[LU];  // cls: 0 not kept for sure, 1 equal to T, 2 above T
 #pragma unroll
         for (int j = 0; j < LU; ++j) {
             const uint32_t i = t0 + j * BLOCK + threadIdx.x;
             const bool valid = i < end;
-            raw[j] = valid ? static_cast<uint32_t>(Lv[i]) : 0u;
-            id[j] = valid ? Li[i] : 0;
             const uint32_t key = key_of<VEC>(raw[j]);
             const bool gt = valid && key > T, eq = valid && key == T;
             cls[j] = gt ? 2u : (eq ? 1u : 0u);
