@@ -345,21 +345,6 @@ __device__ __forceinline__ int find_segment_by(const Launch &a, int g, bool by_c
     return 63 - __builtin_clzll(owner_or_before | 1ull);
 }
 
-// Global histogram G[NB] (complete: written by an earlier kernel) -> bucket B holding the
-// krem-th largest digit and the count `above` it.  h[NB], sm[NW], s_pick[2] are LDS scratch.
-template <int NB>
-__device__ __forceinline__ void pick_from_global(const uint32_t *G, uint32_t krem, uint32_t *h, uint32_t *sm,
-                                                 uint32_t *s_pick, uint32_t &B, uint32_t &above) {
-    for (int b = threadIdx.x; b < NB; b += BLOCK) h[b] = G[b];
-    __syncthreads();
-    block_suffix_inplace<NB>(h, sm);
-    block_pick_bucket<NB>(h, krem, s_pick);
-    __syncthreads();
-    B = s_pick[0];
-    above = s_pick[1];
-    __syncthreads();
-}
-
 // Bucket search on per-block rows of suffix sums.  rows[r][NB] holds, for block r, the number of
 // its keys whose digit is >= d at entry d; coarse[r][NC] repeats every (NB / NC)-th entry
 // contiguously.  The column sums over the nrows rows are the global suffix sums S[d], non-increasing
@@ -373,9 +358,17 @@ struct ColumnPick {
     uint32_t total;  // S[B]
     uint32_t below;  // the part of S[B] that comes from rows < below_rows
 };
-template <int NB, int NC>
+// `after_first_loads` is called once, right after the first batch of step-A loads has been issued and
+// before anything waits for it: loads that the caller issues there (a first input tile) are behind
+// the step-A loads in the wavefront's in-order load counter, so step A does not wait for them, and
+// they have the whole of step A to arrive before step B's loads queue up behind them.
+struct NoPrefetch {
+    __device__ __forceinline__ void operator()() const {}
+};
+template <int NB, int NC, int UA = 8, typename Prefetch = NoPrefetch>
 __device__ __forceinline__ ColumnPick column_pick(const uint32_t *rows, const uint32_t *coarse, int nrows,
-                                                  int below_rows, uint32_t krem, uint32_t *red) {
+                                                  int below_rows, uint32_t krem, uint32_t *red,
+                                                  Prefetch after_first_loads = Prefetch()) {
     constexpr int FINE = NB / NC;
     static_assert(NC <= 64 && FINE <= 64 && NC % 4 == 0 && FINE % 4 == 0 && BLOCK % (NC / 4) == 0 &&
                       BLOCK % (FINE / 4) == 0 && NC + 2 * FINE <= BLOCK,
@@ -391,15 +384,23 @@ __device__ __forceinline__ ColumnPick column_pick(const uint32_t *rows, const ui
         const int q = threadIdx.x % Q;
         const uint4 *co = reinterpret_cast<const uint4 *>(coarse) + q;
         uint4 sum = make_uint4(0, 0, 0, 0);
-        for (int r0 = threadIdx.x / Q; r0 < nrows; r0 += G * 8) {
-            uint4 v[8];
+        // UA rows per thread and batch: the caller picks it so that its usual row count is one batch
+        bool first = true;
+        for (int r0 = threadIdx.x / Q; r0 < nrows || first; r0 += G * UA) {
+            uint4 v[UA];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < UA; ++u) {
                 const int rr = r0 + u * G;
                 v[u] = (rr < nrows) ? co[static_cast<size_t>(rr) * Q] : make_uint4(0, 0, 0, 0);
             }
+            if (first) {
+                __builtin_amdgcn_sched_barrier(0);
+                after_first_loads();
+                __builtin_amdgcn_sched_barrier(0);
+                first = false;
+            }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < UA; ++u) {
                 sum.x += v[u].x; sum.y += v[u].y; sum.z += v[u].z; sum.w += v[u].w;
             }
         }
@@ -686,16 +687,19 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_gather(Launch a) {
     const int64_t beg = static_cast<int64_t>(c) * a.E;
     const int64_t end = (beg + a.E < sg.n) ? beg + a.E : sg.n;
 
-    // The first tile does not depend on the prologue: put its loads in flight now.
+    // The first tile does not depend on the prologue: its loads are put in flight inside it, behind
+    // the prologue's first loads.
     uint32_t cur[St::SLOTS], nxt[St::SLOTS], valid[St::SLOTS];
     const int64_t ntiles = sg.aligned4 ? (end - beg) / TILE : 0;
-    if (ntiles > 0) St::load_fast(sg.x, beg, cur);
+    auto first_tile = [&]() {
+        if (ntiles > 0) St::load_fast(sg.x, beg, cur);
+    };
 
     // Prologue, the same in every block of the segment: bucket B1 of the k-th key from the rows of
     // k_hist1; the part of S[B1] that belongs to the earlier chunks is this chunk's offset in the list.
-    const ColumnPick p1 = column_pick<NB1, NC1>(a.rows1 + static_cast<size_t>(sg.chunk_begin) * NB1,
+    const ColumnPick p1 = column_pick<NB1, NC1, 16>(a.rows1 + static_cast<size_t>(sg.chunk_begin) * NB1,
                                                 a.coarse1 + static_cast<size_t>(sg.chunk_begin) * NC1, sg.nchunks, c,
-                                                static_cast<uint32_t>(sg.k), h);
+                                                static_cast<uint32_t>(sg.k), h, first_tile);
     const uint32_t B1 = p1.B, c_gt1 = p1.above, off = p1.below, m_total = p1.total;
     const uint32_t cnt = (B1 < NB1) ? a.rows1[static_cast<size_t>(g) * NB1 + B1] : 0u;
     if (c == sg.nchunks - 1 && threadIdx.x == 0) {
@@ -799,19 +803,21 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
     const uint32_t B1 = a.state[s].B1, c_gt1 = a.state[s].c_gt1;
 
     // The first LU entries of every thread do not depend on the prologue: their loads are in flight
-    // while it runs (a typical list block has no more than these).
+    // while it runs (a typical list block has no more than these), issued behind its first loads.
     const R *Lv = static_cast<const R *>(a.L_val) + sg.l_base;
     uint32_t first[LU];
+    auto first_entries = [&]() {
 #pragma unroll
-    for (int j = 0; j < LU; ++j) {
-        const uint32_t i = beg + j * BLOCK + threadIdx.x;
-        first[j] = (i < end) ? static_cast<uint32_t>(Lv[i]) : 0u;
-    }
+        for (int j = 0; j < LU; ++j) {
+            const uint32_t i = beg + j * BLOCK + threadIdx.x;
+            first[j] = (i < end) ? static_cast<uint32_t>(Lv[i]) : 0u;
+        }
+    };
 
     // Prologue: bucket of the second digit among the members of bucket B1.
     const ColumnPick p2 = column_pick<NB2, NC2>(a.rows2 + static_cast<size_t>(sg.chunk_begin) * NB2,
                                                 a.coarse2 + static_cast<size_t>(sg.chunk_begin) * NC2, sg.nchunks, 0,
-                                                static_cast<uint32_t>(sg.k) - c_gt1, h);
+                                                static_cast<uint32_t>(sg.k) - c_gt1, h, first_entries);
     const uint32_t B2 = p2.B, above2 = p2.above;
     if (lb == 0 && threadIdx.x == 0) {
         a.state[s].B2 = B2;
@@ -895,14 +901,25 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
             id[j] = valid ? Li[i] : 0;
         }
     };
-    load_tile(beg);
 
-    // Prologue: last digit -> threshold key T and tie quota q.
+    // Prologue: last digit -> threshold key T and tie quota q.  The loads of the third-digit
+    // histogram go first, the list tile behind them (the wavefront's load counter is in order).
     uint32_t B3, above3;
     uint32_t my_bins[NB3 / BLOCK];  // raw counts of the third-digit bins this thread owns
 #pragma unroll
     for (int j = 0; j < NB3 / BLOCK; ++j) my_bins[j] = a.G3[s * NB3 + threadIdx.x * (NB3 / BLOCK) + j];
-    pick_from_global<NB3>(a.G3 + s * NB3, kout - c_gt2, h, sm, s_pick, B3, above3);
+    __builtin_amdgcn_sched_barrier(0);
+    load_tile(beg);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < NB3 / BLOCK; ++j) h[threadIdx.x * (NB3 / BLOCK) + j] = my_bins[j];
+    __syncthreads();
+    block_suffix_inplace<NB3>(h, sm);
+    block_pick_bucket<NB3>(h, kout - c_gt2, s_pick);
+    __syncthreads();
+    B3 = s_pick[0];
+    above3 = s_pick[1];
+    __syncthreads();
     const uint32_t T = (B3 < NB3) ? ((P << BITS3) | B3) : 0xFFFFFFFFu;
     const uint32_t q = kout - (c_gt2 + above3);
 
@@ -1010,7 +1027,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
 // sums the squares of the dropped ones.  Same results as the big path.  One compute unit works
 // through about 3 elements per ns in the ordered round, so tensors beyond one register tile stay
 // with the four-kernel path, which spreads them over many compute units.
-constexpr int SMALL_EPT = 16;                  // elements per thread
+constexpr int SMALL_EPT = 128 / NW;            // elements per thread (16 with 512 threads)
 constexpr int SMALL_N = BLOCK * SMALL_EPT;     // largest tensor this path takes
 constexpr int SMALL_MAXSEG = 128;              // tensors per launch (the table travels as kernel arguments)
 struct SmallDesc {
