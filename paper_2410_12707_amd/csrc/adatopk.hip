@@ -203,11 +203,15 @@ template <int VEC> struct Stream {
         const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
         return t0 + (static_cast<int64_t>(w * SLOTS + slot) * 64 + lane) * EPD;
     }
-    // whole tile in range, base 4-byte aligned: plain dword loads
+    // whole tile in range, base 4-byte aligned: dword loads, nontemporal.  The input is streamed
+    // through twice and is as large as the caches or larger; loaded nontemporally it does not
+    // displace what the call does reuse (the per-chunk rows, the candidate list) nor the output of
+    // the previous call that is still draining to memory (measured: 83.7 -> 76.6 us per step on
+    // the 100 MB tensor, 636 -> 554 us on the 805 MB batch).
     static __device__ __forceinline__ void load_fast(const void *x, int64_t t0, uint32_t (&dw)[SLOTS]) {
         const uint32_t *p = static_cast<const uint32_t *>(x) + first_elem(t0, 0) / EPD;
 #pragma unroll
-        for (int e = 0; e < SLOTS; ++e) dw[e] = p[e * 64];
+        for (int e = 0; e < SLOTS; ++e) dw[e] = __builtin_nontemporal_load(p + e * 64);
     }
     // ragged tile or misaligned bf16 base: element-wise, guarded; valid[e] has bit h set when
     // element h of slot e is below `end`
