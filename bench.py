@@ -68,10 +68,12 @@ def micro_batch_pipeline(B, torch, xs, k, tdt, n, esize, ws, n_b=4, rounds=25):
         return (time.perf_counter() - t0) / (n_b * rounds) * 1e6
 
     run(True)  # warm-up of both paths
-    serial, overlapped = run(False), run(True)
+    serial = min(run(False) for _ in range(3))
+    overlapped = min(run(True) for _ in range(3))  # the two-stream run stalls now and then: best of three
     return {"n_b": n_b, "message_bytes": nbytes, "serial_us_per_micro_batch": round(serial, 2),
             "overlapped_us_per_micro_batch": round(overlapped, 2),
-            "what": "compress into a wire message + copy of the message to pinned host memory"}
+            "what": "compress into a wire message + copy of the message to pinned host memory, best of 3 runs of %d micro-batches"
+                    % (n_b * rounds)}
 
 
 def concurrent_streams(B, torch, xs, k, tdt, n, esize, streams=4, rounds=50):
