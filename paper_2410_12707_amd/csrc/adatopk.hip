@@ -329,6 +329,25 @@ template <int NB> __device__ __forceinline__ void block_pick_bucket(const uint32
     }
 }
 
+// One count per active lane into h[bin].  Lanes of a wavefront that hit the same LDS word are
+// served one after the other; with most of the 64 lanes on one word (a constant or mostly-zero
+// tensor, sorted data) a histogram pass gets several times slower.  So when at least half of the
+// wavefront is active and at least a quarter of it shares the bin of the first active lane, those
+// lanes are counted with a single add.  Only the lanes that execute the call take part in it.
+__device__ __forceinline__ void hist_add(uint32_t *h, uint32_t bin, bool active) {
+    const uint64_t act = __ballot(active);
+    if (__popcll(act) >= 32) {  // wave-uniform
+        const int leader = __ffsll(static_cast<unsigned long long>(act)) - 1;
+        const uint32_t lbin = __builtin_amdgcn_readlane(bin, leader);
+        const uint64_t same = __ballot(active && bin == lbin);
+        if (__popcll(same) >= 16) {
+            if (static_cast<int>(threadIdx.x & 63) == leader) atomicAdd(&h[lbin], static_cast<uint32_t>(__popcll(same)));
+            active = active && bin != lbin;
+        }
+    }
+    if (active) atomicAdd(&h[bin], 1u);
+}
+
 // Adds the non-zero bins of an LDS histogram into a global one.
 template <int NB> __device__ __forceinline__ void flush_bins(const uint32_t *h, uint32_t *G) {
     for (int b = threadIdx.x; b < NB; b += BLOCK) {
@@ -468,6 +487,25 @@ __device__ __forceinline__ void hist1_tile(const uint32_t (&dw)[Stream<VEC>::SLO
                                            const uint32_t (&valid)[Stream<VEC>::SLOTS], uint32_t *h) {
     constexpr int EPD = Stream<VEC>::EPD;
     const uint32_t copy = threadIdx.x & (HREP - 1);
+    // Probe: does half of the wavefront share the top digit of lane 0's first element?  Then the tile
+    // is counted with that digit's lanes taken together, slot by slot (one add per slot for them);
+    // otherwise every lane adds for itself, which is the faster way when digits are spread.
+    const uint32_t d0 = key_of<VEC>(elem_of<VEC>(dw[0], 0)) >> SH1;
+    const uint32_t hot = __builtin_amdgcn_readfirstlane(d0);
+    const bool skewed = FAST && __popcll(__ballot(d0 == hot)) >= 32;  // wave-uniform
+    if (skewed) {
+        uint32_t hot_count = 0;
+#pragma unroll
+        for (int e = 0; e < Stream<VEC>::SLOTS; ++e)
+#pragma unroll
+            for (int hh = 0; hh < EPD; ++hh) {
+                const uint32_t d = key_of<VEC>(elem_of<VEC>(dw[e], hh)) >> SH1;
+                hot_count += static_cast<uint32_t>(__popcll(__ballot(d == hot)));
+                if (d != hot) atomicAdd(&h[d * HREP + copy], 1u);
+            }
+        if ((threadIdx.x & 63) == 0) atomicAdd(&h[hot * HREP], hot_count);
+        return;
+    }
 #pragma unroll
     for (int e = 0; e < Stream<VEC>::SLOTS; ++e)
 #pragma unroll
@@ -580,7 +618,7 @@ __device__ __forceinline__ void flush_stage(const uint2 *stage, uint32_t from, u
             Lv[i] = static_cast<typename Raw<VEC>::type>(pr.y);
         }
         const uint32_t key = key_of<VEC>(pr.y);
-        if (key < thr_hi) atomicAdd(&h2[(key >> SH2) & (NB2 - 1)], 1u);
+        hist_add(h2, (key >> SH2) & (NB2 - 1), key < thr_hi);
     }
 }
 
@@ -664,7 +702,7 @@ __device__ __forceinline__ void gather_tile(const uint32_t (&dw)[Stream<VEC>::SL
                         Lv[pos] = static_cast<R>(raw);
                     }
                     const uint32_t key = key_of<VEC>(raw);
-                    if (key < thr_hi) atomicAdd(&h2[(key >> SH2) & (NB2 - 1)], 1u);
+                    hist_add(h2, (key >> SH2) & (NB2 - 1), key < thr_hi);
                     ++pos;
                 }
                 slot_base += __popcll(m[e][hh]);
@@ -838,7 +876,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
         const uint32_t key = key_of<VEC>(raw);
         const uint32_t p = key >> SH2;
         def += (p > P) ? 1u : 0u;
-        if (p == P) atomicAdd(&h3[key & (NB3 - 1)], 1u);
+        hist_add(h3, key & (NB3 - 1), p == P);
         const double xd = (p < P) ? static_cast<double>(value_of<VEC>(raw)) : 0.0;
         acc = fma(xd, xd, acc);
     };
@@ -1068,7 +1106,7 @@ __device__ __forceinline__ void small_round(const uint32_t (&raw)[SMALL_EPT], in
             const int i = e * BLOCK + static_cast<int>(threadIdx.x);
             const uint32_t key = key_of<VEC>(raw[e]);
             const bool in = i < n && (!use_prefix || (key >> prefix_shift) == prefix);
-            if (in) atomicAdd(&h[(key >> shift) & (NB - 1)], 1u);
+            hist_add(h, (key >> shift) & (NB - 1), in);
         }
     }
     __syncthreads();
