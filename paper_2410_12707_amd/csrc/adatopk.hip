@@ -1100,13 +1100,26 @@ __device__ __forceinline__ void small_round(const uint32_t (&raw)[SMALL_EPT], in
                                             uint32_t *s_pick, uint32_t &B, uint32_t &above) {
     for (int b = threadIdx.x; b < NB; b += BLOCK) h[b] = 0;
     __syncthreads();
+    // probe on the first slot: do half of the wavefront's lanes count, and into one bin?  Then the
+    // round adds through hist_add (equal keys would serialise on one LDS word), else every lane for itself
+    bool skewed;
+    {
+        const uint32_t key = key_of<VEC>(raw[0]);
+        const bool in = static_cast<int>(threadIdx.x) < n && (!use_prefix || (key >> prefix_shift) == prefix);
+        const uint32_t bin = (key >> shift) & (NB - 1);
+        const uint64_t act = __ballot(in);
+        const uint32_t lbin = __builtin_amdgcn_readlane(bin, act ? __ffsll(static_cast<unsigned long long>(act)) - 1 : 0);
+        skewed = __popcll(__ballot(in && bin == lbin)) >= 32;  // wave-uniform
+    }
 #pragma unroll
     for (int e = 0; e < SMALL_EPT; ++e) {
         if (e * BLOCK < n) {  // uniform
             const int i = e * BLOCK + static_cast<int>(threadIdx.x);
             const uint32_t key = key_of<VEC>(raw[e]);
             const bool in = i < n && (!use_prefix || (key >> prefix_shift) == prefix);
-            hist_add(h, (key >> shift) & (NB - 1), in);
+            const uint32_t bin = (key >> shift) & (NB - 1);
+            if (skewed) hist_add(h, bin, in);
+            else if (in) atomicAdd(&h[bin], 1u);
         }
     }
     __syncthreads();
