@@ -28,9 +28,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 # From profiles/hbm_traffic_cfg2_k1pct.md (fetched + written bytes per launch); None where no
 # counter run has been made for that kernel.
 TRAFFIC_BYTES = {
-    "k_hist1": 100743893 + 4329536,
-    "k_gather": 102641410 + 4512032,
-    "k_merge": 6482811 + 112930390,
+    "k_hist1": 100809436 + 4329536,
+    "k_gather": 102651614 + 4512032,
+    "k_merge": 6485916 + 112960884,
 }
 
 
