@@ -80,7 +80,14 @@ constexpr int NC1 = 64;             // coarse boundaries of the top digit: every
 constexpr int FINE1 = NB1 / NC1;    // fine bins per coarse interval
 constexpr int NC2 = 32;             // the same for the second digit
 constexpr int MAXSEG = 64;          // segments per launch (the table travels as kernel arguments)
-constexpr int CTARGET = ADATOPK_CTARGET;  // chunks aimed at per launch
+constexpr int CTARGET = ADATOPK_CTARGET;  // chunks aimed at per launch of several tensors (and the most any launch has)
+#ifndef ADATOPK_CTARGET_ONE
+#define ADATOPK_CTARGET_ONE 256
+#endif
+// chunks aimed at for a single tensor: one workgroup per compute unit.  Half the rows for every
+// prologue to sum (76 instead of 77.5 us per step on the 100 MB tensor); a batch of tensors with
+// unequal keep counts wants the finer split, whose workgroups even out (24 tensors: 560 vs 600 us).
+constexpr int CTARGET_ONE = ADATOPK_CTARGET_ONE < ADATOPK_CTARGET ? ADATOPK_CTARGET_ONE : ADATOPK_CTARGET;
 constexpr int LB_ELEMS = 8192;      // input elements per list block when sizing the list grid
 constexpr int LB_TOTAL = 4096;      // list blocks aimed at per launch, all segments together
 #ifndef ADATOPK_MERGE_SPANS
@@ -1490,10 +1497,9 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int elem_size(adatopk_dtype dt) { return dt == ADATOPK_F32 ? 4 : 2; }
 inline bool dtype_ok(adatopk_dtype dt) { return dt == ADATOPK_F32 || dt == ADATOPK_BF16 || dt == ADATOPK_F16; }
 
-int64_t chunk_elems(int64_t n_total, adatopk_dtype dt) {
-    (void)dt;
+int64_t chunk_elems(int64_t n_total, int64_t target) {
     const int64_t tile = TILE;
-    int64_t e = (n_total + CTARGET - 1) / CTARGET;
+    int64_t e = (n_total + target - 1) / target;
     if (e < tile) e = tile;
     e = (e + tile - 1) / tile * tile;
     const int64_t cap = (static_cast<int64_t>(1) << 30) / tile * tile;
@@ -1664,12 +1670,13 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
         // are resident at once (a few chunks beyond that would run as a second, nearly empty round).
         int64_t n_batch = 0;
         for (int32_t i = 0; i < a.S; ++i) n_batch += n[s0 + i];
-        int64_t E = chunk_elems(n_batch, dt);
+        const int64_t target = a.S == 1 ? CTARGET_ONE : CTARGET;
+        int64_t E = chunk_elems(n_batch, target);
         for (int iter = 0; iter < 32; ++iter) {
             int64_t count = 0;
             for (int32_t i = 0; i < a.S; ++i) count += (n[s0 + i] + E - 1) / E;
-            if (count <= CTARGET) break;
-            const int64_t grown = ((E * count + CTARGET - 1) / CTARGET + TILE - 1) / TILE * TILE;
+            if (count <= target) break;
+            const int64_t grown = ((E * count + target - 1) / target + TILE - 1) / TILE * TILE;
             E = grown > E ? grown : E + TILE;
             if (E > (static_cast<int64_t>(1) << 30)) break;
         }
