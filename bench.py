@@ -28,9 +28,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 # From profiles/hbm_traffic_cfg2_k1pct.md (fetched + written bytes per launch); None where no
 # counter run has been made for that kernel.
 TRAFFIC_BYTES = {
-    "k_hist1": 100809436 + 4329536,
-    "k_gather": 102651614 + 4512032,
-    "k_merge": 6485916 + 112960884,
+    "k_hist1": 100809361 + 2166848,
+    "k_gather": 101865281 + 3407968,
+    "k_merge": 6486697 + 112961915,
 }
 
 
