@@ -24,8 +24,9 @@
 //             suffix sums per list block
 //   k_emit    over L.  Prologue: G3 -> threshold key T and tie quota q; output offsets of the
 //             list block from the rows of the earlier blocks.  Stable compaction into idx_out /
-//             val_out (key > T, plus the first q keys equal to T).  The first list block adds up
-//             the error norm from partials stored by the earlier kernels, in a fixed order
+//             val_out (key > T, plus the first q keys equal to T).  One list block (an otherwise
+//             idle one when there is one) adds up the error norm from partials stored by the
+//             earlier kernels, in a fixed order
 // Cross-block order comes only from counts that an EARLIER kernel stored and that every block
 // of the next kernel scans for itself: no block waits for another block (no launch can hang),
 // no block needs a release fence (on this chip an agent-scope fence writes back the L2 of its
