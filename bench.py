@@ -40,15 +40,16 @@ def micro_batch_pipeline(B, torch, xs, k, tdt, n, esize, ws, n_b=4, rounds=25):
     """Sender side of pipeline parallelism with n_b micro-batches (paper Sec. 3.6): every micro-batch's
     activation is compressed straight into a wire message, and the message is copied to pinned host
     memory, where a network stack would pick it up.  Serial: both on one stream.  Overlapped: the copy
-    of micro-batch j runs on a second stream while micro-batch j + 1 is compressed (two message buffers).
+    of micro-batch j runs on a second stream while the next micro-batches are compressed (n_b message buffers).
     Returns microseconds per micro-batch for both."""
     dt_code = B._dtype_code(tdt)
     nbytes = B.adatopk_wire_bytes(k, dt_code, 4)
-    wire = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(2)]
-    host = [torch.empty(nbytes, dtype=torch.uint8, pin_memory=True) for _ in range(2)]
+    nbuf = n_b  # one message buffer per micro-batch in flight: a buffer is waited for only every n_b-th time
+    wire = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(nbuf)]
+    host = [torch.empty(nbytes, dtype=torch.uint8, pin_memory=True) for _ in range(nbuf)]
     comp, copy = torch.cuda.Stream(), torch.cuda.Stream()
-    done = [torch.cuda.Event() for _ in range(2)]
-    freed = [torch.cuda.Event() for _ in range(2)]
+    done = [torch.cuda.Event() for _ in range(nbuf)]
+    freed = [torch.cuda.Event() for _ in range(nbuf)]
 
     def run(overlap: bool) -> float:
         torch.cuda.synchronize()
@@ -56,7 +57,7 @@ def micro_batch_pipeline(B, torch, xs, k, tdt, n, esize, ws, n_b=4, rounds=25):
             e.record(comp)
         t0 = time.perf_counter()
         for j in range(n_b * rounds):
-            b = j % 2
+            b = j % nbuf
             with torch.cuda.stream(comp):
                 comp.wait_event(freed[b])
                 B.adatopk_compress_wire(xs[j % len(xs)][0], k, 4, float(n) / max(k, 1), wire[b], ws)
@@ -70,12 +71,13 @@ def micro_batch_pipeline(B, torch, xs, k, tdt, n, esize, ws, n_b=4, rounds=25):
         return (time.perf_counter() - t0) / (n_b * rounds) * 1e6
 
     run(True)  # warm-up of both paths
-    serial = min(run(False) for _ in range(3))
-    overlapped = min(run(True) for _ in range(3))  # the two-stream run stalls now and then: best of three
-    return {"n_b": n_b, "message_bytes": nbytes, "serial_us_per_micro_batch": round(serial, 2),
-            "overlapped_us_per_micro_batch": round(overlapped, 2),
-            "what": "compress into a wire message + copy of the message to pinned host memory, best of 3 runs of %d micro-batches"
-                    % (n_b * rounds)}
+    serial = sorted(run(False) for _ in range(5))
+    overlapped = sorted(run(True) for _ in range(5))  # cross-stream event waits make this one vary from run to run
+    return {"n_b": n_b, "message_bytes": nbytes, "serial_us_per_micro_batch": round(serial[2], 2),
+            "overlapped_us_per_micro_batch": round(overlapped[2], 2),
+            "overlapped_us_best_and_worst": [round(overlapped[0], 2), round(overlapped[-1], 2)],
+            "what": "compress into a wire message + copy of the message to pinned host memory; median of 5 runs of %d "
+                    "micro-batches" % (n_b * rounds)}
 
 
 def concurrent_streams(B, torch, xs, k, tdt, n, esize, streams=4, rounds=50):
