@@ -70,14 +70,27 @@ def micro_batch_pipeline(B, torch, xs, k, tdt, n, esize, ws, n_b=4, rounds=25):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / (n_b * rounds) * 1e6
 
-    run(True)  # warm-up of both paths
+    def run_zero_copy() -> float:  # the kernels write the message straight into pinned host memory
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        with torch.cuda.stream(comp):
+            for j in range(n_b * rounds):
+                B.adatopk_compress_wire(xs[j % len(xs)][0], k, 4, float(n) / max(k, 1), host[j % nbuf], ws)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / (n_b * rounds) * 1e6
+
+    run(True)  # warm-up of all paths
+    run_zero_copy()
+    zero_copy = sorted(run_zero_copy() for _ in range(5))
     serial = sorted(run(False) for _ in range(5))
     overlapped = sorted(run(True) for _ in range(5))  # cross-stream event waits make this one vary from run to run
     return {"n_b": n_b, "message_bytes": nbytes, "serial_us_per_micro_batch": round(serial[2], 2),
             "overlapped_us_per_micro_batch": round(overlapped[2], 2),
             "overlapped_us_best_and_worst": [round(overlapped[0], 2), round(overlapped[-1], 2)],
-            "what": "compress into a wire message + copy of the message to pinned host memory; median of 5 runs of %d "
-                    "micro-batches" % (n_b * rounds)}
+            "into_pinned_host_us_per_micro_batch": round(zero_copy[2], 2),
+            "what": "compress into a wire message + copy of the message to pinned host memory (serial: one stream; "
+                    "overlapped: copies on a second stream), or the message written by the kernels straight into pinned "
+                    "host memory; median of 5 runs of %d micro-batches" % (n_b * rounds)}
 
 
 def concurrent_streams(B, torch, xs, k, tdt, n, esize, streams=4, rounds=50):

@@ -172,7 +172,11 @@ int64_t adatopk_wire_keep_count(size_t wire_bytes, adatopk_dtype dt, int32_t ind
 adatopk_status adatopk_wire_parse_header(const void *host_bytes, size_t wire_bytes, adatopk_wire_header *out);
 
 /* adatopk_compress with the outputs laid out as one wire message.
- *   wire_out       device, 16-byte aligned, wire_capacity >= adatopk_wire_bytes(k, dt, index_bytes) bytes
+ *   wire_out       device, 16-byte aligned, wire_capacity >= adatopk_wire_bytes(k, dt, index_bytes) bytes.
+ *                  May also be pinned host memory that the device addresses (hipHostMalloc): the kernels
+ *                  then write the message over the bus and no device-to-host copy is needed before the
+ *                  host sends it (measured: 95 us per call on the 25 M element tensor at k = 1 %,
+ *                  against 60 us into device memory and 141 us with a copy behind it on the same stream).
  *   index_bytes    4, or 8 for int64 indices
  *   ratio          stored in the header as given
  * Everything else as adatopk_compress; EINVAL also for a buffer that is too small or misaligned. */

@@ -121,6 +121,13 @@ def _dev(t: torch.Tensor) -> int:
     return t.data_ptr()
 
 
+def _dev_or_pinned(t: torch.Tensor) -> int:
+    """Device tensor, or pinned host memory (which the device addresses directly: the kernels then write over the bus)."""
+    if t.is_contiguous() and (t.is_cuda or t.is_pinned()):
+        return t.data_ptr()
+    raise ValueError("adatopk needs a contiguous device tensor or pinned host tensor here")
+
+
 def adatopk_workspace_bytes(n_total: int, num_segments: int, dtype: torch.dtype) -> int:
     return int(load_library().adatopk_workspace_bytes(int(n_total), int(num_segments), _dtype_code(dtype)))
 
@@ -201,10 +208,11 @@ def adatopk_wire_parse_header(host_bytes: bytes, wire_bytes: int) -> WireHeader:
 
 def adatopk_compress_wire(dense: torch.Tensor, k: int, index_bytes: int, ratio: float, wire_out: torch.Tensor,
                           workspace: torch.Tensor) -> None:
-    """adatopk_compress writing one wire message into the uint8 tensor wire_out."""
+    """adatopk_compress writing one wire message into the uint8 tensor wire_out (device memory, or pinned
+    host memory: the message then needs no copy before the host can send it)."""
     lib = load_library()
     _check(lib.adatopk_compress_wire(_dev(dense), dense.numel(), _dtype_code(dense.dtype), int(k), int(index_bytes),
-                                     float(ratio), _dev(wire_out), wire_out.numel() * wire_out.element_size(),
+                                     float(ratio), _dev_or_pinned(wire_out), wire_out.numel() * wire_out.element_size(),
                                      _dev(workspace), workspace.numel(), _stream()), "adatopk_compress_wire")
 
 
@@ -220,7 +228,7 @@ def adatopk_compress_wire_segmented(dense: Sequence[torch.Tensor], ks: Sequence[
     kk = (ctypes.c_int64 * max(S, 1))(*[int(v) for v in ks])
     off = (ctypes.c_int64 * max(S, 1))(*[int(v) for v in wire_offset])
     rr = _dbl_array(ratios) if ratios is not None else None
-    _check(lib.adatopk_compress_wire_segmented(ptrs, ns, kk, S, dt, int(index_bytes), rr, _dev(wire_out), off,
+    _check(lib.adatopk_compress_wire_segmented(ptrs, ns, kk, S, dt, int(index_bytes), rr, _dev_or_pinned(wire_out), off,
                                                wire_out.numel() * wire_out.element_size(), _dev(workspace),
                                                workspace.numel(), _stream()), "adatopk_compress_wire_segmented")
 

@@ -132,3 +132,27 @@ def test_segmented_compress_into_one_message_per_tensor(dtype, ib, small):
         covered[offs[i]:offs[i] + len(ref)] = True
     rest = np.frombuffer(raw, dtype=np.uint8)[~covered]
     assert np.all(rest == 0xAB), "bytes outside the messages were written"
+
+
+def test_message_written_straight_into_pinned_host_memory():
+    # wire_out may be pinned host memory: the kernels write the message over the bus, byte for byte
+    # what they write into device memory
+    import torch
+
+    import gpu_harness as H
+    from paper_2410_12707_amd import binding as B
+
+    for dtype, ib in (("f32", 4), ("bf16", 8)):
+        n, k = 1_000_003, 20_000
+        x = wl.small_case("normal", n, seed=77, dtype=dtype)
+        ri, rv, re = orc.compress(x, k)
+        ref = wf.pack(ri, rv, n, float(re), 50.0, ib)
+        d = H.to_device(x)
+        host = torch.full((len(ref) + GUARD,), 0xAB, dtype=torch.uint8).pin_memory()
+        ws = B.new_workspace(n, 1, d.dtype)
+        B.adatopk_compress_wire(d, k, ib, 50.0, host[: len(ref)], ws)
+        torch.cuda.synchronize()
+        got = host.numpy().tobytes()
+        assert got[len(ref):] == b"\xAB" * GUARD
+        assert got[:12] == ref[:12] and got[16:len(ref)] == ref[16:]
+        assert H.same_err(struct.unpack("<f", got[12:16])[0], re, ERR_RTOL)
