@@ -268,3 +268,21 @@ def test_randomized_shapes_and_keep_counts():
         k = int(rng.integers(0, n + 1)) if case % 2 else int(n * np.exp(rng.uniform(np.log(1e-3), 0.0)))
         x = wl.small_case(kind, n, seed=5000 + case, dtype=dtype)
         check_one(x, k, label="case %d: %s %s n=%d k=%d" % (case, kind, dtype, n, k))
+
+
+@pytest.mark.parametrize("n", [5000, 300_000])
+def test_error_norm_is_optional(n):
+    # err_norm_out = NULL: same indices and values, on the one-launch path (n <= 8192) and the four-kernel path,
+    # single and segmented
+    import gpu_harness as H
+
+    x = wl.small_case("normal", n, seed=n)
+    k = n // 20
+    ri, rv, _ = orc.compress(x, k)
+    gi, gv, ge = H.gpu_compress(x, k, want_err=False)
+    assert ge is None and np.array_equal(gi, ri) and np.array_equal(H.bits(gv), H.bits(rv))
+    xs = [x, wl.small_case("few_levels", n // 2, seed=n + 1)]
+    ks = [k, n // 8]
+    si, sv, off, se = H.gpu_compress_segmented(xs, ks, want_err=False)
+    qi, qv, qoff, _ = orc.compress_segmented(xs, ks)
+    assert se is None and np.array_equal(si, qi) and np.array_equal(H.bits(sv), H.bits(qv))
