@@ -891,7 +891,18 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
 #pragma unroll
     for (int j = 0; j < LU; ++j)
         if (beg + j * BLOCK + threadIdx.x < end) count_entry(first[j]);
-    for (uint32_t i = beg + LU * BLOCK + threadIdx.x; i < end; i += BLOCK) count_entry(Lv[i]);
+    // longer list blocks (large k, many ties): LU entries per thread at a time, their loads in flight together
+    for (uint32_t i0 = beg + LU * BLOCK; i0 < end; i0 += LU * BLOCK) {
+        uint32_t more[LU];
+#pragma unroll
+        for (int j = 0; j < LU; ++j) {
+            const uint32_t i = i0 + j * BLOCK + threadIdx.x;
+            more[j] = (i < end) ? static_cast<uint32_t>(Lv[i]) : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < LU; ++j)
+            if (i0 + j * BLOCK + threadIdx.x < end) count_entry(more[j]);
+    }
     const double bsum = block_sum_f64(acc, smd);
     if (threadIdx.x == 0) a.lerr[g] = bsum;
     __syncthreads();
