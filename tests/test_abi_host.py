@@ -237,3 +237,19 @@ def test_segmented_wire_rejects_bad_message_tables(lib):
     assert call(k=I(10, 201)) == EINVAL
     assert call(need=need - 1) == EWORKSPACE
     assert call(S=0) == 0
+
+
+def test_headers_compile_as_c_and_host_entry_points_answer_from_a_c_program(tmp_path):
+    import subprocess
+
+    from paper_2410_12707_amd import binding as B
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "abi_host_check")
+    libdir = os.path.dirname(B.LIB_PATH)
+    cmd = ["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(root, "include"),
+           os.path.join(root, "tests", "c", "abi_host_check.c"), "-o", exe, "-L", libdir, "-ladatopk", "-lm",
+           "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"]
+    subprocess.run(cmd, check=True)
+    r = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=120)
+    assert r.returncode == 0 and "ok" in r.stdout, (r.returncode, r.stdout, r.stderr)
