@@ -31,6 +31,9 @@
  *     must be ordered by the stream.
  *   - errors are returned as adatopk_status; nothing is enqueued when the status is
  *     ADATOPK_EINVAL or ADATOPK_EWORKSPACE.
+ *   - the library keeps no state between calls: calls from several host threads are fine as long
+ *     as calls that share a workspace or an output are ordered by their stream.  Every call can be
+ *     captured into a HIP graph (kernel launches only; no memset or copy nodes).
  */
 #ifndef ADATOPK_H
 #define ADATOPK_H
