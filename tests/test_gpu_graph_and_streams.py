@@ -166,3 +166,56 @@ def test_measurement_hooks_do_what_the_benchmark_assumes():
     for name in ("k_hist1", "k_gather", "k_hist3", "k_emit"):
         assert 0.0 < ms[name] < 5.0, (name, ms[name])  # milliseconds; each of these kernels takes microseconds here
     assert ms["k_merge"] < 0 and ms["k_small"] < 0  # not launched by this call
+
+
+def test_graph_capture_of_wire_and_segmented_calls():
+    # the wire and the segmented entry points enqueue kernels only as well: captured once, replayed on new data
+    import struct
+
+    import torch
+
+    import gpu_harness as H
+    from oracle import wire_format as wf
+    from paper_2410_12707_amd import binding as B
+
+    lens = [40_000, 3_000, 150_000]
+    ks = [400, 300, 15_000]
+    cases = [[wl.small_case(kind, n, seed=s * 10 + i) for i, n in enumerate(lens)]
+             for s, kind in enumerate(["normal", "few_levels", "sparse"])]
+    ds = [torch.empty(n, dtype=torch.float32, device="cuda") for n in lens]
+    offs, pos = [], 0
+    for k in ks:
+        offs.append(pos)
+        pos += (wf.message_bytes(k, np.float32, 8) + 15) // 16 * 16
+    wire = torch.zeros(pos, dtype=torch.uint8, device="cuda")
+    ys = [torch.empty(n, dtype=torch.float32, device="cuda") for n in lens]
+    ws = B.new_workspace(sum(lens), len(lens), torch.float32)
+
+    def enqueue():
+        B.adatopk_compress_wire_segmented(ds, ks, 8, None, wire, offs, ws)
+        for s, (n, k) in enumerate(zip(lens, ks)):
+            nb = wf.message_bytes(k, np.float32, 8)
+            B.adatopk_decompress_wire(wire[offs[s]:offs[s] + nb], nb, 8, ys[s])
+
+    for d, x in zip(ds, cases[0]):
+        d.copy_(torch.from_numpy(x))
+    enqueue()  # eager warm-up
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        enqueue()
+    for rep in range(5):
+        xs = cases[rep % 3]
+        for d, x in zip(ds, xs):
+            d.copy_(torch.from_numpy(x))
+        wire.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        raw = wire.cpu().numpy().tobytes()
+        for s, (x, k) in enumerate(zip(xs, ks)):
+            ri, rv, re = orc.compress(x, k)
+            ref = wf.pack(ri, rv, lens[s], float(re), lens[s] / k, 8)
+            got = raw[offs[s]:offs[s] + len(ref)]
+            assert got[:12] == ref[:12] and got[16:] == ref[16:], (rep, s)
+            assert H.same_err(struct.unpack("<f", got[12:16])[0], re, 1e-5)
+            assert np.array_equal(H.bits(H.to_host(ys[s])), H.bits(orc.decompress(ri, rv, lens[s]))), (rep, s)
