@@ -77,6 +77,55 @@ def test_two_streams_with_their_own_workspaces():
         assert np.array_equal(y.cpu().numpy().view(np.uint32), orc.decompress(ri, rv, n).view(np.uint32))
 
 
+def test_host_threads_each_with_a_stream_and_a_workspace():
+    # The library keeps no state between calls, so host threads may call it at the same time as long
+    # as each brings its own workspace and outputs (ctypes drops the interpreter lock during a call,
+    # so the calls really do overlap in the library's host code).
+    import threading
+
+    import torch
+
+    from paper_2410_12707_amd import binding as B
+
+    kinds = ["normal", "few_levels", "all_equal", "sparse"]
+    sizes = [300_001, 70_000, 8_192, 1_234_567]
+    jobs = [(wl.small_case(kind, n, seed=40 + t), max(1, n // (50 * (t + 1)))) for t, (kind, n) in enumerate(zip(kinds, sizes))]
+    results, failures = [None] * len(jobs), []
+
+    def worker(t):
+        try:
+            x, k = jobs[t]
+            n = x.size
+            st = torch.cuda.Stream()
+            with torch.cuda.stream(st):
+                d = torch.from_numpy(x).cuda()
+                idx = torch.empty(k, dtype=torch.int32, device="cuda")
+                val = torch.empty(k, dtype=torch.float32, device="cuda")
+                err = torch.empty(1, dtype=torch.float32, device="cuda")
+                y = torch.empty(n, dtype=torch.float32, device="cuda")
+                ws = B.new_workspace(n, 1, torch.float32)
+                for _ in range(25):
+                    B.adatopk_compress(d, k, idx, val, err, ws)
+                    B.adatopk_decompress_sorted(idx, val, k, y)
+                st.synchronize()
+                results[t] = (idx.cpu().numpy(), val.cpu().numpy(), float(err.cpu()[0]), y.cpu().numpy())
+        except Exception as e:  # reported by the main thread
+            failures.append((t, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(len(jobs))]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not failures, failures
+    for (x, k), (gi, gv, ge, gy) in zip(jobs, results):
+        ri, rv, re = orc.compress(x, k)
+        assert np.array_equal(gi, ri)
+        assert np.array_equal(gv.view(np.uint32), rv.view(np.uint32))
+        assert abs(ge - float(re)) <= 1e-5 * max(float(re), 1e-30)
+        assert np.array_equal(gy.view(np.uint32), orc.decompress(ri, rv, x.size).view(np.uint32))
+
+
 def test_micro_batch_pipeline_overlapping_compress_and_message_copy():
     # Sender side of pipeline parallelism with several micro-batches (paper Sec. 3.6): micro-batch j + 1
     # is compressed into a wire message while the message of micro-batch j is copied to pinned host
