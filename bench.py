@@ -118,6 +118,47 @@ def concurrent_streams(B, torch, xs, k, tdt, n, esize, streams=4, rounds=50):
     return {"streams": streams, "us_per_step": round(sec * 1e6, 2), "value": round(n * esize / sec / 1e9, 1), "unit": "GB/s"}
 
 
+def call_times(B, torch, compress, decompress, reps):
+    """Median GPU time of the compress call and of the decompress call on their own: one pair of
+    events on the launch stream around each call, `reps` calls each, inputs rotating as in the step."""
+    out = {}
+    for name, fn in (("t_compress_us", compress), ("t_decompress_us", decompress)):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        torch.cuda.synchronize()
+        for i, (e0, e1) in enumerate(evs):
+            e0.record()
+            fn(i)
+            e1.record()
+        torch.cuda.synchronize()
+        ms = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+        out[name] = round(ms[len(ms) // 2] * 1e3, 2)
+    return out
+
+
+def streaming_ceilings(B, torch, src, dst, reps=20):
+    """What the memory system gives the library's plain kernels on a buffer of the tensor's size:
+    read only, fill only, copy (GB/s of bytes moved; the copy moves twice the buffer)."""
+    nbytes = src.numel() * src.element_size()
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = {}
+    for name, fn, moved in (("read", lambda: B.measure_read_only(src, sink), nbytes),
+                            ("fill", lambda: B.measure_fill(dst), nbytes),
+                            ("copy", lambda: B.measure_copy(dst, src), 2 * nbytes)):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        fn()
+        torch.cuda.synchronize()
+        for e0, e1 in evs:
+            e0.record()
+            fn()
+            e1.record()
+        torch.cuda.synchronize()
+        ms = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+        out[name] = round(moved / (ms[len(ms) // 2] * 1e-3) / 1e9, 1)
+    out["unit"] = "GB/s"
+    out["bytes"] = nbytes
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -246,6 +287,21 @@ def main() -> int:
     B.measure_enable(False)
     stage_us = {nm: (1e3 * acc[j] / cnt[j] if cnt[j] else None) for j, nm in enumerate(names)}
 
+    # the two calls of a step timed apart
+    def compress_only(i: int) -> None:
+        if S == 1:
+            B.adatopk_compress(xs[i % NBUF][0], k, idx, val, err, ws)
+        else:
+            B.adatopk_compress_segmented(xs[i % NBUF], ks, idx, val, off, err, ws)
+
+    def decompress_only(i: int) -> None:
+        if S == 1:
+            B.adatopk_decompress_sorted(idx, val, k, y)
+        else:
+            B.adatopk_decompress_segmented(idx, val, off, ys)
+
+    times = call_times(B, torch, compress_only, decompress_only, max(args.steps, 50)) if not graph_timed else {}
+
     # algorithmic bytes per launch of the full-size kernels (b bytes per value, n elements, k kept);
     # the segmented workload decompresses all its tensors in one k_merge launch as well
     b = esize
@@ -282,10 +338,13 @@ def main() -> int:
         "stage_us": {nm: (round(v, 2) if v is not None else None) for nm, v in stage_us.items()},
         "roofline": roofline,
     }
+    out.update(times)
 
     if S == 1 and not args.no_extras:
         out["micro_batch_pipeline"] = micro_batch_pipeline(B, torch, xs, k, tdt, n, esize, ws)
         out["concurrent_streams"] = concurrent_streams(B, torch, xs, k, tdt, n, esize)
+        whole16 = (n * esize // 16) * 16 // esize
+        out["streaming_ceiling"] = streaming_ceilings(B, torch, xs[0][0][:whole16], y[:whole16])
 
     if not args.no_cpu_baseline:
         from oracle import adatopk_oracle as orc
@@ -312,6 +371,25 @@ def main() -> int:
                                "sample": "tensor 1 of %d of the workload, whole (1 compress + 1 decompress of %d elements)"
                                          % (S, x_host.size)}
         out["parity_with_oracle"] = bool(ok)
+        if S > 1:
+            # the same oracle over every tensor of the batch, one host thread per tensor up to the
+            # GPU machine's share of cores (the oracle's C code runs outside the interpreter lock)
+            from concurrent.futures import ThreadPoolExecutor
+
+            cores = min(S, 16, os.cpu_count() or 1)
+
+            def one(s_):
+                ri_, rv_, _ = orc.compress(w.tensors[s_], ks[s_])
+                orc.decompress(ri_, rv_, w.tensors[s_].size)
+
+            t0 = time.perf_counter()
+            with ThreadPoolExecutor(max_workers=cores) as pool:
+                list(pool.map(one, range(S)))
+            par_sec = time.perf_counter() - t0
+            out["cpu_baseline_all_tensors"] = {"value": round(n * esize / par_sec / 1e9, 5), "unit": "GB/s", "cores": cores,
+                                               "host_threads_total": os.cpu_count(), "kind": "oracle",
+                                               "seconds": round(par_sec, 3),
+                                               "sample": "all %d tensors of the workload, one thread per tensor" % S}
     print(json.dumps(out))
     return 0
 
