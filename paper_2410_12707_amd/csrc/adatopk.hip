@@ -265,6 +265,27 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
     return v;
 }
 
+// Counts that lane 0 of every wavefront has put into cnt[0 .. NW) before a barrier: the sum over the
+// wavefronts before this one and the sum over all.  Lanes 0 .. NW-1 load the counts in wavefront order
+// and scan them with row shifts inside the vector unit (NW <= 16, one row); the two results are read out
+// of the scanned lanes into scalar registers.  A dozen instructions, where selecting every count by
+// "is that wavefront before mine" took about fifty in the streaming loop of k_gather.
+template <int DPP_CTRL> __device__ __forceinline__ uint32_t row_shr_add(uint32_t v) {
+    return v + static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), DPP_CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ void wave_counts(const uint32_t *cnt, uint32_t &before, uint32_t &total) {
+    static_assert(NW <= 16, "the scan stays inside one row of 16 lanes");
+    const uint32_t w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint32_t v = cnt[threadIdx.x & (NW - 1)];
+    v = row_shr_add<0x111>(v);                // row_shr:1
+    if (NW > 2) v = row_shr_add<0x112>(v);    // row_shr:2
+    if (NW > 4) v = row_shr_add<0x114>(v);    // row_shr:4
+    if (NW > 8) v = row_shr_add<0x118>(v);    // row_shr:8
+    total = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), NW - 1));
+    const uint32_t prev = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), w ? w - 1 : 0));
+    before = w ? prev : 0u;
+}
+
 // Inclusive prefix sum over the block in thread order; *total = block sum.  sm holds NW words.
 __device__ __forceinline__ uint32_t block_incl_scan(uint32_t v, uint32_t *sm, uint32_t *total) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -662,16 +683,8 @@ __device__ __forceinline__ void gather_tile(const uint32_t (&dw)[Stream<VEC>::SL
         }
     if (lane == 0) wcnt[w] = wc;
     __syncthreads();
-    uint32_t before_v = 0, tot_v = 0;
-#pragma unroll
-    for (int i = 0; i < NW; ++i) {
-        const uint32_t t = wcnt[i];
-        before_v += (i < w) ? t : 0u;
-        tot_v += t;
-    }
-    // wave-uniform values, moved to scalar registers so that the branches below are scalar
-    const uint32_t before = __builtin_amdgcn_readfirstlane(before_v);
-    const uint32_t tot = __builtin_amdgcn_readfirstlane(tot_v);
+    uint32_t before, tot;  // wave-uniform, in scalar registers: the branches below are scalar
+    wave_counts(wcnt, before, tot);
     if (tot == 0) return;  // uniform over the workgroup
     if (running + tot - flushed > STAGE_CAP) {  // uniform: make room
         flush_stage<VEC>(stage, flushed, running, cnt, thr_hi, h2, Li, Lv);
