@@ -28,11 +28,11 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 # From profiles/hbm_traffic_cfg2_k1pct.md (fetched + written bytes per launch); None where no
 # counter run has been made for that kernel.
 TRAFFIC_BYTES = {
-    "k_hist1": 100808124 + 2166848,
-    "k_gather": 101846818 + 3407968,
-    "k_hist3": 1814031 + 591616,
-    "k_emit": 2608508 + 2021408,
-    "k_merge": 6491481 + 112936609,
+    "k_hist1": 100834731 + 2166848,
+    "k_gather": 101826353 + 3407968,
+    "k_hist3": 1805841 + 591616,
+    "k_emit": 2609532 + 2021408,
+    "k_merge": 6496496 + 112868013,
 }
 
 

@@ -198,6 +198,8 @@ template <int VEC> __device__ __forceinline__ uint32_t elem_of(uint32_t dword, i
     return VEC == TAG_F32 ? dword : ((dword >> (16 * h)) & 0xFFFFu);
 }
 
+typedef uint32_t dword4 __attribute__((ext_vector_type(4)));
+
 // Streaming layout of the two full-input kernels.  A tile is TILE consecutive elements; wave w
 // of the workgroup owns the w-th contiguous 1/NW of it and reads it as SLOTS dword loads of
 // 64 consecutive dwords each (256 contiguous bytes per wave-level load).  Index order inside
@@ -220,6 +222,20 @@ template <int VEC> struct Stream {
         const uint32_t *p = static_cast<const uint32_t *>(x) + first_elem(t0, 0) / EPD;
 #pragma unroll
         for (int e = 0; e < SLOTS; ++e) dw[e] = __builtin_nontemporal_load(p + e * 64);
+    }
+    // The same tile with 16-byte loads, thread t taking the t-th, (BLOCK + t)-th ... 16 bytes: for a
+    // kernel that does not care which lane holds which element (the histogram).  Base 16-byte aligned.
+    static __device__ __forceinline__ void load_wide(const void *x, int64_t t0, uint32_t (&dw)[SLOTS]) {
+        static_assert(SLOTS % 4 == 0, "whole 16-byte loads");
+        const dword4 *p = reinterpret_cast<const dword4 *>(static_cast<const uint32_t *>(x) + t0 / EPD) + threadIdx.x;
+#pragma unroll
+        for (int j = 0; j < SLOTS / 4; ++j) {
+            const dword4 v = __builtin_nontemporal_load(p + j * BLOCK);
+            dw[4 * j] = v.x;
+            dw[4 * j + 1] = v.y;
+            dw[4 * j + 2] = v.z;
+            dw[4 * j + 3] = v.w;
+        }
     }
     // ragged tile or misaligned bf16 base: element-wise, guarded; valid[e] has bit h set when
     // element h of slot e is below `end`
@@ -543,6 +559,45 @@ __device__ __forceinline__ void hist1_tile(const uint32_t (&dw)[Stream<VEC>::SLO
                 atomicAdd(&h[(key_of<VEC>(elem_of<VEC>(dw[e], hh)) >> SH1) * HREP + copy], 1u);
 }
 
+// The full tiles of a chunk: `rem` tiles from element t0 on, which is advanced past them.
+// Two register buffers used in turn: the next tile's loads are in flight while this one is
+// counted.  The loop body loads unconditionally and moves no registers (the last one or two
+// tiles are peeled): a load under a condition, or a copy of the new buffer into the old one,
+// makes the compiler wait for the new tile before the old one is processed.
+template <int VEC, bool WIDE>
+__device__ __forceinline__ void hist1_full_tiles(const void *x, int64_t &t0, int64_t rem, uint32_t *h) {
+    using St = Stream<VEC>;
+    uint32_t cur[St::SLOTS], nxt[St::SLOTS], valid[St::SLOTS];
+    auto load = [&](int64_t at, uint32_t(&dw)[St::SLOTS]) {
+        if (WIDE)
+            St::load_wide(x, at, dw);
+        else
+            St::load_fast(x, at, dw);
+    };
+    if (rem <= 0) return;
+    load(t0, cur);
+    while (rem > 2) {
+        load(t0 + TILE, nxt);
+        __builtin_amdgcn_sched_barrier(0);
+        hist1_tile<VEC, true>(cur, valid, h);
+        load(t0 + 2 * static_cast<int64_t>(TILE), cur);
+        __builtin_amdgcn_sched_barrier(0);
+        hist1_tile<VEC, true>(nxt, valid, h);
+        t0 += 2 * static_cast<int64_t>(TILE);
+        rem -= 2;
+    }
+    if (rem == 2) {
+        load(t0 + TILE, nxt);
+        __builtin_amdgcn_sched_barrier(0);
+        hist1_tile<VEC, true>(cur, valid, h);
+        hist1_tile<VEC, true>(nxt, valid, h);
+        t0 += 2 * static_cast<int64_t>(TILE);
+    } else {
+        hist1_tile<VEC, true>(cur, valid, h);
+        t0 += TILE;
+    }
+}
+
 template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist1(Launch a) {
     using St = Stream<VEC>;
     __shared__ uint32_t h[NB1 * HREP];
@@ -558,36 +613,14 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist1(Launch a) {
     for (int b = threadIdx.x; b < NB1 * HREP; b += BLOCK) h[b] = 0;
     __syncthreads();
 
-    // Full tiles, two register buffers used in turn: the next tile's loads are in flight while this
-    // one is counted.  The loop body loads unconditionally and moves no registers (the last one or
-    // two tiles are peeled): a load under a condition, or a copy of the new buffer into the old one,
-    // makes the compiler wait for the new tile before the old one is processed.
-    uint32_t cur[St::SLOTS], nxt[St::SLOTS], valid[St::SLOTS];
+    uint32_t cur[St::SLOTS], valid[St::SLOTS];
     int64_t t0 = beg;
-    int64_t rem = sg.aligned4 ? (end - beg) / TILE : 0;
-    if (rem > 0) {
-        St::load_fast(sg.x, t0, cur);
-        while (rem > 2) {
-            St::load_fast(sg.x, t0 + TILE, nxt);
-            __builtin_amdgcn_sched_barrier(0);
-            hist1_tile<VEC, true>(cur, valid, h);
-            St::load_fast(sg.x, t0 + 2 * static_cast<int64_t>(TILE), cur);
-            __builtin_amdgcn_sched_barrier(0);
-            hist1_tile<VEC, true>(nxt, valid, h);
-            t0 += 2 * static_cast<int64_t>(TILE);
-            rem -= 2;
-        }
-        if (rem == 2) {
-            St::load_fast(sg.x, t0 + TILE, nxt);
-            __builtin_amdgcn_sched_barrier(0);
-            hist1_tile<VEC, true>(cur, valid, h);
-            hist1_tile<VEC, true>(nxt, valid, h);
-            t0 += 2 * static_cast<int64_t>(TILE);
-        } else {
-            hist1_tile<VEC, true>(cur, valid, h);
-            t0 += TILE;
-        }
-    }
+    const int64_t full = sg.aligned4 ? (end - beg) / TILE : 0;
+    // 16-byte loads when the tensor's base allows them (chunks start at multiples of the tile)
+    if ((reinterpret_cast<uintptr_t>(sg.x) & 15) == 0)
+        hist1_full_tiles<VEC, true>(sg.x, t0, full, h);
+    else
+        hist1_full_tiles<VEC, false>(sg.x, t0, full, h);
     for (; t0 < end; t0 += TILE) {
         St::load_slow(sg.x, t0, end, cur, valid);
         hist1_tile<VEC, false>(cur, valid, h);
@@ -790,7 +823,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK, GATHER_WAVES_PER_SIMD) vo
     double acc = 0.0;
     uint32_t running = 0, flushed = 0;
     int wb = 0;
-    // Full tiles, two register buffers used in turn, unconditional loads, peeled tail (see k_hist1).
+    // Full tiles, two register buffers used in turn, unconditional loads, peeled tail (see hist1_full_tiles).
     int64_t t0 = beg;
     int64_t rem = ntiles;
     auto tile = [&](const uint32_t(&dw)[St::SLOTS]) {
@@ -1318,7 +1351,6 @@ __global__ __launch_bounds__(BLOCK) void k_scatter_add(const I *idx, const typen
 // 210 -> 179 us, the next call's first read pass 217 -> 178 us; single tensors of 150 to 400 MB: the
 // compress + decompress step 4 to 6 % faster).  An output of 100 MB is better left to the cache
 // (decompress 16 us with plain stores, 25 us with nontemporal ones).
-typedef uint32_t dword4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ void store16(uint4 *dst, uint4 v, bool stream) {
     if (stream) __builtin_nontemporal_store(dword4{v.x, v.y, v.z, v.w}, reinterpret_cast<dword4 *>(dst));
     else *dst = v;
