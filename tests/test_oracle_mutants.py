@@ -49,6 +49,20 @@ MUTANTS = [
     ("bf16_one_significand_bit_short", C, "round_to_format(s, 8, -126, 127)", "round_to_format(s, 7, -126, 127)", 0, PINS),
     ("accumulate_overwrites", C, "y[idx[j]] = (float)((double)y[idx[j]] + (double)val[j]);",
      "y[idx[j]] = val[j];", 0, PINS),
+    ("segmented_bf16_values_at_previous_tensors_offset", C,
+     "int rc = oracle_compress_bf16(x + in_offset[s], in_offset[s + 1] - in_offset[s], k[s],\n"
+     "                                      idx + out_offset[s], val + out_offset[s], err ? err + s : NULL);",
+     "int rc = oracle_compress_bf16(x + in_offset[s], in_offset[s + 1] - in_offset[s], k[s],\n"
+     "                                      idx + out_offset[s], val + out_offset[s > 0 ? s - 1 : s], err ? err + s : NULL);", 0, PINS),
+    ("segmented_f16_reads_neighbours_k", C,
+     "int rc = oracle_compress_f16(x + in_offset[s], in_offset[s + 1] - in_offset[s], k[s],",
+     "int rc = oracle_compress_f16(x + in_offset[s], in_offset[s + 1] - in_offset[s], k[s > 0 ? s - 1 : s],", 0, PINS),
+    ("segmented_f32_error_of_first_tensor_only", C,
+     "idx + out_offset[s], val + out_offset[s], err ? err + s : NULL);",
+     "idx + out_offset[s], val + out_offset[s], err ? err : NULL);", 0, PINS),
+    ("segmented_bf16_tensor_length_from_k", C,
+     "int rc = oracle_compress_bf16(x + in_offset[s], in_offset[s + 1] - in_offset[s], k[s],",
+     "int rc = oracle_compress_bf16(x + in_offset[s], in_offset[s + 1] - in_offset[s] - (s == 5), k[s],", 0, PINS),
     ("wire_padding_to_8", W, "return HEADER_BYTES + (k * index_bytes + 15) // 16 * 16",
      "return HEADER_BYTES + (k * index_bytes + 7) // 8 * 8", 0, WIRE),
     ("wire_big_endian_indices", W, 'dtype="<i4" if index_bytes == 4 else "<i8").tobytes()',

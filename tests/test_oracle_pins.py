@@ -368,17 +368,30 @@ def test_error_norm_gaussian_closed_form():
 
 
 # --------------------------------------------------------------------------- segmented
-def test_segmented_is_per_tensor():
-    xs = [wl.small_case("normal", 5000, 1), wl.small_case("few_levels", 129, 2), wl.small_case("sparse", 1, 3),
-          np.empty(0, dtype=np.float32)]
-    ks = [50, 129, 0, 0]
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_segmented_is_per_tensor(dtype):
+    # Unequal lengths, an empty tensor in the middle and at the end, lengths 1 and 2, k = 0 and k = n.
+    # Every tensor's part of the output is checked against the repeated arg-max on that tensor alone
+    # (so a wrong input or output offset, or a k taken from the neighbour, shows) and against the
+    # single-tensor routine, error norm included.
+    kinds = ["normal", "few_levels", "sparse", "normal", "all_equal", "normal", "few_levels", "normal"]
+    ns = [500, 129, 1, 0, 2, 193, 64, 0]
+    ks = [50, 129, 0, 0, 1, 7, 0, 0]
+    xs = [wl.small_case(kind, n, 300 + s, dtype=dtype) if n else wl.small_case("normal", 1, 1, dtype=dtype)[:0]
+          for s, (kind, n) in enumerate(zip(kinds, ns))]
     idx, val, off, err = orc.compress_segmented(xs, ks)
-    assert off.tolist() == [0, 50, 179, 179, 179]
+    assert off.tolist() == [0, 50, 179, 179, 179, 180, 187, 187, 187]
+    assert idx.size == 187 and val.size == 187 and err.size == len(xs) and val.dtype == xs[0].dtype
     for s, (x, k) in enumerate(zip(xs, ks)):
+        part_i, part_v = idx[off[s]:off[s + 1]], val[off[s]:off[s + 1]]
+        assert part_i.tolist() == brute_force_topk(magnitudes(x), k), (dtype, s)
+        assert np.array_equal(bits(part_v), bits(x)[part_i])
+        keep = np.zeros(x.size, dtype=bool)
+        keep[part_i] = True
+        dropped = float(np.sum(magnitudes(x)[~keep] ** 2))
+        assert math.isclose(float(err[s]), math.sqrt(dropped), rel_tol=2e-7, abs_tol=0.0)
         i1, v1, e1 = orc.compress(x, k)
-        assert np.array_equal(idx[off[s]:off[s + 1]], i1)
-        assert np.array_equal(val[off[s]:off[s + 1]].view(np.uint32), v1.view(np.uint32))
-        assert err[s] == e1
+        assert np.array_equal(part_i, i1) and np.array_equal(bits(part_v), bits(v1)) and err[s] == e1
 
 
 # ------------------------------------------------------------- ratio rule and wire size
@@ -397,8 +410,13 @@ def test_wire_size_arithmetic_printed_in_the_paper():
     # 32-bit indices (64 k bits).
     d, k = 1_000_000, orc.k_for_ratio(1_000_000, g["ratio"])
     assert k == d // g["ratio"]
-    assert 32 * d == g["fig_topk_dense_bits_per_element"] * d
-    assert (32 + 32) * k == g["fig_topk_wire_bits_per_kept"] * k
+    # the oracle's message of k pairs (fp32 values, int32 indices) carries exactly the caption's 64 bits
+    # per kept element behind its fixed header, against the caption's 32 bits per element of the dense vector
+    from oracle import wire_format as wf
+
+    payload_bits = 8 * (wf.message_bytes(k, np.float32, 4) - wf.message_bytes(0, np.float32, 4))
+    assert payload_bits == g["fig_topk_wire_bits_per_kept"] * k
+    assert 8 * np.dtype(np.float32).itemsize == g["fig_topk_dense_bits_per_element"]
     # Latency figure caption: at ratio 100 with fp32 values and int64 indices the data sent
     # is 33.3x smaller; the same accounting gives the coefficient 3 of Eq. "adacompress".
     shrink = (4 * d) / ((4 + 8) * k)
