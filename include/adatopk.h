@@ -56,8 +56,9 @@ typedef enum {
 } adatopk_status;
 
 /* Bytes of device workspace that a compress call over `num_segments` tensors holding
- * `n_total` elements in all needs (single-tensor call: num_segments = 1).  Returns 0
- * for invalid arguments.  Host-only; touches no device. */
+ * `n_total` elements in all needs (single-tensor call: num_segments = 1): the scratch of the
+ * threshold search and of the ordered compaction of Sec. 5.1's Top-K step (per-chunk digit counts,
+ * the candidate list).  Returns 0 for invalid arguments.  Host-only; touches no device. */
 size_t adatopk_workspace_bytes(int64_t n_total, int32_t num_segments, adatopk_dtype dt);
 
 /* Top-K sparsification of one tensor (Sec. 5.1).
@@ -77,7 +78,7 @@ adatopk_status adatopk_compress(const void *dense, int64_t n, adatopk_dtype dt, 
  *   idx, val   device, k entries; indices unique; any order (ascending is fastest)
  *   dense_out  device, n values of type dt
  * Indices outside [0, n) are skipped; with duplicate indices one of the values wins.
- * k == 0 gives all zeros.  EINVAL as for compress. */
+ * k == 0 gives all zeros.  EINVAL as for compress (k > n included). */
 adatopk_status adatopk_decompress(const int32_t *idx, const void *val, int64_t k, adatopk_dtype dt,
                                   void *dense_out, int64_t n, void *hip_stream);
 
@@ -217,8 +218,9 @@ adatopk_status adatopk_decompress_wire(const void *wire, size_t wire_bytes, adat
 adatopk_status adatopk_adaptive_ratios(const double *R, int32_t m, double r_user, double coeff,
                                        double *r_out);
 
-/* Host-only: elements kept at ratio r_i >= 1: max(1, floor(n / r_i)), at most n; 0 when
- * n <= 0; -1 when r_i < 1 or is NaN. */
+/* Host-only: elements kept at ratio r_i >= 1 (Sec. 5.2: a link with ratio r_i sends one element in
+ * r_i; ratio 1 sends the tensor as it is): max(1, floor(n / r_i)), at most n; 0 when n <= 0; -1 when
+ * r_i < 1 or is NaN. */
 int64_t adatopk_k_for_ratio(int64_t n, double r_i);
 
 /* Host-only: the estimates that feed the rule (paper Sec. 3.5 and 3.6) and what the rule does to

@@ -22,7 +22,11 @@ OK, EINVAL, EWORKSPACE, ERUNTIME, ENOTIMPL = 0, 1, 2, 3, 4
 _STATUS = {OK: "ADATOPK_OK", EINVAL: "ADATOPK_EINVAL", EWORKSPACE: "ADATOPK_EWORKSPACE",
            ERUNTIME: "ADATOPK_ERUNTIME", ENOTIMPL: "ADATOPK_ENOTIMPL"}
 
-_lib = None
+MEASURE_LIB_PATH = os.path.join(_HERE, "libadatopk_measure.so")
+
+_lib = None          # the product library
+_measure_lib = None  # the same sources built with the benchmark's timing hooks (adatopk_measure.h)
+_active = None       # what load_library() returns when set: the measuring build inside `with measuring()`
 
 
 class AdaTopKError(RuntimeError):
@@ -33,12 +37,62 @@ class AdaTopKError(RuntimeError):
 
 def load_library() -> ctypes.CDLL:
     global _lib
+    if _active is not None:
+        return _active
     if _lib is not None:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise ImportError("libadatopk.so is not built: run `python -m paper_2410_12707_amd.build` "
                           "(or __graft_entry__.build()) first; there is no CPU fallback")
-    lib = ctypes.CDLL(LIB_PATH)
+    _lib = _declare(ctypes.CDLL(LIB_PATH))
+    return _lib
+
+
+def load_measure_library() -> ctypes.CDLL:
+    """The measuring build: the whole C ABI plus the hooks of adatopk_measure.h (benchmarks only)."""
+    global _measure_lib
+    if _measure_lib is not None:
+        return _measure_lib
+    if not os.path.exists(MEASURE_LIB_PATH):
+        raise ImportError("libadatopk_measure.so is not built: run `python -m paper_2410_12707_amd.build`")
+    lib = _declare(ctypes.CDLL(MEASURE_LIB_PATH))
+    i32, p, sz = ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t
+    lib.adatopk_measure_enable.argtypes = [i32]
+    lib.adatopk_measure_enable.restype = i32
+    lib.adatopk_measure_stage_count.restype = i32
+    lib.adatopk_measure_stage_name.argtypes = [i32]
+    lib.adatopk_measure_stage_name.restype = ctypes.c_char_p
+    lib.adatopk_measure_read.argtypes = [p]
+    lib.adatopk_measure_read.restype = i32
+    lib.adatopk_measure_copy.argtypes = [p, p, sz, p]
+    lib.adatopk_measure_copy.restype = i32
+    lib.adatopk_measure_read_only.argtypes = [p, sz, p, p]
+    lib.adatopk_measure_read_only.restype = i32
+    lib.adatopk_measure_fill.argtypes = [p, sz, p]
+    lib.adatopk_measure_fill.restype = i32
+    _measure_lib = lib
+    return lib
+
+
+class measuring:
+    """``with measuring():`` routes every call of this module through the measuring build and times each
+    kernel launch with events of its own; ``measure_read()`` inside the block returns the durations."""
+
+    def __enter__(self):
+        global _active
+        lib = load_measure_library()
+        _check(lib.adatopk_measure_enable(1), "adatopk_measure_enable")
+        _active = lib
+        return self
+
+    def __exit__(self, *exc):
+        global _active
+        _active = None
+        _check(load_measure_library().adatopk_measure_enable(0), "adatopk_measure_enable")
+        return False
+
+
+def _declare(lib: ctypes.CDLL) -> ctypes.CDLL:
     i64, i32, p, sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t
     lib.adatopk_workspace_bytes.argtypes = [i64, i32, i32]
     lib.adatopk_workspace_bytes.restype = sz
@@ -79,20 +133,6 @@ def load_library() -> ctypes.CDLL:
     lib.adatopk_pipeline_time_compressed.restype = dbl
     lib.adatopk_plan_keep_counts.argtypes = [p, p, p, i32, i32, dbl, dbl, p, p]
     lib.adatopk_plan_keep_counts.restype = i32
-    lib.adatopk_measure_enable.argtypes = [i32]
-    lib.adatopk_measure_enable.restype = i32
-    lib.adatopk_measure_stage_count.restype = i32
-    lib.adatopk_measure_stage_name.argtypes = [i32]
-    lib.adatopk_measure_stage_name.restype = ctypes.c_char_p
-    lib.adatopk_measure_read.argtypes = [p]
-    lib.adatopk_measure_read.restype = i32
-    lib.adatopk_measure_copy.argtypes = [p, p, sz, p]
-    lib.adatopk_measure_copy.restype = i32
-    lib.adatopk_measure_read_only.argtypes = [p, sz, p, p]
-    lib.adatopk_measure_read_only.restype = i32
-    lib.adatopk_measure_fill.argtypes = [p, sz, p]
-    lib.adatopk_measure_fill.restype = i32
-    _lib = lib
     return lib
 
 
@@ -128,6 +168,30 @@ def _dev_or_pinned(t: torch.Tensor) -> int:
     raise ValueError("adatopk needs a contiguous device tensor or pinned host tensor here")
 
 
+def _check_outputs(dtype: torch.dtype, k_total: int, idx_out: torch.Tensor, val_out: torch.Tensor,
+                   err_norm_out: Optional[torch.Tensor], num_tensors: int) -> None:
+    """Output buffers of a compress call: the library gets raw pointers and cannot see their sizes or
+    types, so a buffer that is too small or of another type is refused here."""
+    if idx_out.dtype != torch.int32 or idx_out.numel() < k_total:
+        raise ValueError("idx_out must be int32 with at least %d entries" % k_total)
+    if val_out.dtype != dtype or val_out.numel() < k_total:
+        raise ValueError("val_out must have the dense tensor's dtype (%s) and at least %d entries" % (dtype, k_total))
+    if err_norm_out is not None and (err_norm_out.dtype != torch.float32 or err_norm_out.numel() < num_tensors):
+        raise ValueError("err_norm_out must be float32 with one entry per tensor (%d)" % num_tensors)
+
+
+def _check_pairs(dtype: torch.dtype, k_total: int, idx: torch.Tensor, val: torch.Tensor) -> None:
+    if idx.dtype != torch.int32 or idx.numel() < k_total:
+        raise ValueError("idx must be int32 with at least %d entries" % k_total)
+    if val.dtype != dtype or val.numel() < k_total:
+        raise ValueError("val must have the dense tensor's dtype (%s) and at least %d entries" % (dtype, k_total))
+
+
+def _one_dtype(tensors: Sequence[torch.Tensor]) -> None:
+    if any(t.dtype != tensors[0].dtype for t in tensors):
+        raise ValueError("all tensors of a segmented call must share one dtype")
+
+
 def adatopk_workspace_bytes(n_total: int, num_segments: int, dtype: torch.dtype) -> int:
     return int(load_library().adatopk_workspace_bytes(int(n_total), int(num_segments), _dtype_code(dtype)))
 
@@ -141,6 +205,7 @@ def adatopk_compress(dense: torch.Tensor, k: int, idx_out: torch.Tensor, val_out
                      err_norm_out: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
     """Enqueues compress of one tensor on the current stream; outputs are written in place."""
     lib = load_library()
+    _check_outputs(dense.dtype, int(k), idx_out, val_out, err_norm_out, 1)
     err_ptr = _dev(err_norm_out) if err_norm_out is not None else None
     _check(lib.adatopk_compress(_dev(dense), dense.numel(), _dtype_code(dense.dtype), int(k), _dev(idx_out),
                                 _dev(val_out), err_ptr, _dev(workspace), workspace.numel(), _stream()),
@@ -149,6 +214,7 @@ def adatopk_compress(dense: torch.Tensor, k: int, idx_out: torch.Tensor, val_out
 
 def adatopk_decompress(idx: torch.Tensor, val: torch.Tensor, k: int, dense_out: torch.Tensor) -> None:
     lib = load_library()
+    _check_pairs(dense_out.dtype, int(k), idx, val)
     _check(lib.adatopk_decompress(_dev(idx), _dev(val), int(k), _dtype_code(dense_out.dtype), _dev(dense_out),
                                   dense_out.numel(), _stream()), "adatopk_decompress")
 
@@ -156,6 +222,7 @@ def adatopk_decompress(idx: torch.Tensor, val: torch.Tensor, k: int, dense_out: 
 def adatopk_decompress_sorted(idx: torch.Tensor, val: torch.Tensor, k: int, dense_out: torch.Tensor) -> None:
     """Decompress for strictly ascending idx (what adatopk_compress produces)."""
     lib = load_library()
+    _check_pairs(dense_out.dtype, int(k), idx, val)
     _check(lib.adatopk_decompress_sorted(_dev(idx), _dev(val), int(k), _dtype_code(dense_out.dtype),
                                          _dev(dense_out), dense_out.numel(), _stream()), "adatopk_decompress_sorted")
 
@@ -163,6 +230,7 @@ def adatopk_decompress_sorted(idx: torch.Tensor, val: torch.Tensor, k: int, dens
 def adatopk_decompress_accumulate(idx: torch.Tensor, val: torch.Tensor, k: int, dense_inout: torch.Tensor) -> None:
     """dense_inout[idx[j]] += val[j] for unique indices; every other entry is left alone."""
     lib = load_library()
+    _check_pairs(dense_inout.dtype, int(k), idx, val)
     _check(lib.adatopk_decompress_accumulate(_dev(idx), _dev(val), int(k), _dtype_code(dense_inout.dtype),
                                              _dev(dense_inout), dense_inout.numel(), _stream()),
            "adatopk_decompress_accumulate")
@@ -174,6 +242,9 @@ def adatopk_decompress_segmented(idx: torch.Tensor, val: torch.Tensor, out_offse
     lib = load_library()
     S = len(dense_out)
     dt = _dtype_code(dense_out[0].dtype) if S else F32
+    if S:
+        _one_dtype(dense_out)
+        _check_pairs(dense_out[0].dtype, int(out_offset[S]), idx, val)
     ptrs = (ctypes.c_void_p * max(S, 1))(*[_dev(t) for t in dense_out])
     ns = (ctypes.c_int64 * max(S, 1))(*[t.numel() for t in dense_out])
     off = (ctypes.c_int64 * (S + 1))(*[int(v) for v in out_offset])
@@ -223,6 +294,8 @@ def adatopk_compress_wire_segmented(dense: Sequence[torch.Tensor], ks: Sequence[
     lib = load_library()
     S = len(dense)
     dt = _dtype_code(dense[0].dtype) if S else F32
+    if S:
+        _one_dtype(dense)
     ptrs = (ctypes.c_void_p * max(S, 1))(*[_dev(t) for t in dense])
     ns = (ctypes.c_int64 * max(S, 1))(*[t.numel() for t in dense])
     kk = (ctypes.c_int64 * max(S, 1))(*[int(v) for v in ks])
@@ -247,6 +320,9 @@ def adatopk_compress_segmented(dense: Sequence[torch.Tensor], ks: Sequence[int],
     lib = load_library()
     S = len(dense)
     dt = _dtype_code(dense[0].dtype) if S else F32
+    if S:
+        _one_dtype(dense)
+        _check_outputs(dense[0].dtype, sum(int(v) for v in ks), idx_out, val_out, err_norm_out, S)
     ptrs = (ctypes.c_void_p * max(S, 1))(*[_dev(t) for t in dense])
     ns = (ctypes.c_int64 * max(S, 1))(*[t.numel() for t in dense])
     kk = (ctypes.c_int64 * max(S, 1))(*[int(v) for v in ks])
@@ -301,18 +377,14 @@ def adatopk_plan_keep_counts(alpha: Sequence[float], beta: Sequence[float], n: S
     return [r_out[i] for i in range(m)], [int(k_out[i]) for i in range(m)]
 
 
-# ------------------------------------------------------------------ measurement hooks
-def measure_enable(on: bool) -> None:
-    _check(load_library().adatopk_measure_enable(1 if on else 0), "adatopk_measure_enable")
-
-
+# ------------------------------------------------------------------ measurement hooks (measuring build only)
 def measure_stage_names():
-    lib = load_library()
+    lib = load_measure_library()
     return [lib.adatopk_measure_stage_name(i).decode() for i in range(lib.adatopk_measure_stage_count())]
 
 
 def measure_read():
-    lib = load_library()
+    lib = load_measure_library()
     n = lib.adatopk_measure_stage_count()
     buf = (ctypes.c_float * n)()
     _check(lib.adatopk_measure_read(buf), "adatopk_measure_read")
@@ -321,15 +393,15 @@ def measure_read():
 
 def measure_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
     nbytes = src.numel() * src.element_size()
-    _check(load_library().adatopk_measure_copy(_dev(dst), _dev(src), nbytes, _stream()), "adatopk_measure_copy")
+    _check(load_measure_library().adatopk_measure_copy(_dev(dst), _dev(src), nbytes, _stream()), "adatopk_measure_copy")
 
 
 def measure_read_only(src: torch.Tensor, sink: torch.Tensor) -> None:
     nbytes = src.numel() * src.element_size()
-    _check(load_library().adatopk_measure_read_only(_dev(src), nbytes, _dev(sink), _stream()),
+    _check(load_measure_library().adatopk_measure_read_only(_dev(src), nbytes, _dev(sink), _stream()),
            "adatopk_measure_read_only")
 
 
 def measure_fill(dst: torch.Tensor) -> None:
     nbytes = dst.numel() * dst.element_size()
-    _check(load_library().adatopk_measure_fill(_dev(dst), nbytes, _stream()), "adatopk_measure_fill")
+    _check(load_measure_library().adatopk_measure_fill(_dev(dst), nbytes, _stream()), "adatopk_measure_fill")

@@ -49,29 +49,21 @@
 
 #include <stdint.h>
 #include <stddef.h>
-#include <stdlib.h>
 #include <string.h>
 
 #include "adatopk.h"
+#include "wire_layout.h"
+#ifdef ADATOPK_MEASURE_BUILD
 #include "adatopk_measure.h"
+#endif
 
 namespace {
 
-// Launch-shape constants; the -D overrides exist for tuning sweeps only.
-#ifndef ADATOPK_BLOCK
-#define ADATOPK_BLOCK 512
-#endif
-#ifndef ADATOPK_HREP
-#define ADATOPK_HREP 1
-#endif
-#ifndef ADATOPK_CTARGET
-#define ADATOPK_CTARGET 512
-#endif
-constexpr int BLOCK = ADATOPK_BLOCK;  // threads per workgroup
+// Launch-shape constants.
+constexpr int BLOCK = 512;            // threads per workgroup
 constexpr int NW = BLOCK / 64;        // wavefronts per workgroup
 constexpr int EPT = 16;               // input elements per thread per tile
 constexpr int TILE = BLOCK * EPT;     // input elements per workgroup per tile, both dtypes
-constexpr int HREP = ADATOPK_HREP;    // copies of the top-digit LDS histogram (spreads same-bin lanes over banks)
 constexpr int LU = 4;               // list elements per thread per tile in the list kernels
 constexpr int BITS1 = 11, BITS2 = 10, BITS3 = 10;
 constexpr int NB1 = 1 << BITS1, NB2 = 1 << BITS2, NB3 = 1 << BITS3;
@@ -81,28 +73,18 @@ constexpr int NC1 = 64;             // coarse boundaries of the top digit: every
 constexpr int FINE1 = NB1 / NC1;    // fine bins per coarse interval
 constexpr int NC2 = 32;             // the same for the second digit
 constexpr int MAXSEG = 64;          // segments per launch (the table travels as kernel arguments)
-constexpr int CTARGET = ADATOPK_CTARGET;  // chunks aimed at per launch of several tensors (and the most any launch has)
-#ifndef ADATOPK_CTARGET_ONE
-#define ADATOPK_CTARGET_ONE 256
-#endif
+constexpr int CTARGET = 512;        // chunks aimed at per launch of several tensors (and the most any launch has)
 // chunks aimed at for a single tensor: one workgroup per compute unit.  Half the rows for every
 // prologue to sum (76 instead of 77.5 us per step on the 100 MB tensor); a batch of tensors with
 // unequal keep counts wants the finer split, whose workgroups even out (24 tensors: 560 vs 600 us).
-constexpr int CTARGET_ONE = ADATOPK_CTARGET_ONE < ADATOPK_CTARGET ? ADATOPK_CTARGET_ONE : ADATOPK_CTARGET;
+constexpr int CTARGET_ONE = 256;
 constexpr int LB_ELEMS = 8192;      // input elements per list block when sizing the list grid
 constexpr int LB_TOTAL = 4096;      // list blocks aimed at per launch, all segments together
-#ifndef ADATOPK_MERGE_SPANS
-#define ADATOPK_MERGE_SPANS 1024
-#endif
-constexpr size_t MERGE_SPANS = ADATOPK_MERGE_SPANS;  // output spans aimed at by the one-kernel decompress
+constexpr size_t MERGE_SPANS = 1024;       // output spans aimed at by the one-kernel decompress
 constexpr int64_t MERGE_DENSE_RATIO = 32;  // k > n / 32 takes the LDS-built variant of the one-kernel decompress
-constexpr size_t MERGE_MIN_SPAN = 16384;  // bytes; smaller outputs use fewer workgroups
-#ifndef ADATOPK_MERGE_MAX_SPAN
-#define ADATOPK_MERGE_MAX_SPAN 98304
-#endif
-constexpr size_t MERGE_MAX_SPAN = ADATOPK_MERGE_MAX_SPAN;  // bytes; larger outputs use more workgroups
+constexpr size_t MERGE_MIN_SPAN = 16384;   // bytes; smaller outputs use fewer workgroups
+constexpr size_t MERGE_MAX_SPAN = 98304;   // bytes; larger outputs use more workgroups
 static_assert(LU * NW <= 64, "per-tile wave counts must fit one wavefront scan");
-static_assert(HREP == 1 || HREP == 2 || HREP == 4 || HREP == 8, "histogram copies");
 static_assert(NB1 % BLOCK == 0 && NB2 % BLOCK == 0 && NB3 % BLOCK == 0, "bins split evenly over threads");
 static_assert(BITS1 + BITS2 + BITS3 == 31, "digits cover the 31-bit key");
 static_assert(BLOCK >= 256, "k_emit scans the list blocks of a segment with one thread each");
@@ -525,13 +507,11 @@ __device__ __forceinline__ ColumnPick column_pick(const uint32_t *rows, const ui
 }
 
 // ------------------------------------------------------------------ k_hist1
-// LDS histogram of the top digit with HREP interleaved copies: lane l adds into copy l % HREP of
-// its bin, stored at word bin * HREP + copy, so lanes that share a hot bin spread over banks.
+// LDS histogram of the top digit of one tile.
 template <int VEC, bool FAST>
 __device__ __forceinline__ void hist1_tile(const uint32_t (&dw)[Stream<VEC>::SLOTS],
                                            const uint32_t (&valid)[Stream<VEC>::SLOTS], uint32_t *h) {
     constexpr int EPD = Stream<VEC>::EPD;
-    const uint32_t copy = threadIdx.x & (HREP - 1);
     // Probe: does half of the wavefront share the top digit of lane 0's first element?  Then the tile
     // is counted with that digit's lanes taken together, slot by slot (one add per slot for them);
     // otherwise every lane adds for itself, which is the faster way when digits are spread.
@@ -546,9 +526,9 @@ __device__ __forceinline__ void hist1_tile(const uint32_t (&dw)[Stream<VEC>::SLO
             for (int hh = 0; hh < EPD; ++hh) {
                 const uint32_t d = key_of<VEC>(elem_of<VEC>(dw[e], hh)) >> SH1;
                 hot_count += static_cast<uint32_t>(__popcll(__ballot(d == hot)));
-                if (d != hot) atomicAdd(&h[d * HREP + copy], 1u);
+                if (d != hot) atomicAdd(&h[d], 1u);
             }
-        if ((threadIdx.x & 63) == 0) atomicAdd(&h[hot * HREP], hot_count);
+        if ((threadIdx.x & 63) == 0) atomicAdd(&h[hot], hot_count);
         return;
     }
 #pragma unroll
@@ -556,7 +536,7 @@ __device__ __forceinline__ void hist1_tile(const uint32_t (&dw)[Stream<VEC>::SLO
 #pragma unroll
         for (int hh = 0; hh < EPD; ++hh)
             if (FAST || ((valid[e] >> hh) & 1u))
-                atomicAdd(&h[(key_of<VEC>(elem_of<VEC>(dw[e], hh)) >> SH1) * HREP + copy], 1u);
+                atomicAdd(&h[key_of<VEC>(elem_of<VEC>(dw[e], hh)) >> SH1], 1u);
 }
 
 // The full tiles of a chunk: `rem` tiles from element t0 on, which is advanced past them.
@@ -600,7 +580,7 @@ __device__ __forceinline__ void hist1_full_tiles(const void *x, int64_t &t0, int
 
 template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist1(Launch a) {
     using St = Stream<VEC>;
-    __shared__ uint32_t h[NB1 * HREP];
+    __shared__ uint32_t h[NB1];
     __shared__ uint32_t sm[NW];
 
     const int g = blockIdx.x;
@@ -610,7 +590,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist1(Launch a) {
     const int64_t beg = static_cast<int64_t>(c) * a.E;
     const int64_t end = (beg + a.E < sg.n) ? beg + a.E : sg.n;
 
-    for (int b = threadIdx.x; b < NB1 * HREP; b += BLOCK) h[b] = 0;
+    for (int b = threadIdx.x; b < NB1; b += BLOCK) h[b] = 0;
     __syncthreads();
 
     uint32_t cur[St::SLOTS], valid[St::SLOTS];
@@ -627,21 +607,6 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist1(Launch a) {
     }
     __syncthreads();
 
-    if (HREP > 1) {  // fold the copies into copy 0, compacted to h[0 .. NB1)
-        uint32_t folded[NB1 / BLOCK];
-#pragma unroll
-        for (int j = 0; j < NB1 / BLOCK; ++j) {
-            const int b = threadIdx.x + j * BLOCK;
-            uint32_t t = 0;
-#pragma unroll
-            for (int r = 0; r < HREP; ++r) t += h[b * HREP + r];
-            folded[j] = t;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int j = 0; j < NB1 / BLOCK; ++j) h[threadIdx.x + j * BLOCK] = folded[j];
-        __syncthreads();
-    }
     // The chunk's row of suffix sums, and every FINE1-th entry of it once more, contiguously: the
     // next kernel finds the bucket of the k-th key from the column sums of these rows alone.
     block_suffix_inplace<NB1>(h, sm);
@@ -1355,10 +1320,7 @@ __device__ __forceinline__ void store16(uint4 *dst, uint4 v, bool stream) {
     if (stream) __builtin_nontemporal_store(dword4{v.x, v.y, v.z, v.w}, reinterpret_cast<dword4 *>(dst));
     else *dst = v;
 }
-#ifndef ADATOPK_STREAM_STORE_MB
-#define ADATOPK_STREAM_STORE_MB 128
-#endif
-constexpr size_t STREAM_STORE_BYTES = static_cast<size_t>(ADATOPK_STREAM_STORE_MB) << 20;
+constexpr size_t STREAM_STORE_BYTES = static_cast<size_t>(128) << 20;
 
 // Lower bound by one wavefront: the first j in [0, k) with idx[j] >= value (k if none), for
 // ascending idx.  The 64 lanes probe evenly spaced entries; the number of probes below `value`
@@ -1540,6 +1502,7 @@ template <typename R> __global__ __launch_bounds__(BLOCK) void k_merge_seg(const
     else merge_span<R, int32_t>(idx, val, sg.k, sg.y, total, head, a.span, blk, nblk, stream, s_range);
 }
 
+#ifdef ADATOPK_MEASURE_BUILD
 __global__ __launch_bounds__(BLOCK) void k_copy16(uint4 *dst, const uint4 *src, size_t n16) {
     const size_t stride = static_cast<size_t>(gridDim.x) * BLOCK;
     for (size_t i = static_cast<size_t>(blockIdx.x) * BLOCK + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
@@ -1555,11 +1518,13 @@ __global__ __launch_bounds__(BLOCK) void k_read16(const uint4 *src, size_t n16, 
     if (f == 0x9E3779B9u) sink[0] = f;  // keeps the loads alive; practically never true
 }
 
-// ------------------------------------------------------------------ host side: plan and launch
-inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+#endif
 
-inline int elem_size(adatopk_dtype dt) { return dt == ADATOPK_F32 ? 4 : 2; }
-inline bool dtype_ok(adatopk_dtype dt) { return dt == ADATOPK_F32 || dt == ADATOPK_BF16 || dt == ADATOPK_F16; }
+// ------------------------------------------------------------------ host side: plan and launch
+using adatopk_internal::align_up;
+using adatopk_internal::dtype_ok;
+using adatopk_internal::elem_size;
+using adatopk_internal::wire_val_offset;
 
 int64_t chunk_elems(int64_t n_total, int64_t target) {
     const int64_t tile = TILE;
@@ -1625,24 +1590,31 @@ void bounds_for(int64_t n_total, int32_t S, adatopk_dtype dt, int64_t *max_chunk
     *max_lb = static_cast<int64_t>(batch) * list_blocks_cap(S);
 }
 
-// ---- stage timing (measurement hook): in measuring mode every kernel is launched with its own
-// start / stop events, whose timestamps are those of the dispatch itself (as a profiler sees it)
+// Every kernel launch of the library goes through launch().  The stage names the kernel for the
+// measuring build of this file (ADATOPK_MEASURE_BUILD, a library of its own next to the product
+// library), which gives every launch start / stop events carrying the timestamps of the dispatch
+// itself, as a profiler sees it; the product build launches plainly and keeps no state.
 enum Stage { ST_HIST1, ST_GATHER, ST_HIST3, ST_EMIT, ST_FILL, ST_SCATTER, ST_MERGE, ST_HEADER, ST_SMALL, NSTAGE };
+#ifdef ADATOPK_MEASURE_BUILD
 const char *const kStageNames[NSTAGE] = {"k_hist1", "k_gather", "k_hist3", "k_emit",
                                          "k_fill",  "k_scatter", "k_merge", "k_wire_header", "k_small"};
 bool g_measure = false;
 bool g_events_made = false;
 hipEvent_t g_start[NSTAGE], g_stop[NSTAGE];
 bool g_ran[NSTAGE];  // launched, with events, since the last read
+#endif
 
 template <typename K, typename... Args>
 inline void launch(int stage, K kernel, dim3 grid, hipStream_t st, Args... args) {
+#ifdef ADATOPK_MEASURE_BUILD
     if (g_measure) {
         hipExtLaunchKernelGGL(kernel, grid, dim3(BLOCK), 0, st, g_start[stage], g_stop[stage], 0, args...);
         g_ran[stage] = true;
-    } else {
-        hipLaunchKernelGGL(kernel, grid, dim3(BLOCK), 0, st, args...);
+        return;
     }
+#endif
+    (void)stage;
+    hipLaunchKernelGGL(kernel, grid, dim3(BLOCK), 0, st, args...);
 }
 
 template <int VEC> adatopk_status launch_batch(const Launch &a, int total_chunks, int total_lb, hipStream_t st) {
@@ -1657,8 +1629,9 @@ template <int VEC> adatopk_status launch_batch(const Launch &a, int total_chunks
 
 // Where a compress call writes.  Plain: idx_out / val_out arrays, tensor s at element offset[s]
 // (offset = exclusive scan of k, S + 1 entries).  Wire: one message buffer (idx_out), tensor s's
-// index section at byte offset[s] (S entries), its values behind the padded indices, and the
-// error norms in the workspace (err_out is ignored) for the header kernel to pick up.
+// message at byte offset[s] (S entries): its index section behind the header, its values behind the
+// padded indices, and the error norms in the workspace (err_out is ignored) for the header kernel
+// to pick up.
 struct OutSpec {
     void *idx_out;
     int idx_bytes;
@@ -1710,7 +1683,7 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
             const int32_t cnt = (S - s0 < SMALL_MAXSEG) ? S - s0 : SMALL_MAXSEG;
             for (int32_t i = 0; i < cnt; ++i) {
                 sl.seg[i].x = dense[s0 + i];
-                sl.seg[i].out_off = out_offset[s0 + i];
+                sl.seg[i].out_off = out_offset[s0 + i] + (out.wire ? static_cast<int64_t>(sizeof(adatopk_wire_header)) : 0);
                 sl.seg[i].n = static_cast<int32_t>(n[s0 + i]);
                 sl.seg[i].k = static_cast<int32_t>(k[s0 + i]);
             }
@@ -1768,7 +1741,7 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
             SegDesc &d = a.seg[i];
             const int32_t s = s0 + i;
             d.x = dense[s];
-            d.out_off = out_offset[s];
+            d.out_off = out_offset[s] + (out.wire ? static_cast<int64_t>(sizeof(adatopk_wire_header)) : 0);
             d.l_base = l_base;
             d.n = static_cast<int32_t>(n[s]);
             d.k = static_cast<int32_t>(k[s]);
@@ -1819,8 +1792,7 @@ inline size_t merge_span_bytes(size_t bytes) {
 // ---- decompress, for either index width
 adatopk_status check_pairs(const void *idx, int ib, const void *val, int64_t k, adatopk_dtype dt, const void *dense,
                            int64_t n) {
-    if (!dtype_ok(dt) || n < 0 || k < 0 || n >= (static_cast<int64_t>(1) << 31) || k >= (static_cast<int64_t>(1) << 31))
-        return ADATOPK_EINVAL;
+    if (!dtype_ok(dt) || n < 0 || k < 0 || k > n || n >= (static_cast<int64_t>(1) << 31)) return ADATOPK_EINVAL;
     const int es = elem_size(dt);
     if (n > 0 && (!dense || reinterpret_cast<uintptr_t>(dense) % es)) return ADATOPK_EINVAL;
     if (k > 0 && (!idx || !val || reinterpret_cast<uintptr_t>(idx) % ib || reinterpret_cast<uintptr_t>(val) % es))
@@ -1966,9 +1938,6 @@ adatopk_status decompress_segmented_impl(const int32_t *idx, const void *val, co
 }
 
 // ---- wire message: header | indices, padded to 16 bytes | values
-inline size_t wire_val_offset(int64_t k, int index_bytes) {
-    return sizeof(adatopk_wire_header) + align_up(static_cast<size_t>(k) * index_bytes, 16);
-}
 struct WireWords {
     uint32_t w[sizeof(adatopk_wire_header) / 4];
 };
@@ -2018,12 +1987,8 @@ adatopk_status compress_wire_impl(const void *const *dense, const int64_t *n, co
         end_prev = msg_off[s] + static_cast<int64_t>(bytes);
     }
     if (static_cast<uint64_t>(end_prev) > wire_capacity) return ADATOPK_EINVAL;
-    int64_t *idx_off = static_cast<int64_t *>(malloc(sizeof(int64_t) * static_cast<size_t>(S)));
-    if (!idx_off) return ADATOPK_ERUNTIME;
-    for (int32_t s = 0; s < S; ++s) idx_off[s] = msg_off[s] + static_cast<int64_t>(sizeof(adatopk_wire_header));
-    const OutSpec out{wire_out, index_bytes, nullptr, idx_off, true};
-    adatopk_status rc = compress_impl(dense, n, k, S, dt, out, nullptr, workspace, workspace_bytes, st);
-    free(idx_off);
+    const OutSpec out{wire_out, index_bytes, nullptr, msg_off, true};
+    const adatopk_status rc = compress_impl(dense, n, k, S, dt, out, nullptr, workspace, workspace_bytes, st);
     if (rc != ADATOPK_OK) return rc;
     // the error norms are in the workspace now (stream order): write the headers around them
     int64_t n_total = 0;
@@ -2112,41 +2077,7 @@ adatopk_status adatopk_decompress_segmented(const int32_t *idx, const void *val,
     return decompress_segmented_impl(idx, val, out_offset, S, dt, dense_out, n, static_cast<hipStream_t>(hip_stream));
 }
 
-// ---- wire format
-size_t adatopk_wire_bytes(int64_t k, adatopk_dtype dt, int32_t index_bytes) {
-    if (k < 0 || k >= (static_cast<int64_t>(1) << 31) || !dtype_ok(dt) || (index_bytes != 4 && index_bytes != 8)) return 0;
-    return wire_val_offset(k, index_bytes) + static_cast<size_t>(k) * elem_size(dt);
-}
-
-int64_t adatopk_wire_keep_count(size_t wire_bytes, adatopk_dtype dt, int32_t index_bytes) {
-    if (!dtype_ok(dt) || (index_bytes != 4 && index_bytes != 8) || wire_bytes < sizeof(adatopk_wire_header)) return -1;
-    // bytes(k) grows by index_bytes + element size per pair plus padding of at most 15: start from
-    // the estimate without padding and walk down to the k whose size matches
-    const size_t per = static_cast<size_t>(index_bytes) + elem_size(dt);
-    int64_t k = static_cast<int64_t>((wire_bytes - sizeof(adatopk_wire_header)) / per);
-    if (k >= (static_cast<int64_t>(1) << 31)) return -1;
-    for (int step = 0; step < 16 && k >= 0; ++step, --k)
-        if (adatopk_wire_bytes(k, dt, index_bytes) == wire_bytes) return k;
-    return -1;
-}
-
-adatopk_status adatopk_wire_parse_header(const void *host_bytes, size_t wire_bytes, adatopk_wire_header *out) {
-    if (!host_bytes || !out || wire_bytes < sizeof(adatopk_wire_header)) return ADATOPK_EINVAL;
-    adatopk_wire_header h;
-    memcpy(&h, host_bytes, sizeof h);
-    if (h.magic != ADATOPK_WIRE_MAGIC || h.version != ADATOPK_WIRE_VERSION || h.algorithm != ADATOPK_WIRE_TOPK)
-        return ADATOPK_EINVAL;
-    const adatopk_dtype dt = static_cast<adatopk_dtype>(h.dtype);
-    if (!dtype_ok(dt) || (h.index_bytes != 4 && h.index_bytes != 8)) return ADATOPK_EINVAL;
-    if (h.n < 0 || h.n >= (static_cast<int64_t>(1) << 31) || h.k < 0 || h.k > h.n) return ADATOPK_EINVAL;
-    if (h.idx_offset != static_cast<int64_t>(sizeof(adatopk_wire_header)) ||
-        h.val_offset != static_cast<int64_t>(wire_val_offset(h.k, h.index_bytes)) ||
-        adatopk_wire_bytes(h.k, dt, h.index_bytes) != wire_bytes)
-        return ADATOPK_EINVAL;
-    *out = h;
-    return ADATOPK_OK;
-}
-
+// ---- wire format (the host-only helpers are in adatopk_host.cpp)
 adatopk_status adatopk_compress_wire(const void *dense, int64_t n, adatopk_dtype dt, int64_t k, int32_t index_bytes,
                                      double ratio, void *wire_out, size_t wire_capacity, void *workspace,
                                      size_t workspace_bytes, void *hip_stream) {
@@ -2176,6 +2107,7 @@ adatopk_status adatopk_decompress_wire(const void *wire, size_t wire_bytes, adat
     return decompress_sorted_impl(idx, index_bytes, val, k, dt, dense, n, st);
 }
 
+#ifdef ADATOPK_MEASURE_BUILD
 // ---- measurement hooks
 adatopk_status adatopk_measure_enable(int32_t on) {
     if (on && !g_events_made) {
@@ -2228,5 +2160,6 @@ adatopk_status adatopk_measure_fill(void *dst, size_t bytes, void *hip_stream) {
     if (!dst || bytes % 16 || reinterpret_cast<uintptr_t>(dst) % 16) return ADATOPK_EINVAL;
     return fill_impl(dst, bytes, static_cast<hipStream_t>(hip_stream));
 }
+#endif  // ADATOPK_MEASURE_BUILD
 
 }  // extern "C"

@@ -1,9 +1,17 @@
-// Host-only helpers of libadatopk: the bandwidth-adaptive ratio rule of the paper's
-// Sec. 5.2 (Eq. "adacompress") and the ratio -> element-count conversion.
+// Host-only entry points of libadatopk (no device is touched, nothing here needs hipcc): the
+// bandwidth-adaptive ratio rule of the paper's Sec. 5.2 (Eq. "adacompress"), the ratio ->
+// element-count conversion, the link and pipeline time estimates that feed the rule (Sec. 3.5,
+// 3.6), and the size arithmetic and header check of the wire message.
 #include <cmath>
 #include <cstdint>
+#include <cstring>
 
 #include "adatopk.h"
+#include "wire_layout.h"
+
+using adatopk_internal::dtype_ok;
+using adatopk_internal::elem_size;
+using adatopk_internal::wire_val_offset;
 
 extern "C" {
 
@@ -30,7 +38,7 @@ int64_t adatopk_k_for_ratio(int64_t n, double r_i) {
 }
 
 namespace {
-bool times_ok(const double *C, const double *R, int32_t m) {
+static bool times_ok(const double *C, const double *R, int32_t m) {
     if (!C || !R || m <= 0) return false;
     for (int32_t p = 0; p < m; ++p)
         if (!(C[p] >= 0.0) || !(R[p] >= 0.0) || std::isinf(C[p]) || std::isinf(R[p])) return false;
@@ -92,6 +100,41 @@ adatopk_status adatopk_plan_keep_counts(const double *alpha, const double *beta,
         if (r_out) r_out[s] = r_s;
         k_out[s] = adatopk_k_for_ratio(n[s], r_s);
     }
+    return ADATOPK_OK;
+}
+
+// ---- wire message
+size_t adatopk_wire_bytes(int64_t k, adatopk_dtype dt, int32_t index_bytes) {
+    if (k < 0 || k >= (static_cast<int64_t>(1) << 31) || !dtype_ok(dt) || (index_bytes != 4 && index_bytes != 8)) return 0;
+    return wire_val_offset(k, index_bytes) + static_cast<size_t>(k) * elem_size(dt);
+}
+
+int64_t adatopk_wire_keep_count(size_t wire_bytes, adatopk_dtype dt, int32_t index_bytes) {
+    if (!dtype_ok(dt) || (index_bytes != 4 && index_bytes != 8) || wire_bytes < sizeof(adatopk_wire_header)) return -1;
+    // bytes(k) grows by index_bytes + element size per pair plus padding of at most 15: start from
+    // the estimate without padding and walk down to the k whose size matches
+    const size_t per = static_cast<size_t>(index_bytes) + elem_size(dt);
+    int64_t k = static_cast<int64_t>((wire_bytes - sizeof(adatopk_wire_header)) / per);
+    if (k >= (static_cast<int64_t>(1) << 31)) return -1;
+    for (int step = 0; step < 16 && k >= 0; ++step, --k)
+        if (adatopk_wire_bytes(k, dt, index_bytes) == wire_bytes) return k;
+    return -1;
+}
+
+adatopk_status adatopk_wire_parse_header(const void *host_bytes, size_t wire_bytes, adatopk_wire_header *out) {
+    if (!host_bytes || !out || wire_bytes < sizeof(adatopk_wire_header)) return ADATOPK_EINVAL;
+    adatopk_wire_header h;
+    std::memcpy(&h, host_bytes, sizeof h);
+    if (h.magic != ADATOPK_WIRE_MAGIC || h.version != ADATOPK_WIRE_VERSION || h.algorithm != ADATOPK_WIRE_TOPK)
+        return ADATOPK_EINVAL;
+    const adatopk_dtype dt = static_cast<adatopk_dtype>(h.dtype);
+    if (!dtype_ok(dt) || (h.index_bytes != 4 && h.index_bytes != 8)) return ADATOPK_EINVAL;
+    if (h.n < 0 || h.n >= (static_cast<int64_t>(1) << 31) || h.k < 0 || h.k > h.n) return ADATOPK_EINVAL;
+    if (h.idx_offset != static_cast<int64_t>(sizeof(adatopk_wire_header)) ||
+        h.val_offset != static_cast<int64_t>(wire_val_offset(h.k, h.index_bytes)) ||
+        adatopk_wire_bytes(h.k, dt, h.index_bytes) != wire_bytes)
+        return ADATOPK_EINVAL;
+    *out = h;
     return ADATOPK_OK;
 }
 

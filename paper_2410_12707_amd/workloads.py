@@ -81,6 +81,14 @@ class Workload:
     tensors: List[np.ndarray] = field(default_factory=list)
     ks: List[int] = field(default_factory=list)
     note: str = ""
+    # For workloads whose keep counts are to be PLANNED from link parameters (ks is then empty):
+    # latency in seconds and inverse bandwidth in seconds per byte of the link each tensor crosses,
+    # the user's ratio r and the coefficient of Eq. "adacompress".  Inputs only: the rule itself is
+    # applied by whoever consumes the workload (the library on one side, the oracle on the other).
+    alpha: List[float] = field(default_factory=list)
+    beta: List[float] = field(default_factory=list)
+    r_user: float = 0.0
+    coeff: float = 0.0
 
     @property
     def n_total(self) -> int:
@@ -122,6 +130,26 @@ def config4(num_segments: int = 24, seg_shape=(8, 1024, 1024)) -> Workload:
     tensors = [normal_f32(n, BASE_SEED + 4 + 100 * s) for s in range(num_segments)]
     return Workload("cfg4_gpt2m_hidden_%dx8x1024x1024_f32_adaptive" % num_segments, "f32", seg_shape,
                     tensors, ks, "GPT-2-medium hidden activations, per-link adaptive ratios")
+
+
+def config4_links(num_segments: int = 24, seg_shape=(8, 1024, 1024)) -> Workload:
+    """The tensors of config 4, each crossing a link of its own; the keep counts are left to the
+    bandwidth-adaptive rule.  Link bandwidths span the range of the paper's testbeds (8 Mbps to
+    10 Gbps, abstract and Sec. 7): the two ends are present and the rest is log-uniform between them;
+    latencies are log-uniform in 0.1 ms to 50 ms, the slower links tending to the longer ones as for
+    links between distant sites.  r = 100 and coefficient 3 as in the paper's experiments."""
+    w = config4(num_segments, seg_shape)
+    rng = _rng(BASE_SEED + 40)
+    lo, hi = 8e6 / 8.0, 10e9 / 8.0  # bytes per second
+    bw = np.exp(rng.uniform(np.log(lo), np.log(hi), size=num_segments))
+    bw[0], bw[-1] = lo, hi
+    order = rng.permutation(num_segments)
+    bw = bw[order]
+    lat = np.exp(rng.uniform(np.log(1e-4), np.log(5e-2), size=num_segments))
+    lat = np.sort(lat)[np.argsort(np.argsort(-bw))]  # longest latency on the lowest bandwidth
+    return Workload("cfg4r_gpt2m_hidden_%dx8x1024x1024_f32_planned" % num_segments, "f32", seg_shape, w.tensors, [],
+                    "GPT-2-medium hidden activations, keep counts planned from 8 Mbps - 10 Gbps links",
+                    alpha=[float(v) for v in lat], beta=[float(1.0 / v) for v in bw], r_user=100.0, coeff=3.0)
 
 
 def config5() -> Workload:

@@ -19,20 +19,30 @@ def lib():
     return binding.load_library()
 
 
-def declared_functions():
-    names = []
-    for h in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))):
-        src = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
-        names += re.findall(r"\b(adatopk_[a-z0-9_]+)\s*\(", src)
-    return sorted(set(names))
+def declared_functions(header):
+    src = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", header)).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(adatopk_[a-z0-9_]+)\s*\(", src)))
 
 
 def test_every_declared_symbol_is_exported(lib):
-    names = declared_functions()
+    from paper_2410_12707_amd import binding
+
+    assert sorted(os.path.basename(h) for h in glob.glob(os.path.join(ROOT, "include", "*.h"))) == \
+        ["adatopk.h", "adatopk_measure.h"]
+    names = declared_functions("adatopk.h")
     assert {"adatopk_compress", "adatopk_decompress", "adatopk_compress_segmented", "adatopk_workspace_bytes",
             "adatopk_adaptive_ratios", "adatopk_k_for_ratio"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
+    # the benchmark's hooks live in the measuring build only; that build exports the whole ABI as well
+    hooks = declared_functions("adatopk_measure.h")
+    mlib = binding.load_measure_library()
+    assert len(hooks) >= 7
+    for name in hooks:
+        assert hasattr(mlib, name), name
+        assert not hasattr(lib, name), "the product library must not carry %s" % name
+    for name in names:
+        assert hasattr(mlib, name), name
 
 
 def test_workspace_bytes(lib):
@@ -93,7 +103,8 @@ def test_decompress_rejects_bad_arguments(lib):
     assert d(None, fake, 10, 0, fake, 100, None) == EINVAL
     assert d(fake, fake, 10, 0, None, 100, None) == EINVAL
     assert d(fake + 2, fake, 10, 0, fake, 100, None) == EINVAL
-    assert d(fake, fake, 10, 0, fake, 0, None) == 0  # n == 0: nothing to write
+    assert d(fake, fake, 10, 0, fake, 0, None) == EINVAL  # more pairs than elements
+    assert d(fake, fake, 0, 0, fake, 0, None) == 0  # n == 0: nothing to write
 
 
 def test_adaptive_ratio_rule(lib):
@@ -245,11 +256,51 @@ def test_headers_compile_as_c_and_host_entry_points_answer_from_a_c_program(tmp_
     from paper_2410_12707_amd import binding as B
 
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    exe = str(tmp_path / "abi_host_check")
     libdir = os.path.dirname(B.LIB_PATH)
-    cmd = ["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(root, "include"),
-           os.path.join(root, "tests", "c", "abi_host_check.c"), "-o", exe, "-L", libdir, "-ladatopk", "-lm",
-           "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"]
-    subprocess.run(cmd, check=True)
-    r = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=120)
-    assert r.returncode == 0 and "ok" in r.stdout, (r.returncode, r.stdout, r.stderr)
+    for libname, extra in (("adatopk", []), ("adatopk_measure", ["-DWITH_MEASURE"])):
+        exe = str(tmp_path / ("abi_host_check_" + libname))
+        cmd = ["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(root, "include")] + extra + [
+            os.path.join(root, "tests", "c", "abi_host_check.c"), "-o", exe, "-L", libdir, "-l" + libname, "-lm",
+            "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"]
+        subprocess.run(cmd, check=True)
+        r = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=120)
+        assert r.returncode == 0 and "ok" in r.stdout, (libname, r.returncode, r.stdout, r.stderr)
+
+
+def test_decompress_rejects_more_pairs_than_elements(lib):
+    EINVAL = 1
+    fake = 0x1000
+    for f in (lib.adatopk_decompress, lib.adatopk_decompress_sorted, lib.adatopk_decompress_accumulate):
+        assert f(fake, fake, 11, 0, fake, 10, None) == EINVAL
+        assert f(fake, fake, -1, 0, fake, 10, None) == EINVAL
+
+
+def test_binding_refuses_output_buffers_of_the_wrong_type_or_size():
+    # the library sees raw pointers only: the Python layer checks what it can see (CPU tensors stand in
+    # for device tensors here: the size and type checks come first)
+    import torch
+
+    from paper_2410_12707_amd import binding as B
+
+    x = torch.zeros(100)
+    ws = torch.zeros(1 << 20, dtype=torch.uint8)
+    ok_i, ok_v, ok_e = torch.zeros(10, dtype=torch.int32), torch.zeros(10), torch.zeros(1)
+    with pytest.raises(ValueError, match="idx_out"):
+        B.adatopk_compress(x, 10, torch.zeros(10, dtype=torch.int64), ok_v, ok_e, ws)
+    with pytest.raises(ValueError, match="idx_out"):
+        B.adatopk_compress(x, 10, torch.zeros(9, dtype=torch.int32), ok_v, ok_e, ws)
+    with pytest.raises(ValueError, match="val_out"):
+        B.adatopk_compress(x, 10, ok_i, torch.zeros(10, dtype=torch.bfloat16), ok_e, ws)
+    with pytest.raises(ValueError, match="val_out"):
+        B.adatopk_compress(x, 10, ok_i, torch.zeros(9), ok_e, ws)
+    with pytest.raises(ValueError, match="err_norm_out"):
+        B.adatopk_compress(x, 10, ok_i, ok_v, torch.zeros(1, dtype=torch.float64), ws)
+    with pytest.raises(ValueError, match="one dtype"):
+        B.adatopk_compress_segmented([x, x.to(torch.bfloat16)], [5, 5], ok_i, ok_v, [0, 5, 10], None, ws)
+    with pytest.raises(ValueError, match="err_norm_out"):
+        B.adatopk_compress_segmented([x, x], [5, 5], ok_i, ok_v, [0, 5, 10], ok_e, ws)
+    with pytest.raises(ValueError, match="idx must be"):
+        B.adatopk_decompress(torch.zeros(9, dtype=torch.int32), ok_v, 10, x)
+    with pytest.raises(ValueError, match="val must"):
+        B.adatopk_decompress_sorted(ok_i, torch.zeros(10, dtype=torch.float16), 10, x)
+

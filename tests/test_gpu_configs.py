@@ -80,3 +80,68 @@ def test_config5_shape_in_fp16():
     n = 16 * 1024 * 1600
     x = wl.normal_f16(n, wl.BASE_SEED + 5)
     full_check(x, wl.keep_count(n, 5, 1000))
+
+
+def test_config4_keep_counts_planned_from_links():
+    # The bandwidth-adaptive rule end to end: link parameters (Sec. 3.5, alpha-beta model) -> one ratio per
+    # link (Sec. 5.2, Eq. "adacompress") -> one keep count per tensor -> segmented compress, plain and as
+    # wire messages that carry the ratio -> segmented decompress.  The library plans its own k array; the
+    # reference is the oracle run with the oracle's own plan.  Fast links get ratio 1 (k = n, the
+    # identity), the slowest link gets 3 r.
+    import struct
+
+    import torch
+
+    import gpu_harness as H
+    from oracle import wire_format as wf
+    from paper_2410_12707_amd import binding as B
+
+    w = wl.config4_links()
+    S = len(w.tensors)
+    ns = [t.size for t in w.tensors]
+    ratios, ks = B.adatopk_plan_keep_counts(w.alpha, w.beta, ns, B.F32, w.r_user, w.coeff)
+    R = [orc.link_time(a, b, 4.0 * n) for a, b, n in zip(w.alpha, w.beta, ns)]
+    ref_ratios = orc.adaptive_ratios(R, w.r_user, w.coeff)
+    ref_ks = [orc.k_for_ratio(n, r) for n, r in zip(ns, ref_ratios)]
+    assert ks == ref_ks and np.allclose(ratios, ref_ratios, rtol=1e-12, atol=0)
+    slowest = int(np.argmax(R))
+    assert ks[slowest] == int(ns[slowest] // (w.coeff * w.r_user)) and ratios[slowest] == w.coeff * w.r_user
+    identity = [s for s in range(S) if ks[s] == ns[s]]
+    assert identity and all(ratios[s] == 1.0 for s in identity) and len(identity) < S
+    print("planned k per tensor:", ks)
+
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        refs = list(ex.map(lambda a: orc.compress(a[0], a[1]), zip(w.tensors, ref_ks)))
+
+    # plain outputs
+    gi, gv, off, ge = H.gpu_compress_segmented(w.tensors, ks)
+    for s, (ri, rv, re) in enumerate(refs):
+        assert np.array_equal(gi[off[s]:off[s + 1]], ri), s
+        assert np.array_equal(H.bits(gv[off[s]:off[s + 1]]), H.bits(rv)), s
+        assert H.same_err(ge[s], re, ERR_RTOL), (s, ge[s], re)
+    for s in identity:  # ratio 1: nothing is lost
+        assert ge[s] == 0.0 and np.array_equal(gi[off[s]:off[s + 1]], np.arange(ns[s], dtype=np.int32))
+    ys = H.gpu_decompress_segmented(gi, gv, off, ns)
+    for s, (ri, rv, re) in enumerate(refs):
+        assert np.array_equal(H.bits(ys[s]), H.bits(orc.decompress(ri, rv, ns[s]))), s
+    del ys, gi, gv
+
+    # one wire message per link, the link's ratio in its header
+    offs, pos = [], 0
+    for k in ks:
+        offs.append(pos)
+        pos += (wf.message_bytes(k, np.float32, 4) + 15) // 16 * 16
+    buf = torch.full((pos + 64,), 0xAB, dtype=torch.uint8, device="cuda")
+    ds = [H.to_device(x) for x in w.tensors]
+    ws = B.new_workspace(sum(ns), S, torch.float32)
+    B.adatopk_compress_wire_segmented(ds, ks, 4, ratios, buf[:pos], offs, ws)
+    torch.cuda.synchronize()
+    raw = buf.cpu().numpy().tobytes()
+    assert raw[pos:] == b"\xAB" * 64
+    for s, (ri, rv, re) in enumerate(refs):
+        ref = wf.pack(ri, rv, ns[s], float(re), float(ref_ratios[s]), 4)
+        got = raw[offs[s]:offs[s] + len(ref)]
+        assert got[:12] == ref[:12] and got[16:] == ref[16:], s
+        assert H.same_err(struct.unpack("<f", got[12:16])[0], re, ERR_RTOL), s
+        hdr, _, _ = wf.unpack(got)
+        assert hdr["ratio"] == ref_ratios[s] and hdr["k"] == ref_ks[s]
