@@ -31,7 +31,8 @@
  *     must be ordered by the stream.
  *   - errors are returned as adatopk_status; nothing is enqueued when the status is
  *     ADATOPK_EINVAL or ADATOPK_EWORKSPACE.
- *   - the library keeps no state between calls: calls from several host threads are fine as long
+ *   - the library keeps no state between calls (adatopk_compress_noalloc's device array aside):
+ *     calls from several host threads are fine as long
  *     as calls that share a workspace or an output are ordered by their stream.  Every call can be
  *     captured into a HIP graph (kernel launches only; no memset or copy nodes).
  */
@@ -73,6 +74,22 @@ size_t adatopk_workspace_bytes(int64_t n_total, int32_t num_segments, adatopk_dt
 adatopk_status adatopk_compress(const void *dense, int64_t n, adatopk_dtype dt, int64_t k,
                                 int32_t *idx_out, void *val_out, float *err_norm_out,
                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* adatopk_compress for callers that cannot allocate device memory or carry a workspace around: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * result and errors as adatopk_compress, without the workspace: the scratch is an array of
+ * ADATOPK_NOALLOC_MAX_WORKSPACE bytes (64 MiB) that lives in the library's device image, on every GPU
+ * the library is loaded on, until the process ends.  The call allocates and frees nothing (its first
+ * call on a device looks up the array's address there, once).
+ *   ADATOPK_EWORKSPACE  adatopk_workspace_bytes(n, 1, dt) is larger than ADATOPK_NOALLOC_MAX_WORKSPACE
+ *                       (nothing is enqueued)
+ * All calls on one GPU share that GPU's array: calls that may overlap on one GPU (different streams
+ * without an ordering between them, several host threads) race on it and must be ordered by the
+ * caller; calls on one stream are ordered by the stream. */
+#define ADATOPK_NOALLOC_MAX_WORKSPACE ((size_t)64 << 20)
+adatopk_status adatopk_compress_noalloc(const void *dense, int64_t n, adatopk_dtype dt, int64_t k,
+                                        int32_t *idx_out, void *val_out, float *err_norm_out,
+                                        void *hip_stream);
 
 /* Decompression (Sec. 5.1): dense_out = +0.0 everywhere, then dense_out[idx[j]] = val[j].
  *   idx, val   device, k entries; indices unique; any order (ascending is fastest)

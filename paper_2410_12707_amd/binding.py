@@ -133,6 +133,8 @@ def _declare(lib: ctypes.CDLL) -> ctypes.CDLL:
     lib.adatopk_pipeline_time_compressed.restype = dbl
     lib.adatopk_plan_keep_counts.argtypes = [p, p, p, i32, i32, dbl, dbl, p, p]
     lib.adatopk_plan_keep_counts.restype = i32
+    lib.adatopk_compress_noalloc.argtypes = [p, i64, i32, i64, p, p, p, p]
+    lib.adatopk_compress_noalloc.restype = i32
     return lib
 
 
@@ -210,6 +212,16 @@ def adatopk_compress(dense: torch.Tensor, k: int, idx_out: torch.Tensor, val_out
     _check(lib.adatopk_compress(_dev(dense), dense.numel(), _dtype_code(dense.dtype), int(k), _dev(idx_out),
                                 _dev(val_out), err_ptr, _dev(workspace), workspace.numel(), _stream()),
            "adatopk_compress")
+
+
+def adatopk_compress_noalloc(dense: torch.Tensor, k: int, idx_out: torch.Tensor, val_out: torch.Tensor,
+                             err_norm_out: Optional[torch.Tensor]) -> None:
+    """adatopk_compress on the library's own resident scratch (no workspace argument, nothing allocated)."""
+    lib = load_library()
+    _check_outputs(dense.dtype, int(k), idx_out, val_out, err_norm_out, 1)
+    err_ptr = _dev(err_norm_out) if err_norm_out is not None else None
+    _check(lib.adatopk_compress_noalloc(_dev(dense), dense.numel(), _dtype_code(dense.dtype), int(k), _dev(idx_out),
+                                        _dev(val_out), err_ptr, _stream()), "adatopk_compress_noalloc")
 
 
 def adatopk_decompress(idx: torch.Tensor, val: torch.Tensor, k: int, dense_out: torch.Tensor) -> None:

@@ -51,11 +51,20 @@
 #include <stddef.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "adatopk.h"
 #include "wire_layout.h"
 #ifdef ADATOPK_MEASURE_BUILD
 #include "adatopk_measure.h"
 #endif
+
+// Scratch of adatopk_compress_noalloc: the workspace of a compress call, resident in every GPU the
+// library is loaded on for the life of the process.  In host code this name is a stand-in, not a
+// device address: the address is asked for once per device (scratch_of_current_device) and only
+// that pointer is handed to kernels.
+#define ADATOPK_NOALLOC_SCRATCH_BYTES (static_cast<size_t>(64) << 20)
+static __device__ __align__(256) unsigned char scratch[ADATOPK_NOALLOC_SCRATCH_BYTES];
 
 namespace {
 
@@ -2025,6 +2034,22 @@ adatopk_status compress_wire_impl(const void *const *dense, const int64_t *n, co
     return ADATOPK_OK;
 }
 
+// Device address of `scratch` on the current device: every GPU holds its own copy of the array at
+// its own address, looked up on the first call made with that device current and kept.
+constexpr int MAX_DEVICES = 64;
+std::atomic<void *> g_scratch_ptr[MAX_DEVICES];
+adatopk_status scratch_of_current_device(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return ADATOPK_ERUNTIME;
+    void *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return ADATOPK_ERUNTIME;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // two threads racing here store the same address
+    }
+    *out = ptr;
+    return ADATOPK_OK;
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ C ABI
@@ -2044,6 +2069,22 @@ adatopk_status adatopk_compress(const void *dense, int64_t n, adatopk_dtype dt, 
     const int64_t off[2] = {0, k};
     const OutSpec out{idx_out, 4, val_out, off, false};
     return compress_impl(ptrs, &n, &k, 1, dt, out, err_norm_out, workspace, workspace_bytes,
+                         static_cast<hipStream_t>(hip_stream));
+}
+
+adatopk_status adatopk_compress_noalloc(const void *dense, int64_t n, adatopk_dtype dt, int64_t k, int32_t *idx_out,
+                                        void *val_out, float *err_norm_out, void *hip_stream) {
+    if (!dtype_ok(dt) || n < 0 || n >= (static_cast<int64_t>(1) << 31)) return ADATOPK_EINVAL;
+    if (adatopk_workspace_bytes(n, 1, dt) > ADATOPK_NOALLOC_SCRATCH_BYTES) return ADATOPK_EWORKSPACE;
+    void *ptr = nullptr;
+    const adatopk_status rc = scratch_of_current_device(&ptr);
+    if (rc != ADATOPK_OK) return rc;
+    // Every kernel of the call clears what it accumulates into before using it, so what the previous
+    // call left in the array does not matter.
+    const void *ptrs[1] = {dense};
+    const int64_t off[2] = {0, k};
+    const OutSpec out{idx_out, 4, val_out, off, false};
+    return compress_impl(ptrs, &n, &k, 1, dt, out, err_norm_out, ptr, ADATOPK_NOALLOC_SCRATCH_BYTES,
                          static_cast<hipStream_t>(hip_stream));
 }
 

@@ -30,6 +30,10 @@ int main(void) {
 #ifdef WITH_MEASURE
     if (adatopk_measure_stage_count() < 5 || adatopk_measure_stage_name(0) == NULL) return 11;
 #endif
+    /* the call without a workspace refuses a tensor whose scratch would not fit its resident array,
+     * and bad arguments, before any device is touched */
+    if (adatopk_compress_noalloc(raw, (int64_t)1 << 30, ADATOPK_F32, 1, NULL, NULL, NULL, NULL) != ADATOPK_EWORKSPACE) return 12;
+    if (adatopk_compress_noalloc(raw, -1, ADATOPK_F32, 0, NULL, NULL, NULL, NULL) != ADATOPK_EINVAL) return 13;
     if (adatopk_decompress(NULL, NULL, 11, ADATOPK_F32, raw, 10, NULL) != ADATOPK_EINVAL) return 14; /* k > n */
     printf("c abi host check ok\n");
     return 0;

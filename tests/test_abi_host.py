@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(lib):
         ["adatopk.h", "adatopk_measure.h"]
     names = declared_functions("adatopk.h")
     assert {"adatopk_compress", "adatopk_decompress", "adatopk_compress_segmented", "adatopk_workspace_bytes",
-            "adatopk_adaptive_ratios", "adatopk_k_for_ratio"} <= set(names)
+            "adatopk_adaptive_ratios", "adatopk_k_for_ratio", "adatopk_compress_noalloc"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
     # the benchmark's hooks live in the measuring build only; that build exports the whole ABI as well
@@ -275,6 +275,18 @@ def test_decompress_rejects_more_pairs_than_elements(lib):
         assert f(fake, fake, -1, 0, fake, 10, None) == EINVAL
 
 
+def test_noalloc_call_validates_before_touching_the_device(lib):
+    EINVAL, EWORKSPACE = 1, 2
+    fake = 0x1000
+    c = lib.adatopk_compress_noalloc
+    limit = 64 << 20
+    assert lib.adatopk_workspace_bytes(1 << 28, 1, 0) > limit
+    assert c(fake, 1 << 28, 0, 10, fake, fake, None, None) == EWORKSPACE
+    assert c(fake, -1, 0, 0, fake, fake, None, None) == EINVAL
+    assert c(fake, 1000, 9, 10, fake, fake, None, None) == EINVAL
+    assert c(fake, 1 << 31, 0, 10, fake, fake, None, None) == EINVAL
+
+
 def test_binding_refuses_output_buffers_of_the_wrong_type_or_size():
     # the library sees raw pointers only: the Python layer checks what it can see (CPU tensors stand in
     # for device tensors here: the size and type checks come first)
@@ -303,4 +315,5 @@ def test_binding_refuses_output_buffers_of_the_wrong_type_or_size():
         B.adatopk_decompress(torch.zeros(9, dtype=torch.int32), ok_v, 10, x)
     with pytest.raises(ValueError, match="val must"):
         B.adatopk_decompress_sorted(ok_i, torch.zeros(10, dtype=torch.float16), 10, x)
-
+    with pytest.raises(ValueError, match="idx_out"):
+        B.adatopk_compress_noalloc(x, 10, torch.zeros(3, dtype=torch.int32), ok_v, None)
