@@ -22,7 +22,7 @@ OK, EINVAL, EWORKSPACE, ERUNTIME, ENOTIMPL = 0, 1, 2, 3, 4
 _STATUS = {OK: "ADATOPK_OK", EINVAL: "ADATOPK_EINVAL", EWORKSPACE: "ADATOPK_EWORKSPACE",
            ERUNTIME: "ADATOPK_ERUNTIME", ENOTIMPL: "ADATOPK_ENOTIMPL"}
 
-MEASURE_LIB_PATH = os.path.join(_HERE, "libadatopk_measure.so")
+MEASURE_LIB_PATH = os.environ.get("ADATOPK_MEASURE_LIBRARY") or os.path.join(_HERE, "libadatopk_measure.so")
 
 _lib = None          # the product library
 _measure_lib = None  # the same sources built with the benchmark's timing hooks (adatopk_measure.h)

@@ -73,72 +73,88 @@ constexpr int BLOCK = 512;            // threads per workgroup
 constexpr int NW = BLOCK / 64;        // wavefronts per workgroup
 constexpr int EPT = 16;               // input elements per thread per tile
 constexpr int TILE = BLOCK * EPT;     // input elements per workgroup per tile, both dtypes
-constexpr int LU = 4;               // list elements per thread per tile in the list kernels
-constexpr int BITS1 = 11, BITS2 = 10, BITS3 = 10;
-constexpr int NB1 = 1 << BITS1, NB2 = 1 << BITS2, NB3 = 1 << BITS3;
-constexpr int SH1 = BITS2 + BITS3;  // key >> SH1 = first digit
+constexpr int LU = 4;                 // list elements per thread per tile in the list kernels
+constexpr int BITS1 = 11;             // top digit of the key, counted by k_hist1
+constexpr int NB1 = 1 << BITS1;
+constexpr int SH1 = 31 - BITS1;       // key >> SH1 = top digit
+constexpr int NC1 = 64;               // coarse boundaries of the top digit: every (NB1 / NC1)-th suffix sum
+constexpr int FINE1 = NB1 / NC1;      // fine bins per coarse interval
+constexpr int NBW = 2048;             // bins of the key window that the scan pass counts its candidates in
+constexpr int NCW = 64;               // coarse boundaries of the window bins
+constexpr int BITS3 = 10;             // the last digit: position of a key inside its window bin
+constexpr int NB3 = 1 << BITS3;
+constexpr int BITS2 = 31 - BITS1 - BITS3;  // the one-workgroup path selects on the fixed digits BITS1 / BITS2 / BITS3
+constexpr int NB2 = 1 << BITS2;
 constexpr int SH2 = BITS3;
-constexpr int NC1 = 64;             // coarse boundaries of the top digit: every (NB1 / NC1)-th suffix sum
-constexpr int FINE1 = NB1 / NC1;    // fine bins per coarse interval
-constexpr int NC2 = 32;             // the same for the second digit
-constexpr int MAXSEG = 64;          // segments per launch (the table travels as kernel arguments)
-constexpr int CTARGET = 512;        // chunks aimed at per launch of several tensors (and the most any launch has)
-// chunks aimed at for a single tensor: one workgroup per compute unit.  Half the rows for every
-// prologue to sum (76 instead of 77.5 us per step on the 100 MB tensor); a batch of tensors with
-// unequal keep counts wants the finer split, whose workgroups even out (24 tensors: 560 vs 600 us).
+constexpr int SAMPLE_ELEMS = 32768;   // elements of a tensor that the speculative pass looks at first
+constexpr int SAMPLE_SH = 18;         // sample histogram: bin = key >> SAMPLE_SH ...
+constexpr int NSB = 1 << (31 - SAMPLE_SH);  // ... 8192 bins, 4 to the binade's eighth (2.2 % in value)
+constexpr int LIST_DIV = 4;           // a chunk's candidate list holds up to a quarter of the chunk
+constexpr int MAXSEG = 64;            // segments per launch (the table travels as kernel arguments)
+constexpr int CTARGET = 512;          // chunks of a launch of several tensors, at most (two workgroups per compute unit)
+// ... and of a single tensor: one workgroup per compute unit.  Half the rows for every prologue to
+// sum; a batch of tensors with unequal keep counts wants the finer split, whose workgroups even out.
 constexpr int CTARGET_ONE = 256;
-constexpr int LB_ELEMS = 8192;      // input elements per list block when sizing the list grid
-constexpr int LB_TOTAL = 4096;      // list blocks aimed at per launch, all segments together
+constexpr int64_t SPEC_MIN_N = 1 << 20;    // tensors below this are not worth a speculative pass
+constexpr double SPEC_MIN_EXPECTED = 32.0; // ... nor are keep counts that leave fewer than this many kept elements in the largest sample
+constexpr double SPEC_GOOD_EXPECTED = 96.0; // a smaller sample will do when it still expects this many
+constexpr double SPEC_SIGMAS = 5.0;        // width of the sample's rank bracket in standard deviations
+constexpr int64_t SPEC_MAX_KEEP_PERCENT = 21;  // beyond this the candidates (k and the bracket's margin) may not fit a quarter of a chunk
 constexpr size_t MERGE_SPANS = 1024;       // output spans aimed at by the one-kernel decompress
 constexpr int64_t MERGE_DENSE_RATIO = 32;  // k > n / 32 takes the LDS-built variant of the one-kernel decompress
 constexpr size_t MERGE_MIN_SPAN = 16384;   // bytes; smaller outputs use fewer workgroups
 constexpr size_t MERGE_MAX_SPAN = 98304;   // bytes; larger outputs use more workgroups
 static_assert(LU * NW <= 64, "per-tile wave counts must fit one wavefront scan");
-static_assert(NB1 % BLOCK == 0 && NB2 % BLOCK == 0 && NB3 % BLOCK == 0, "bins split evenly over threads");
-static_assert(BITS1 + BITS2 + BITS3 == 31, "digits cover the 31-bit key");
-static_assert(BLOCK >= 256, "k_emit scans the list blocks of a segment with one thread each");
+static_assert(NB1 % BLOCK == 0 && NBW % BLOCK == 0 && NB3 % BLOCK == 0 && NSB % BLOCK == 0, "bins split evenly over threads");
+static_assert(CTARGET <= BLOCK, "k_emit scans the chunks of a segment with one thread each");
 static_assert(BLOCK % 64 == 0, "whole wavefronts");
+static_assert(TILE % (LIST_DIV * BLOCK * LU) == 0, "a chunk's list capacity is whole list tiles");
 
-struct SegState {  // one per segment, zeroed by the segment's first k_hist1 block; 64 bytes
-    uint32_t unused0;
-    uint32_t B1, c_gt1, m;  // bucket of level 1, #keys above it, length of the candidate list
-    uint32_t B2, c_gt2;     // bucket of level 2, #keys above (B1,B2)
-    uint32_t T, q, c_gt;    // threshold key, tie quota, #keys above T
-    uint32_t pad[7];
+// The key window of a scan pass: keys below lo are dropped for sure, a key >= lo falls into window
+// bin min((key - lo) >> shw, NBW - 1).  The last bin is open-ended.
+struct SegState {  // one per segment; 64 bytes
+    uint32_t loA, shwA;   // window of the speculative pass (written by its first chunk's workgroup)
+    uint32_t loB, shwB;   // window of the exact pass (likewise)
+    uint32_t Bw, c_gtw;   // window bin that holds the k-th key, #keys in the bins above it (written by k_refine)
+    uint32_t spec_held;   // the speculative pass bracketed the k-th key (written by k_hist1, which always runs)
+    uint32_t pad[9];
 };
 static_assert(sizeof(SegState) == 64, "state record size");
 
+constexpr uint32_t FLAG_ALIGNED4 = 1u;  // tensor base is 4-byte aligned (always for fp32): dword loads allowed
+constexpr uint32_t FLAG_SPEC = 2u;      // the speculative pass runs for this tensor
 struct SegDesc {
     const void *x;       // device pointer of the tensor
     int64_t out_off;     // first output slot of this segment; in wire mode the byte offset of its index section
-    int64_t l_base;      // first candidate-list slot of this segment
     int32_t n, k;
-    int32_t chunk_begin, nchunks;
-    int32_t lb_begin, lb_count;
-    uint32_t aligned4;   // tensor base is 4-byte aligned (always for fp32): dword loads allowed
-    uint32_t pad;
+    int32_t chunk_begin, nchunks;  // its chunks are workgroups [chunk_begin, chunk_begin + nchunks) of every compress kernel
+    uint32_t flags;
+    uint32_t r_lo, r_hi; // speculative pass: ranks in the sample (counted from the largest key) that bracket the k-th key
+    uint32_t sample_batches;  // ... and the sample's size in batches of SAMPLE_BATCH dword loads per thread
 };
 
 struct Launch {
     SegDesc seg[MAXSEG];
     int32_t S;
-    int32_t E;  // elements per chunk (multiple of the tile)
+    int32_t E;      // elements per chunk (multiple of the tile)
+    uint32_t cap;   // list slots per chunk (E / LIST_DIV)
+    uint32_t idx64;
+    uint32_t wire;  // outputs are wire messages in one buffer (idx_out): values follow the padded index section
     SegState *state;
-    uint32_t *G3;                              // [MAXSEG][NB3] global histogram of the 3rd digit
-    uint32_t *rows2, *coarse2;                 // [chunks][NB2], [chunks][NC2]: the same for the 2nd digit of bucket members
-    uint32_t *coarse1;                         // [chunks][NC1] every FINE1-th entry of the chunk's rows1 row
-    uint32_t *rows1;                           // [chunks][NB1] suffix sums of the chunk histograms
-    double *chunk_err;                         // [chunks] sum of squares below the bucket
-    uint32_t *rows3;                           // [list blocks][NB3] suffix sums
-    uint32_t *ldef;                            // [list blocks] #keys above the 21-bit prefix
-    double *lerr;                              // [list blocks] squares of list entries below the 21-bit prefix
-    int32_t *L_idx;
+    uint32_t *G3;                 // [MAXSEG][NB3] global histogram of the last digit
+    uint32_t *rows1, *coarse1;    // [chunks][NB1], [chunks][NC1]: suffix sums of the chunks' top-digit histograms (k_hist1)
+    uint32_t *rowsW, *coarseW;    // [chunks][NBW], [chunks][NCW]: the same for the window bins of the candidates (k_scan)
+    uint2 *cpairA;                // [chunks] speculative pass only: #candidates, #candidates in the open-ended last bin
+    uint32_t *cnt;                // [chunks] #candidates of the chunk; more than cap: the list is incomplete
+    double *chunk_err;            // [chunks] sum of squares of the chunk's elements below the window
+    uint32_t *rows3;              // [chunks][NB3] suffix sums of the last digit inside the k-th key's window bin
+    uint32_t *ldef;               // [chunks] #candidates in the window bins above that bin
+    double *lerr;                 // [chunks] squares of the candidates in the window bins below it
+    int32_t *L_idx;               // [chunks][cap] candidate lists, one region per chunk
     void *L_val;
     void *idx_out;     // int32 entries, or int64 when idx64 is set (the paper's index width, Sec. 5.2)
     void *val_out;
     float *err_out;
-    uint32_t idx64;
-    uint32_t wire;     // outputs are wire messages in one buffer (idx_out): values follow the padded index section
 };
 static_assert(sizeof(Launch) <= 4096, "kernel arguments stay within 4 KB");
 
@@ -391,15 +407,14 @@ template <int NB> __device__ __forceinline__ void flush_bins(const uint32_t *h, 
         if (c) __hip_atomic_fetch_add(&G[b], c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
-// Segment that owns workgroup g: the last one whose first chunk (or list block) is <= g.  One
-// lane per table entry and one ballot instead of a loop of dependent scalar loads, which costs
-// about 0.1 us per segment.
+// Segment that owns workgroup g: the last one whose first chunk is <= g.  One lane per table entry
+// and one ballot instead of a loop of dependent scalar loads, which costs about 0.1 us per segment.
 static_assert(MAXSEG <= 64, "one lane per segment");
-__device__ __forceinline__ int find_segment_by(const Launch &a, int g, bool by_chunk) {
+__device__ __forceinline__ int find_segment(const Launch &a, int g) {
     if (a.S == 1) return 0;
     const int lane = threadIdx.x & 63;
     int begin = 0x7FFFFFFF;
-    if (lane < a.S) begin = by_chunk ? a.seg[lane].chunk_begin : a.seg[lane].lb_begin;
+    if (lane < a.S) begin = a.seg[lane].chunk_begin;
     const uint64_t owner_or_before = __ballot(g >= begin);  // begins never decrease and the first is 0
     return 63 - __builtin_clzll(owner_or_before | 1ull);
 }
@@ -515,6 +530,56 @@ __device__ __forceinline__ ColumnPick column_pick(const uint32_t *rows, const ui
     return r;
 }
 
+// ------------------------------------------------------------------ which scan pass counts
+// Sums of two counters over the workgroup.  sm holds 2 * NW words.
+__device__ __forceinline__ void block_sum2_u32(uint32_t &a, uint32_t &b, uint32_t *sm) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        a += __shfl_down(a, d);
+        b += __shfl_down(b, d);
+    }
+    __syncthreads();
+    if (lane == 0) {
+        sm[w] = a;
+        sm[NW + w] = b;
+    }
+    __syncthreads();
+    uint32_t sa = 0, sb = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        sa += sm[i];
+        sb += sm[NW + i];
+    }
+    a = sa;
+    b = sb;
+}
+
+// Did the speculative pass of this tensor bracket the k-th key?  Its window was a guess from a
+// sample; the guess holds when at least k keys reached the window and fewer than k of them lie in
+// its open-ended last bin.  Every workgroup of k_hist1, the kernel behind that pass, asks this for
+// itself from the per-chunk counts that the pass stored (and that nothing overwrites), and leaves
+// the answer in the tensor's state for the kernels that follow.  Every thread calls; the result is
+// the same in all of them.
+__device__ __forceinline__ bool spec_holds(const Launch &a, const SegDesc &sg, uint32_t *sm) {
+    if (!(sg.flags & FLAG_SPEC)) return false;
+    uint32_t reached = 0, open_ended = 0;
+    for (int cc = threadIdx.x; cc < sg.nchunks; cc += BLOCK) {
+        const uint2 p = a.cpairA[sg.chunk_begin + cc];
+        reached += p.x;
+        open_ended += p.y;
+    }
+    block_sum2_u32(reached, open_ended, sm);
+    const uint32_t k = static_cast<uint32_t>(sg.k);
+    return reached >= k && open_ended < k;
+}
+
+// Window bin of a key at or above the window's lowest key.
+__device__ __forceinline__ uint32_t window_bin(uint32_t key, uint32_t lo, uint32_t shw) {
+    const uint32_t b = (key - lo) >> shw;
+    return b < NBW - 1 ? b : NBW - 1;
+}
+
 // ------------------------------------------------------------------ k_hist1
 // LDS histogram of the top digit of one tile.
 template <int VEC, bool FAST>
@@ -590,21 +655,24 @@ __device__ __forceinline__ void hist1_full_tiles(const void *x, int64_t &t0, int
 template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist1(Launch a) {
     using St = Stream<VEC>;
     __shared__ uint32_t h[NB1];
-    __shared__ uint32_t sm[NW];
+    __shared__ uint32_t sm[2 * NW];
 
     const int g = blockIdx.x;
-    const int s = find_segment_by(a, g, true);
+    const int s = find_segment(a, g);
     const SegDesc &sg = a.seg[s];
     const int c = g - sg.chunk_begin;
     const int64_t beg = static_cast<int64_t>(c) * a.E;
     const int64_t end = (beg + a.E < sg.n) ? beg + a.E : sg.n;
+    const bool held = spec_holds(a, sg, sm);
+    if (c == 0 && threadIdx.x == 0) a.state[s].spec_held = held ? 1u : 0u;
+    if (held) return;  // the speculative pass bracketed the k-th key: no exact pass is needed
 
     for (int b = threadIdx.x; b < NB1; b += BLOCK) h[b] = 0;
     __syncthreads();
 
     uint32_t cur[St::SLOTS], valid[St::SLOTS];
     int64_t t0 = beg;
-    const int64_t full = sg.aligned4 ? (end - beg) / TILE : 0;
+    const int64_t full = (sg.flags & FLAG_ALIGNED4) ? (end - beg) / TILE : 0;
     // 16-byte loads when the tensor's base allows them (chunks start at multiples of the tile)
     if ((reinterpret_cast<uintptr_t>(sg.x) & 15) == 0)
         hist1_full_tiles<VEC, true>(sg.x, t0, full, h);
@@ -622,48 +690,48 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist1(Launch a) {
     uint32_t *row = a.rows1 + static_cast<size_t>(g) * NB1;
     for (int b = threadIdx.x; b < NB1; b += BLOCK) row[b] = h[b];
     if (threadIdx.x < NC1) a.coarse1[static_cast<size_t>(g) * NC1 + threadIdx.x] = h[threadIdx.x * FINE1];
-    if (c == 0) {  // first chunk of the segment: clear what the later kernels of this call accumulate into
-        uint32_t *st = reinterpret_cast<uint32_t *>(&a.state[s]);
-        if (threadIdx.x < sizeof(SegState) / 4) st[threadIdx.x] = 0;
+    if (c == 0)  // first chunk of the tensor: clear what k_refine accumulates into
         for (int b = threadIdx.x; b < NB3; b += BLOCK) a.G3[s * NB3 + b] = 0;
-    }
 }
 
-// ------------------------------------------------------------------ k_gather
-// One tile.  Common path per element: clear the sign, compare with the bucket's lowest key
-// (the compare's lane mask is the keep bitmap of the slot), add the square of a dropped
-// element in fp64.  Kept elements are rare (about k/n + the bucket's share).  After the waves
-// have exchanged their counts, every kept (index, value) pair is written to its list position
-// inside an LDS stage that holds STAGE_CAP consecutive list slots of the chunk; the stage goes
-// out to memory with full-width stores only when it would overflow and at the end of the
-// chunk, so the streaming loop itself issues loads only (loads and stores share one in-order
-// counter: a store inside the loop would make every wait for the next tile's loads drain it).
-// A tile that alone holds more than STAGE_CAP pairs (dense input, k close to n) stores directly.
+// ------------------------------------------------------------------ k_scan
+// The pass that reads the whole input and keeps the candidates: every element whose key is at least
+// the window's lowest key `lo` goes, in index order, into the candidate list of its chunk and is
+// counted in its window bin; the squares of all other elements are summed in fp64.
+//
+// One tile.  Common path per element: clear the sign, compare with lo (the compare's lane mask is
+// the keep bitmap of the slot), add the square of a dropped element in fp64.  Candidates are rare
+// (about k/n and a margin).  After the waves have exchanged their counts, every kept
+// (index, value) pair is written to its list position inside an LDS stage that holds STAGE_CAP
+// consecutive list slots of the chunk; the stage goes out to memory with full-width stores only
+// when it would overflow and at the end of the chunk, so the streaming loop itself issues loads
+// only (loads and stores share one in-order counter: a store inside the loop would make every wait
+// for the next tile's loads drain it).  A tile that alone holds more than STAGE_CAP pairs (dense
+// input, k close to n) stores directly.  List slots beyond the chunk's capacity are counted, not
+// stored: such a chunk is read from the input again by the kernels that follow.
 constexpr int STAGE_CAP = 2048;
 
-// Writes list slots [from, to) of the chunk from the stage to memory and counts the second
-// digit of the bucket members among them.  stage[0] is list slot `from`.
+// Writes list slots [from, to) of the chunk from the stage to memory and counts their window bins.
+// stage[0] is list slot `from`.
 template <int VEC>
-__device__ __forceinline__ void flush_stage(const uint2 *stage, uint32_t from, uint32_t to, uint32_t cnt,
-                                            uint32_t thr_hi, uint32_t *h2, int32_t *Li,
-                                            typename Raw<VEC>::type *Lv) {
+__device__ __forceinline__ void flush_stage(const uint2 *stage, uint32_t from, uint32_t to, uint32_t cap, uint32_t lo,
+                                            uint32_t shw, uint32_t *hw, int32_t *Li, typename Raw<VEC>::type *Lv) {
     for (uint32_t i = from + threadIdx.x; i < to; i += BLOCK) {
         const uint2 pr = stage[i - from];
-        if (i < cnt) {
+        if (i < cap) {
             Li[i] = static_cast<int32_t>(pr.x);
             Lv[i] = static_cast<typename Raw<VEC>::type>(pr.y);
         }
-        const uint32_t key = key_of<VEC>(pr.y);
-        hist_add(h2, (key >> SH2) & (NB2 - 1), key < thr_hi);
+        hist_add(hw, window_bin(key_of<VEC>(pr.y), lo, shw), true);
     }
 }
 
 template <int VEC, bool FAST>
-__device__ __forceinline__ void gather_tile(const uint32_t (&dw)[Stream<VEC>::SLOTS],
-                                            const uint32_t (&valid)[Stream<VEC>::SLOTS], int64_t t0, uint32_t thr_lo,
-                                            uint32_t thr_hi, uint32_t *h2, uint32_t *wcnt, uint2 *stage,
-                                            uint32_t &running, uint32_t &flushed, uint32_t cnt, int32_t *Li,
-                                            typename Raw<VEC>::type *Lv, double &acc) {
+__device__ __forceinline__ void scan_tile(const uint32_t (&dw)[Stream<VEC>::SLOTS],
+                                          const uint32_t (&valid)[Stream<VEC>::SLOTS], int64_t t0, uint32_t lo,
+                                          uint32_t shw, uint32_t *hw, uint32_t *wcnt, uint2 *stage, uint32_t &running,
+                                          uint32_t &flushed, uint32_t cap, int32_t *Li,
+                                          typename Raw<VEC>::type *Lv, double &acc) {
     using St = Stream<VEC>;
     using R = typename Raw<VEC>::type;
     constexpr int EPD = St::EPD, SLOTS = St::SLOTS;
@@ -677,7 +745,7 @@ __device__ __forceinline__ void gather_tile(const uint32_t (&dw)[Stream<VEC>::SL
         for (int hh = 0; hh < EPD; ++hh) {
             const uint32_t raw = elem_of<VEC>(dw[e], hh);
             const bool ok = FAST || ((valid[e] >> hh) & 1u);
-            keep[e][hh] = ok && key_of<VEC>(raw) >= thr_lo;
+            keep[e][hh] = ok && key_of<VEC>(raw) >= lo;
             m[e][hh] = __ballot(keep[e][hh]);
             wc += __popcll(m[e][hh]);
             float xs = (ok && !keep[e][hh]) ? value_of<VEC>(raw) : 0.0f;
@@ -694,7 +762,7 @@ __device__ __forceinline__ void gather_tile(const uint32_t (&dw)[Stream<VEC>::SL
     wave_counts(wcnt, before, tot);
     if (tot == 0) return;  // uniform over the workgroup
     if (running + tot - flushed > STAGE_CAP) {  // uniform: make room
-        flush_stage<VEC>(stage, flushed, running, cnt, thr_hi, h2, Li, Lv);
+        flush_stage<VEC>(stage, flushed, running, cap, lo, shw, hw, Li, Lv);
         __syncthreads();
         flushed = running;
     }
@@ -729,12 +797,11 @@ __device__ __forceinline__ void gather_tile(const uint32_t (&dw)[Stream<VEC>::SL
             for (int hh = 0; hh < EPD; ++hh) {
                 if (keep[e][hh]) {
                     const uint32_t raw = elem_of<VEC>(dw[e], hh);
-                    if (pos < cnt) {
+                    if (pos < cap) {
                         Li[pos] = static_cast<int32_t>(i_lane + e * 64 * EPD + hh);
                         Lv[pos] = static_cast<R>(raw);
                     }
-                    const uint32_t key = key_of<VEC>(raw);
-                    hist_add(h2, (key >> SH2) & (NB2 - 1), key < thr_hi);
+                    hist_add(hw, window_bin(key_of<VEC>(raw), lo, shw), true);
                     ++pos;
                 }
                 slot_base += __popcll(m[e][hh]);
@@ -745,67 +812,246 @@ __device__ __forceinline__ void gather_tile(const uint32_t (&dw)[Stream<VEC>::SL
     if (direct) flushed = running;  // nothing of this tile is staged
 }
 
-// Four wavefronts per SIMD (two workgroups of 512 threads per CU, what a batch of tensors is launched
-// with) need the kernel to stay within 128 vector registers.
-constexpr int GATHER_WAVES_PER_SIMD = BLOCK <= 512 ? 4 : 2;
-template <int VEC> __global__ __launch_bounds__(BLOCK, GATHER_WAVES_PER_SIMD) void k_gather(Launch a) {
+// The speculative pass's window, from a sample.  Every workgroup of the tensor reads the same
+// SAMPLE_ELEMS elements (runs of 64 dwords spread evenly over the tensor; after the first
+// workgroup they come from the cache), counts their keys in a histogram of NSB bins and takes from
+// it the keys at two ranks that the host derived from k: r_lo, a few standard deviations of the
+// sampling noise below where the k-th key is expected in the sample (the window's lowest key: the
+// lower edge of that rank's bin), and r_hi as far above it (the upper edge of its bin: the window's
+// bins span up to there, as finely as NBW bins and a last digit of BITS3 bits allow).  A rank
+// beyond the sample's size puts the lower end at key 0; rank 0 leaves the upper end open.  All
+// integer work on the same data: every workgroup gets the same window.
+//
+// The histogram lives in LDS with one unused word after every 32 (a thread then walks its NSB / BLOCK
+// consecutive bins without the 16-fold bank conflict of an unpadded stride).  The whole prologue is
+// bound by instruction issue (two wavefronts per SIMD), so the work per sampled element is kept to a
+// handful of instructions: one compare against a floor below which nothing needs counting, one add.
+// The bins holding the two ranks are found while the suffix sums are formed in registers.
+constexpr int NSB_PADDED = NSB + NSB / 32;
+constexpr uint32_t SAMPLE_SKEW = 128;  // runs: the sample's runs are shifted by up to this many run lengths
+constexpr int SAMPLE_BATCH = 16;  // dword loads per thread and batch; the host picks 1, 2 or 4 batches (fp32: 8192 elements each)
+__device__ __forceinline__ uint32_t padded(uint32_t bin) { return bin + (bin >> 5); }
+template <int VEC, typename Prefetch>
+__device__ __forceinline__ void sample_window(const SegDesc &sg, uint32_t *hs, uint32_t *sm, uint32_t *s_pick,
+                                              Prefetch after_loads, uint32_t &lo, uint32_t &shw) {
+    constexpr int EPD = VEC / 4;
+    constexpr int MAXB = SAMPLE_ELEMS / BLOCK / EPD / SAMPLE_BATCH;  // batches at the full sample size
+    constexpr int PER = NSB / BLOCK;                                 // bins per thread in the search
+    static_assert(MAXB == 4 || MAXB == 2, "sample batches");
+    const int lane = threadIdx.x & 63;
+    const uint32_t w = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));  // in a scalar register
+    const int nbatch = static_cast<int>(sg.sample_batches);           // uniform; 1 .. MAXB
+    // nbatch * SAMPLE_BATCH * NW runs of 64 consecutive dwords, a power of two
+    const int run_shift = __builtin_ctz(SAMPLE_BATCH * NW) + (nbatch >= 4 ? 2 : (nbatch >= 2 ? 1 : 0));
+    const uint64_t nruns = (static_cast<uint64_t>(sg.n) / EPD) / 64;  // at least as many as sampled: the host checks the size
+    const uint32_t *x = static_cast<const uint32_t *>(sg.x) + lane;
+    uint32_t v[MAXB][SAMPLE_BATCH];
+#pragma unroll
+    for (int b = 0; b < MAXB; ++b)
+        if (b < nbatch) {
+#pragma unroll
+            for (int j = 0; j < SAMPLE_BATCH; ++j) {
+                // evenly spaced, plus a small run-dependent offset: an even spacing alone can put every
+                // run on the same memory channel
+                const uint32_t r = static_cast<uint32_t>(b * SAMPLE_BATCH + j) * NW + w;
+                const uint64_t run = ((static_cast<uint64_t>(r) * (nruns - SAMPLE_SKEW)) >> run_shift) + (r * 37u) % SAMPLE_SKEW;
+                v[b][j] = x[run * 64];
+            }
+        }
+    __builtin_amdgcn_sched_barrier(0);
+    after_loads();
+    __builtin_amdgcn_sched_barrier(0);
+    for (int b = threadIdx.x; b < NSB_PADDED; b += BLOCK) hs[b] = 0;
+    if (threadIdx.x == 0) {
+        s_pick[0] = NSB;  // what stays when no bin holds the rank
+        s_pick[1] = NSB;
+    }
+    // Only the largest few per cent of the sample decide the two ranks.  Every thread's largest key
+    // is at least `floor` = the smallest of the threads' largest keys, so at least BLOCK sampled keys
+    // are >= floor: when the lower rank is within BLOCK, keys below floor need not be counted at all.
+    // Bin 0 (zeros and the smallest denormals) is never counted: a rank that falls into it is not
+    // found, which puts the window's lower end at key 0 just the same, and a tensor that is mostly
+    // zeros does not pile its lanes onto one word.
+    uint32_t mine = 0;
+#pragma unroll
+    for (int b = 0; b < MAXB; ++b)
+        if (b < nbatch) {
+#pragma unroll
+            for (int j = 0; j < SAMPLE_BATCH; ++j)
+#pragma unroll
+                for (int hh = 0; hh < EPD; ++hh) {
+                    const uint32_t key = key_of<VEC>(elem_of<VEC>(v[b][j], hh));
+                    mine = key > mine ? key : mine;
+                }
+        }
+    uint32_t floor_key = mine;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const uint32_t o = __shfl_xor(floor_key, d);
+        floor_key = o < floor_key ? o : floor_key;
+    }
+    if (lane == 0) sm[w] = floor_key;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NW; ++i) floor_key = sm[i] < floor_key ? sm[i] : floor_key;
+    if (sg.r_lo > BLOCK) floor_key = 0;
+    uint32_t floor_bin = floor_key >> SAMPLE_SH;
+    floor_bin = floor_bin < 1 ? 1 : floor_bin;
+#pragma unroll
+    for (int b = 0; b < MAXB; ++b)
+        if (b < nbatch) {
+#pragma unroll
+            for (int j = 0; j < SAMPLE_BATCH; ++j)
+#pragma unroll
+                for (int hh = 0; hh < EPD; ++hh) {
+                    const uint32_t bin = key_of<VEC>(elem_of<VEC>(v[b][j], hh)) >> SAMPLE_SH;
+                    if (bin >= floor_bin) atomicAdd(&hs[padded(bin)], 1u);
+                }
+        }
+    __syncthreads();
+    // thread t owns bins [t * PER, (t + 1) * PER); higher bins hold larger keys
+    uint32_t cnt[PER], own = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        cnt[j] = hs[padded(threadIdx.x * PER + j)];
+        own += cnt[j];
+    }
+    uint32_t total;
+    const uint32_t inc = block_incl_scan(own, sm, &total);
+    uint32_t above = total - inc;  // sampled (and counted) keys in the bins of the threads after this one
+    const uint32_t r_lo = sg.r_lo, r_hi = sg.r_hi;
+#pragma unroll
+    for (int j = PER - 1; j >= 0; --j) {
+        const uint32_t with = above + cnt[j];  // suffix sum at this bin
+        if (above < r_lo && with >= r_lo) s_pick[0] = threadIdx.x * PER + j;
+        if (r_hi != 0 && above < r_hi && with >= r_hi) s_pick[1] = threadIdx.x * PER + j;
+        above = with;
+    }
+    __syncthreads();
+    const uint32_t b_lo = s_pick[0], b_hi = s_pick[1];
+    __syncthreads();
+    lo = b_lo < NSB ? b_lo << SAMPLE_SH : 0u;
+    const uint32_t hi = b_hi < NSB ? (b_hi + 1u) << SAMPLE_SH : 0x80000000u;  // first key above the bracket
+    const uint32_t shl = VEC == TAG_F32 ? 0u : 16u;  // keys of the 16-bit types have 16 zero bits below the pattern
+    const uint64_t width = hi > lo ? hi - lo : 1u;
+    shw = shl;
+    while (shw < shl + static_cast<uint32_t>(BITS3) && (static_cast<uint64_t>(NBW - 1) << shw) < width) ++shw;
+}
+
+// DEPTH = register buffers of one tile each that the streaming loop rotates through, i.e. DEPTH - 1
+// tiles of loads in flight while one is processed.  The loop waits for memory, not for instructions
+// (one workgroup per compute unit with one tile ahead keeps 32 KB per compute unit in flight, which at
+// the latency of a load under this traffic sustains about 4.8 TB/s), so a single tensor, whose launch has
+// one workgroup per compute unit and twice the registers to spend, runs two tiles ahead.  A batch of
+// tensors is launched with two workgroups per compute unit (four wavefronts per SIMD), which needs the
+// kernel to stay within 128 vector registers: one tile ahead.
+template <int VEC, bool SPEC, int DEPTH>
+__global__ __launch_bounds__(BLOCK, DEPTH == 2 ? 4 : 2) void k_scan(Launch a) {
+    static_assert(DEPTH == 2 || DEPTH == 3, "one or two tiles ahead");
     using R = typename Raw<VEC>::type;
     using St = Stream<VEC>;
-    __shared__ uint32_t h[NB1];  // top-digit histogram during the prologue, then the second-digit one
+    // 32 KB used in turn as: the sample histogram or the bucket search's scratch (prologue), then the
+    // stage (STAGE_CAP pairs) followed by the window histogram
+    __shared__ __attribute__((aligned(16))) uint32_t smem[NSB_PADDED];
     __shared__ uint32_t wcnt[2][NW];
-    __shared__ uint2 stage[STAGE_CAP];
-    __shared__ uint32_t sm[NW];
+    __shared__ uint32_t sm[2 * NW];
     __shared__ double smd[NW];
+    __shared__ uint32_t s_pick[4];
+    static_assert(2 * STAGE_CAP + NBW <= NSB_PADDED && NC1 + 2 * FINE1 <= NSB_PADDED, "shared scratch fits");
 
     const int g = blockIdx.x;
-    const int s = find_segment_by(a, g, true);
+    const int s = find_segment(a, g);
     const SegDesc &sg = a.seg[s];
     const int c = g - sg.chunk_begin;
     const int64_t beg = static_cast<int64_t>(c) * a.E;
     const int64_t end = (beg + a.E < sg.n) ? beg + a.E : sg.n;
+    if (SPEC) {
+        if (!(sg.flags & FLAG_SPEC)) return;  // this tensor goes straight to the exact passes
+    } else {
+        if (a.state[s].spec_held) return;     // the speculative pass did the work already
+    }
 
     // The first tile does not depend on the prologue: its loads are put in flight inside it, behind
     // the prologue's first loads.
-    uint32_t cur[St::SLOTS], nxt[St::SLOTS], valid[St::SLOTS];
-    const int64_t ntiles = sg.aligned4 ? (end - beg) / TILE : 0;
+    uint32_t cur[St::SLOTS], nxt[St::SLOTS], far[St::SLOTS], valid[St::SLOTS];  // far: DEPTH 3 only
+    const int64_t ntiles = (sg.flags & FLAG_ALIGNED4) ? (end - beg) / TILE : 0;
     auto first_tile = [&]() {
         if (ntiles > 0) St::load_fast(sg.x, beg, cur);
     };
 
-    // Prologue, the same in every block of the segment: bucket B1 of the k-th key from the rows of
-    // k_hist1; the part of S[B1] that belongs to the earlier chunks is this chunk's offset in the list.
-    const ColumnPick p1 = column_pick<NB1, NC1, 16>(a.rows1 + static_cast<size_t>(sg.chunk_begin) * NB1,
-                                                a.coarse1 + static_cast<size_t>(sg.chunk_begin) * NC1, sg.nchunks, c,
-                                                static_cast<uint32_t>(sg.k), h, first_tile);
-    const uint32_t B1 = p1.B, c_gt1 = p1.above, off = p1.below, m_total = p1.total;
-    const uint32_t cnt = (B1 < NB1) ? a.rows1[static_cast<size_t>(g) * NB1 + B1] : 0u;
-    if (c == sg.nchunks - 1 && threadIdx.x == 0) {
-        a.state[s].B1 = B1;
-        a.state[s].c_gt1 = c_gt1;
-        a.state[s].m = m_total;
+    uint32_t lo, shw;
+    if (SPEC) {
+        sample_window<VEC>(sg, smem, sm, s_pick, first_tile, lo, shw);
+        if (c == 0) {  // the accumulators of the kernels that follow
+            for (int b = threadIdx.x; b < NB3; b += BLOCK) a.G3[s * NB3 + b] = 0;
+            if (threadIdx.x == 0) {
+                a.state[s].loA = lo;
+                a.state[s].shwA = shw;
+            }
+        }
+    } else {
+        // The same in every workgroup of the tensor: bucket B1 of the k-th key from the rows of k_hist1
+        // is the window, its 2^20 keys in the first 1024 bins.
+        const ColumnPick p1 = column_pick<NB1, NC1, 16>(a.rows1 + static_cast<size_t>(sg.chunk_begin) * NB1,
+                                                        a.coarse1 + static_cast<size_t>(sg.chunk_begin) * NC1, sg.nchunks,
+                                                        0, static_cast<uint32_t>(sg.k), smem, first_tile);
+        lo = p1.B << SH1;  // 2^31 when nothing is kept (k = 0): no key reaches it
+        shw = SH1 - BITS3;
+        if (c == 0 && threadIdx.x == 0) {
+            a.state[s].loB = lo;
+            a.state[s].shwB = shw;
+        }
     }
-    const int64_t lo = sg.l_base + off;
-    int32_t *Li = a.L_idx + lo;
-    R *Lv = static_cast<R *>(a.L_val) + lo;
-    const uint32_t thr_lo = B1 << SH1;         // lowest key of bucket B1 (2^31 when nothing is kept)
-    const uint32_t thr_hi = (B1 + 1u) << SH1;  // lowest key above the bucket
+    const uint32_t cap = a.cap;
+    int32_t *Li = a.L_idx + static_cast<size_t>(g) * cap;
+    R *Lv = static_cast<R *>(a.L_val) + static_cast<size_t>(g) * cap;
 
-    uint32_t *h2 = h;
-    for (int b = threadIdx.x; b < NB2; b += BLOCK) h2[b] = 0;
+    uint2 *stage = reinterpret_cast<uint2 *>(smem);
+    uint32_t *hw = smem + 2 * STAGE_CAP;
+    __syncthreads();
+    for (int b = threadIdx.x; b < NBW; b += BLOCK) hw[b] = 0;
     __syncthreads();
 
     double acc = 0.0;
     uint32_t running = 0, flushed = 0;
     int wb = 0;
-    // Full tiles, two register buffers used in turn, unconditional loads, peeled tail (see hist1_full_tiles).
+    // Full tiles, the register buffers used in turn, unconditional loads in the loop, peeled tail (see
+    // hist1_full_tiles).
     int64_t t0 = beg;
     int64_t rem = ntiles;
     auto tile = [&](const uint32_t(&dw)[St::SLOTS]) {
-        gather_tile<VEC, true>(dw, valid, t0, thr_lo, thr_hi, h2, wcnt[wb], stage, running, flushed, cnt, Li, Lv, acc);
+        scan_tile<VEC, true>(dw, valid, t0, lo, shw, hw, wcnt[wb], stage, running, flushed, cap, Li, Lv, acc);
         t0 += TILE;
         wb ^= 1;
     };
-    if (rem > 0) {
+    if (DEPTH == 3) {
+        // cur holds the tile at t0; nxt the one behind it; far the one behind that
+        if (rem >= 2) St::load_fast(sg.x, t0 + TILE, nxt);
+        while (rem >= 5) {
+            St::load_fast(sg.x, t0 + 2 * static_cast<int64_t>(TILE), far);
+            __builtin_amdgcn_sched_barrier(0);
+            tile(cur);
+            St::load_fast(sg.x, t0 + 2 * static_cast<int64_t>(TILE), cur);
+            __builtin_amdgcn_sched_barrier(0);
+            tile(nxt);
+            St::load_fast(sg.x, t0 + 2 * static_cast<int64_t>(TILE), nxt);
+            __builtin_amdgcn_sched_barrier(0);
+            tile(far);
+            rem -= 3;
+        }
+        if (rem >= 1) {  // one to four tiles left: cur is loaded, nxt is if there are two
+            if (rem >= 3) St::load_fast(sg.x, t0 + 2 * static_cast<int64_t>(TILE), far);
+            __builtin_amdgcn_sched_barrier(0);
+            tile(cur);
+            if (rem >= 2) {
+                if (rem >= 4) St::load_fast(sg.x, t0 + 2 * static_cast<int64_t>(TILE), cur);
+                __builtin_amdgcn_sched_barrier(0);
+                tile(nxt);
+                if (rem >= 3) tile(far);
+                if (rem >= 4) tile(cur);
+            }
+        }
+    } else if (rem > 0) {
         while (rem > 2) {
             St::load_fast(sg.x, t0 + TILE, nxt);
             __builtin_amdgcn_sched_barrier(0);
@@ -826,109 +1072,127 @@ template <int VEC> __global__ __launch_bounds__(BLOCK, GATHER_WAVES_PER_SIMD) vo
     }
     for (; t0 < end; t0 += TILE, wb ^= 1) {
         St::load_slow(sg.x, t0, end, cur, valid);
-        gather_tile<VEC, false>(cur, valid, t0, thr_lo, thr_hi, h2, wcnt[wb], stage, running, flushed, cnt, Li, Lv,
-                                acc);
+        scan_tile<VEC, false>(cur, valid, t0, lo, shw, hw, wcnt[wb], stage, running, flushed, cap, Li, Lv, acc);
     }
     __syncthreads();
-    flush_stage<VEC>(stage, flushed, running, cnt, thr_hi, h2, Li, Lv);
+    flush_stage<VEC>(stage, flushed, running, cap, lo, shw, hw, Li, Lv);
 
     const double bsum = block_sum_f64(acc, smd);
-    if (threadIdx.x == 0) a.chunk_err[g] = bsum;
+    if (threadIdx.x == 0) {
+        a.chunk_err[g] = bsum;
+        a.cnt[g] = running;
+    }
     __syncthreads();
-    // second-digit counts of this chunk's bucket members, as a row of suffix sums (no global atomics)
-    block_suffix_inplace<NB2>(h2, sm);
-    uint32_t *row = a.rows2 + static_cast<size_t>(g) * NB2;
-    for (int b = threadIdx.x; b < NB2; b += BLOCK) row[b] = h2[b];
-    if (threadIdx.x < NC2) a.coarse2[static_cast<size_t>(g) * NC2 + threadIdx.x] = h2[threadIdx.x * (NB2 / NC2)];
+    if (SPEC && threadIdx.x == 0) a.cpairA[g] = make_uint2(running, hw[NBW - 1]);
+    // window-bin counts of this chunk's candidates, as a row of suffix sums (no global atomics)
+    block_suffix_inplace<NBW>(hw, sm);
+    uint32_t *row = a.rowsW + static_cast<size_t>(g) * NBW;
+    for (int b = threadIdx.x; b < NBW; b += BLOCK) row[b] = hw[b];
+    if (threadIdx.x < NCW) a.coarseW[static_cast<size_t>(g) * NCW + threadIdx.x] = hw[threadIdx.x * (NBW / NCW)];
 }
 
 // ------------------------------------------------------------------ list kernels
-// Slot range of list block lb of a segment whose list holds m entries.
-// A short list does not need all list blocks of the grid: a block takes at least LB_MIN entries,
-// so only the first `nactive` blocks (at least one) have work; the others return at once and are
-// ignored by everybody.  Both list kernels derive the same split from m.
-constexpr uint32_t LB_MIN = 2048;
-__device__ __forceinline__ void list_range(uint32_t m, int lb, int lb_count, uint32_t &beg, uint32_t &end,
-                                           int &nactive) {
-    constexpr uint32_t LT = BLOCK * LU;
-    uint32_t per = (m + lb_count - 1) / lb_count;
-    per = per < LB_MIN ? LB_MIN : per;
-    per = (per + LT - 1) / LT * LT;  // whole tiles per block
-    const uint64_t b = static_cast<uint64_t>(per) * lb;
-    beg = b < m ? static_cast<uint32_t>(b) : m;
-    end = (b + per < m) ? static_cast<uint32_t>(b + per) : m;
-    const uint32_t na = (m + per - 1) / per;
-    nactive = na < 1 ? 1 : static_cast<int>(na);
+// Both work chunk by chunk on the candidates that the scan pass kept: from the chunk's list, or,
+// when the chunk had more candidates than its list holds, from the chunk's part of the input
+// itself (every element at or above the window's lowest key, in index order: the same sequence).
+template <int VEC> struct ChunkSource {
+    using R = typename Raw<VEC>::type;
+    const int32_t *Li;
+    const R *Lv;
+    const R *x;          // the chunk's first input element
+    uint32_t base;       // its index in the tensor
+    uint32_t len;        // entries: list entries, or the chunk's elements
+    uint32_t lo;
+    bool from_input;
+    // entry i: its raw pattern, and whether it is a candidate at all
+    __device__ __forceinline__ uint32_t raw(uint32_t i) const {
+        return i < len ? static_cast<uint32_t>(from_input ? x[i] : Lv[i]) : 0u;
+    }
+    __device__ __forceinline__ bool is_candidate(uint32_t i, uint32_t r) const {
+        return i < len && (!from_input || key_of<VEC>(r) >= lo);
+    }
+    __device__ __forceinline__ int32_t index(uint32_t i) const {
+        return from_input ? static_cast<int32_t>(base + i) : (i < len ? Li[i] : 0);
+    }
+};
+template <int VEC>
+__device__ __forceinline__ ChunkSource<VEC> chunk_source(const Launch &a, const SegDesc &sg, int g, uint32_t lo) {
+    using R = typename Raw<VEC>::type;
+    ChunkSource<VEC> src;
+    const int c = g - sg.chunk_begin;
+    const int64_t beg = static_cast<int64_t>(c) * a.E;
+    const int64_t end = (beg + a.E < sg.n) ? beg + a.E : sg.n;
+    const uint32_t count = a.cnt[g];
+    src.from_input = count > a.cap;
+    src.Li = a.L_idx + static_cast<size_t>(g) * a.cap;
+    src.Lv = static_cast<const R *>(a.L_val) + static_cast<size_t>(g) * a.cap;
+    src.x = static_cast<const R *>(sg.x) + beg;
+    src.base = static_cast<uint32_t>(beg);
+    src.len = src.from_input ? static_cast<uint32_t>(end - beg) : count;
+    src.lo = lo;
+    return src;
 }
 
-template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
-    using R = typename Raw<VEC>::type;
-    __shared__ uint32_t h[NB2 > NB3 ? NB2 : NB3];
-    __shared__ uint32_t sm[NW];
+// k_refine.  Prologue (every workgroup of the tensor, redundantly): the column sums of the chunks'
+// window rows give the window bin Bw that holds the k-th key.  Then, over the chunk's candidates:
+// the last digit (the position inside bin Bw) of those in Bw is counted, globally (G3) and as a row
+// of suffix sums per chunk; candidates in higher bins are counted (kept whatever the last digit
+// is), the squares of those in lower bins are summed (dropped whatever it is).
+template <int VEC> __global__ __launch_bounds__(BLOCK) void k_refine(Launch a) {
+    __shared__ uint32_t h[NB3 > NCW + 2 * (NBW / NCW) ? NB3 : NCW + 2 * (NBW / NCW)];
+    __shared__ uint32_t sm[2 * NW];
     __shared__ double smd[NW];
 
     const int g = blockIdx.x;
-    const int s = find_segment_by(a, g, false);
+    const int s = find_segment(a, g);
     const SegDesc &sg = a.seg[s];
-    const int lb = g - sg.lb_begin;
-    if (sg.nchunks == 0) return;  // empty tensor: nothing was listed, and nobody cleared its state
-    const uint32_t m = a.state[s].m;
-    uint32_t beg, end;
-    int nactive;
-    list_range(m, lb, sg.lb_count, beg, end, nactive);
-    if (lb >= nactive) return;
-    const uint32_t B1 = a.state[s].B1, c_gt1 = a.state[s].c_gt1;
+    const int c = g - sg.chunk_begin;
+    const bool spec = a.state[s].spec_held != 0;
+    const uint32_t lo = spec ? a.state[s].loA : a.state[s].loB;
+    const uint32_t shw = spec ? a.state[s].shwA : a.state[s].shwB;
+    const uint32_t shl = VEC == TAG_F32 ? 0u : 16u;
+    const ChunkSource<VEC> src = chunk_source<VEC>(a, sg, g, lo);
 
     // The first LU entries of every thread do not depend on the prologue: their loads are in flight
-    // while it runs (a typical list block has no more than these), issued behind its first loads.
-    const R *Lv = static_cast<const R *>(a.L_val) + sg.l_base;
+    // while it runs (a typical chunk has no more than these), issued behind its first loads.
     uint32_t first[LU];
     auto first_entries = [&]() {
 #pragma unroll
-        for (int j = 0; j < LU; ++j) {
-            const uint32_t i = beg + j * BLOCK + threadIdx.x;
-            first[j] = (i < end) ? static_cast<uint32_t>(Lv[i]) : 0u;
-        }
+        for (int j = 0; j < LU; ++j) first[j] = src.raw(j * BLOCK + threadIdx.x);
     };
-
-    // Prologue: bucket of the second digit among the members of bucket B1.
-    const ColumnPick p2 = column_pick<NB2, NC2>(a.rows2 + static_cast<size_t>(sg.chunk_begin) * NB2,
-                                                a.coarse2 + static_cast<size_t>(sg.chunk_begin) * NC2, sg.nchunks, 0,
-                                                static_cast<uint32_t>(sg.k) - c_gt1, h, first_entries);
-    const uint32_t B2 = p2.B, above2 = p2.above;
-    if (lb == 0 && threadIdx.x == 0) {
-        a.state[s].B2 = B2;
-        a.state[s].c_gt2 = c_gt1 + above2;
+    const ColumnPick pw = column_pick<NBW, NCW>(a.rowsW + static_cast<size_t>(sg.chunk_begin) * NBW,
+                                                a.coarseW + static_cast<size_t>(sg.chunk_begin) * NCW, sg.nchunks, 0,
+                                                static_cast<uint32_t>(sg.k), h, first_entries);
+    const uint32_t Bw = pw.B;  // NBW when nothing is kept
+    if (c == 0 && threadIdx.x == 0) {
+        a.state[s].Bw = Bw;
+        a.state[s].c_gtw = pw.above;
     }
-    const uint32_t P = (B1 << BITS2) | B2;  // 21-bit prefix of the threshold
 
     uint32_t *h3 = h;
     for (int b = threadIdx.x; b < NB3; b += BLOCK) h3[b] = 0;
     __syncthreads();
-    uint32_t def = 0;  // keys above the prefix: kept whatever the last digit is
-    double acc = 0.0;  // squares of the keys below the prefix: dropped whatever the last digit is
-    auto count_entry = [&](uint32_t raw) {
+    const uint32_t in_bin = (1u << shw) - 1u;
+    uint32_t def = 0;  // candidates above bin Bw
+    double acc = 0.0;  // squares of the candidates below bin Bw
+    auto count_entry = [&](uint32_t i, uint32_t raw) {
+        const bool cand = src.is_candidate(i, raw);
         const uint32_t key = key_of<VEC>(raw);
-        const uint32_t p = key >> SH2;
-        def += (p > P) ? 1u : 0u;
-        hist_add(h3, key & (NB3 - 1), p == P);
-        const double xd = (p < P) ? static_cast<double>(value_of<VEC>(raw)) : 0.0;
+        const uint32_t bin = window_bin(key, lo, shw);
+        def += (cand && bin > Bw) ? 1u : 0u;
+        hist_add(h3, ((key - lo) & in_bin) >> shl, cand && bin == Bw);
+        const double xd = (cand && bin < Bw) ? static_cast<double>(value_of<VEC>(raw)) : 0.0;
         acc = fma(xd, xd, acc);
     };
 #pragma unroll
-    for (int j = 0; j < LU; ++j)
-        if (beg + j * BLOCK + threadIdx.x < end) count_entry(first[j]);
-    // longer list blocks (large k, many ties): LU entries per thread at a time, their loads in flight together
-    for (uint32_t i0 = beg + LU * BLOCK; i0 < end; i0 += LU * BLOCK) {
+    for (int j = 0; j < LU; ++j) count_entry(j * BLOCK + threadIdx.x, first[j]);
+    // longer chunks (large k, many ties, a chunk read from the input): LU entries per thread at a time
+    for (uint32_t i0 = LU * BLOCK; i0 < src.len; i0 += LU * BLOCK) {
         uint32_t more[LU];
 #pragma unroll
-        for (int j = 0; j < LU; ++j) {
-            const uint32_t i = i0 + j * BLOCK + threadIdx.x;
-            more[j] = (i < end) ? static_cast<uint32_t>(Lv[i]) : 0u;
-        }
+        for (int j = 0; j < LU; ++j) more[j] = src.raw(i0 + j * BLOCK + threadIdx.x);
 #pragma unroll
-        for (int j = 0; j < LU; ++j)
-            if (i0 + j * BLOCK + threadIdx.x < end) count_entry(more[j]);
+        for (int j = 0; j < LU; ++j) count_entry(i0 + j * BLOCK + threadIdx.x, more[j]);
     }
     const double bsum = block_sum_f64(acc, smd);
     if (threadIdx.x == 0) a.lerr[g] = bsum;
@@ -943,83 +1207,76 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist3(Launch a) {
     if (threadIdx.x == 0) a.ldef[g] = deftot;
 }
 
+// k_emit.  Prologue: G3 -> the last digit B3 of the k-th key, hence the threshold key T and the tie
+// quota q; output offsets of the chunk from the rows of the earlier chunks.  Stable compaction of
+// the chunk's candidates into idx_out / val_out (key > T, plus the first q keys equal to T).  The
+// tensor's last chunk also adds up the error norm from the partial sums stored by the earlier
+// kernels, in a fixed order.
 template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     using R = typename Raw<VEC>::type;
     __shared__ uint32_t h[NB3];
     __shared__ uint32_t wcnt[2][2][LU * NW];
-    __shared__ uint32_t sm[NW];
+    __shared__ uint32_t sm[2 * NW];
     __shared__ double smd[NW];
     __shared__ uint32_t s_pick[2];
     __shared__ uint32_t s_off[2];
 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int g = blockIdx.x;
-    const int s = find_segment_by(a, g, false);
+    const int s = find_segment(a, g);
     const SegDesc &sg = a.seg[s];
-    const int lb = g - sg.lb_begin;
-    if (sg.nchunks == 0) {  // empty tensor: no output, zero error
-        if (lb == 0 && threadIdx.x == 0 && a.err_out != nullptr) a.err_out[s] = 0.0f;
-        return;
-    }
-    const uint32_t m = a.state[s].m;
-    uint32_t beg, end;
-    int nactive;
-    list_range(m, lb, sg.lb_count, beg, end, nactive);
-    // The error norm is summed by a list block that has no list entries of its own when the grid
-    // has one (the first one past the active blocks), so that the sum is off the critical path;
-    // otherwise by the first block.
-    const int err_lb = (a.err_out != nullptr) ? (nactive < sg.lb_count ? nactive : 0) : -1;
-    if (lb >= nactive && lb != err_lb) return;
-    const uint32_t P = (a.state[s].B1 << BITS2) | a.state[s].B2;
-    const uint32_t c_gt2 = a.state[s].c_gt2;
+    const int c = g - sg.chunk_begin;
+    const bool spec = a.state[s].spec_held != 0;
+    const uint32_t lo = spec ? a.state[s].loA : a.state[s].loB;
+    const uint32_t shw = spec ? a.state[s].shwA : a.state[s].shwB;
+    const uint32_t shl = VEC == TAG_F32 ? 0u : 16u;
+    const uint32_t Bw = a.state[s].Bw, c_gtw = a.state[s].c_gtw;
     const uint32_t kout = static_cast<uint32_t>(sg.k);
+    const ChunkSource<VEC> src = chunk_source<VEC>(a, sg, g, lo);
 
-    // The block's first tile of list entries does not depend on the prologue: its loads are in
-    // flight while the prologue runs (a typical list block is one tile).
-    const int32_t *Li = a.L_idx + sg.l_base;
-    const R *Lv = static_cast<const R *>(a.L_val) + sg.l_base;
     uint32_t raw[LU];
     int32_t id[LU];
     auto load_tile = [&](uint32_t t0) {
 #pragma unroll
         for (int j = 0; j < LU; ++j) {
             const uint32_t i = t0 + j * BLOCK + threadIdx.x;
-            const bool valid = i < end;
-            raw[j] = valid ? static_cast<uint32_t>(Lv[i]) : 0u;
-            id[j] = valid ? Li[i] : 0;
+            raw[j] = src.raw(i);
+            id[j] = src.index(i);
         }
     };
 
-    // Prologue: last digit -> threshold key T and tie quota q.  The loads of the third-digit
-    // histogram go first, the list tile behind them (the wavefront's load counter is in order).
+    // Prologue: last digit -> threshold key T and tie quota q.  The loads of the last digit's
+    // histogram go first, the chunk's first tile behind them (the wavefront's load counter is in order).
     uint32_t B3, above3;
-    uint32_t my_bins[NB3 / BLOCK];  // raw counts of the third-digit bins this thread owns
+    uint32_t my_bins[NB3 / BLOCK];  // raw counts of the last-digit bins this thread owns
 #pragma unroll
     for (int j = 0; j < NB3 / BLOCK; ++j) my_bins[j] = a.G3[s * NB3 + threadIdx.x * (NB3 / BLOCK) + j];
     __builtin_amdgcn_sched_barrier(0);
-    load_tile(beg);
+    load_tile(0);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < NB3 / BLOCK; ++j) h[threadIdx.x * (NB3 / BLOCK) + j] = my_bins[j];
     __syncthreads();
     block_suffix_inplace<NB3>(h, sm);
-    block_pick_bucket<NB3>(h, kout - c_gt2, s_pick);
+    block_pick_bucket<NB3>(h, kout - c_gtw, s_pick);
     __syncthreads();
     B3 = s_pick[0];
     above3 = s_pick[1];
     __syncthreads();
-    const uint32_t T = (B3 < NB3) ? ((P << BITS3) | B3) : 0xFFFFFFFFu;
-    const uint32_t q = kout - (c_gt2 + above3);
+    const bool any_kept = Bw < NBW && B3 < NB3;
+    const uint32_t bin_key = lo + (Bw << shw);  // lowest key of window bin Bw
+    const uint32_t T = any_kept ? bin_key + (B3 << shl) : 0xFFFFFFFFu;
+    const uint32_t q = kout - (c_gtw + above3);
 
-    // Error norm of the segment, by one list block only.  Everything it needs was stored by
-    // earlier kernels: per-chunk sums of squares below bucket B1 (k_gather), per-list-block sums of
-    // squares below the 21-bit prefix (k_hist3), and the counts of the entries that match the
-    // prefix: all entries of one third-digit bin share one key, hence one square, so the dropped
-    // ones among them add count * value^2.  Fixed summation order.
-    if (lb == err_lb) {
+    // Error norm of the tensor, by its last chunk's workgroup only (that chunk is the short one).
+    // Everything it needs was stored by earlier kernels: per-chunk sums of squares below the window
+    // (k_scan), per-chunk sums of squares of the candidates below bin Bw (k_refine), and the counts of
+    // the candidates in bin Bw: all entries of one last-digit bin share one key, hence one square, so
+    // the dropped ones among them add count * value^2.  Fixed summation order.
+    if (c == sg.nchunks - 1 && a.err_out != nullptr) {
         double part = 0.0;
-        for (int cc = threadIdx.x; cc < sg.nchunks; cc += BLOCK) part += a.chunk_err[sg.chunk_begin + cc];
-        for (int bb = threadIdx.x; bb < nactive; bb += BLOCK) part += a.lerr[sg.lb_begin + bb];
+        for (int cc = threadIdx.x; cc < sg.nchunks; cc += BLOCK)
+            part += a.chunk_err[sg.chunk_begin + cc] + a.lerr[sg.chunk_begin + cc];
 #pragma unroll
         for (int j = 0; j < NB3 / BLOCK; ++j) {
             const uint32_t b = threadIdx.x * (NB3 / BLOCK) + j;
@@ -1027,30 +1284,28 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
             if (b < B3 || B3 >= NB3) dropped = my_bins[j];
             else if (b == B3) dropped = my_bins[j] - q;
             if (dropped) {
-                const uint32_t key = (P << BITS3) | b;  // 16-bit types carry their pattern in the key's upper half
+                const uint32_t key = bin_key + (b << shl);  // 16-bit types carry their pattern in the key's upper half
                 const double v = static_cast<double>(value_of<VEC>(VEC == TAG_F32 ? key : (key >> 16)));
                 part = fma(static_cast<double>(dropped) * v, v, part);
             }
         }
         const double tot = block_sum_f64(part, smd);
         if (threadIdx.x == 0) a.err_out[s] = static_cast<float>(sqrt(tot));
-        if (lb >= nactive) return;  // no list entries here (uniform for the workgroup)
     }
 
-    // Output offsets of this list block = scan over the earlier list blocks of
-    // (#keys above T, #keys equal to T).
+    // Output offsets of this chunk = scan over the earlier chunks of (#keys above T, #keys equal to T).
     {
         uint32_t gt = 0, eq = 0;
-        if (static_cast<int>(threadIdx.x) < nactive && B3 < NB3) {
-            const uint32_t *r = a.rows3 + static_cast<size_t>(sg.lb_begin + threadIdx.x) * NB3;
+        if (static_cast<int>(threadIdx.x) < sg.nchunks && any_kept) {
+            const uint32_t *r = a.rows3 + static_cast<size_t>(sg.chunk_begin + threadIdx.x) * NB3;
             const uint32_t above = (B3 + 1 < NB3) ? r[B3 + 1] : 0u;
-            gt = a.ldef[sg.lb_begin + threadIdx.x] + above;
+            gt = a.ldef[sg.chunk_begin + threadIdx.x] + above;
             eq = r[B3] - above;
         }
         uint32_t tot;
         const uint32_t inc_gt = block_incl_scan(gt, sm, &tot);
         const uint32_t inc_eq = block_incl_scan(eq, sm, &tot);
-        if (static_cast<int>(threadIdx.x) == lb) {
+        if (static_cast<int>(threadIdx.x) == c) {
             s_off[0] = inc_gt - gt;
             s_off[1] = inc_eq - eq;
         }
@@ -1065,13 +1320,13 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     R *ov = static_cast<R *>(op.val);
 
     int buf = 0;
-    for (uint32_t t0 = beg; t0 < end; t0 += BLOCK * LU, buf ^= 1) {
-        if (t0 != beg) load_tile(t0);
+    for (uint32_t t0 = 0; t0 < src.len; t0 += BLOCK * LU, buf ^= 1) {
+        if (t0 != 0) load_tile(t0);
         uint32_t pre_gt[LU], pre_eq[LU], cls[LU];  // cls: 0 not kept for sure, 1 equal to T, 2 above T
 #pragma unroll
         for (int j = 0; j < LU; ++j) {
             const uint32_t i = t0 + j * BLOCK + threadIdx.x;
-            const bool valid = i < end;
+            const bool valid = i < src.len;
             const uint32_t key = key_of<VEC>(raw[j]);
             const bool gt = valid && key > T, eq = valid && key == T;
             cls[j] = gt ? 2u : (eq ? 1u : 0u);
@@ -1535,35 +1790,25 @@ using adatopk_internal::dtype_ok;
 using adatopk_internal::elem_size;
 using adatopk_internal::wire_val_offset;
 
-int64_t chunk_elems(int64_t n_total, int64_t target) {
+// Elements per chunk for a launch of S_batch tensors holding n_batch elements: a multiple of the
+// tile such that the chunks of all tensors together (every tensor's last chunk may be partial, an
+// empty tensor still gets one) number at most `target`: n_batch / E + S_batch <= target.
+int64_t chunk_elems(int64_t n_batch, int32_t S_batch, int64_t target) {
     const int64_t tile = TILE;
-    int64_t e = (n_total + target - 1) / target;
+    const int64_t full = target - S_batch;  // S_batch <= MAXSEG < target
+    int64_t e = (n_batch + full - 1) / full;
     if (e < tile) e = tile;
-    e = (e + tile - 1) / tile * tile;
-    const int64_t cap = (static_cast<int64_t>(1) << 30) / tile * tile;
-    return e < cap ? e : cap;
+    return (e + tile - 1) / tile * tile;
 }
-
-int32_t list_blocks_cap(int32_t S) {  // k_emit scans a segment's list blocks with one thread each: at most BLOCK
-    int32_t c = LB_TOTAL / (S < 1 ? 1 : (S > MAXSEG ? MAXSEG : S));
-    if (c < 16) c = 16;
-    if (c > BLOCK) c = BLOCK;
-    return c;
-}
-
-int32_t list_blocks(int64_t n, int32_t S) {
-    int64_t b = (n + LB_ELEMS - 1) / LB_ELEMS;
-    const int32_t cap = list_blocks_cap(S);
-    if (b < 1) b = 1;
-    return b > cap ? cap : static_cast<int32_t>(b);
-}
+inline int64_t chunk_target(int32_t S_batch) { return S_batch == 1 ? CTARGET_ONE : CTARGET; }
 
 struct Carve {
-    size_t state, G3, rows1, coarse1, rows2, coarse2, chunk_err, rows3, ldef, lerr, wire_err, L_idx, L_val, total;
+    size_t state, G3, rows1, coarse1, rowsW, coarseW, cpairA, cnt, chunk_err, rows3, ldef, lerr, wire_err, L_idx, L_val,
+        total;
 };
 
-// Workspace layout for up to max_chunks chunks, max_lb list blocks and n_total list slots.
-Carve carve(int64_t max_chunks, int64_t max_lb, int64_t n_total, int32_t S, adatopk_dtype dt) {
+// Workspace layout for up to max_chunks chunks and list_slots candidate-list slots.
+Carve carve(int64_t max_chunks, int64_t list_slots, int32_t S, adatopk_dtype dt) {
     Carve c;
     size_t p = 0;
     auto take = [&](size_t bytes) {
@@ -1575,38 +1820,41 @@ Carve carve(int64_t max_chunks, int64_t max_lb, int64_t n_total, int32_t S, adat
     c.G3 = take(sizeof(uint32_t) * NB3 * MAXSEG);
     c.rows1 = take(sizeof(uint32_t) * NB1 * max_chunks);
     c.coarse1 = take(sizeof(uint32_t) * NC1 * max_chunks);
-    c.rows2 = take(sizeof(uint32_t) * NB2 * max_chunks);
-    c.coarse2 = take(sizeof(uint32_t) * NC2 * max_chunks);
+    c.rowsW = take(sizeof(uint32_t) * NBW * max_chunks);
+    c.coarseW = take(sizeof(uint32_t) * NCW * max_chunks);
+    c.cpairA = take(sizeof(uint2) * max_chunks);
+    c.cnt = take(sizeof(uint32_t) * max_chunks);
     c.chunk_err = take(sizeof(double) * max_chunks);
-    c.rows3 = take(sizeof(uint32_t) * NB3 * max_lb);
-    c.ldef = take(sizeof(uint32_t) * max_lb);
-    c.lerr = take(sizeof(double) * max_lb);
+    c.rows3 = take(sizeof(uint32_t) * NB3 * max_chunks);
+    c.ldef = take(sizeof(uint32_t) * max_chunks);
+    c.lerr = take(sizeof(double) * max_chunks);
     c.wire_err = take(sizeof(float) * static_cast<size_t>(S < 1 ? 1 : S));  // error norms on their way into message headers
-    c.L_idx = take(sizeof(int32_t) * static_cast<size_t>(n_total));
-    c.L_val = take(static_cast<size_t>(elem_size(dt)) * static_cast<size_t>(n_total));
+    c.L_idx = take(sizeof(int32_t) * static_cast<size_t>(list_slots));
+    c.L_val = take(static_cast<size_t>(elem_size(dt)) * static_cast<size_t>(list_slots));
     c.total = p;
     return c;
 }
 
-// Upper bounds on the chunks and list blocks of any one launch of a call over n_total elements
-// in S segments: a launch holds at most MAXSEG segments, every segment's last chunk may be
-// partial, and the planner never uses more than CTARGET full chunks nor chunks below one tile.
-void bounds_for(int64_t n_total, int32_t S, adatopk_dtype dt, int64_t *max_chunks, int64_t *max_lb) {
-    (void)dt;
+// Upper bounds on the chunks and the list slots of any one launch of a call over n_total elements
+// in S tensors: a launch holds at most MAXSEG tensors and at most chunk_target() chunks of
+// chunk_elems() elements, and no launch holds more elements than the whole call.
+void bounds_for(int64_t n_total, int32_t S, int64_t *max_chunks, int64_t *list_slots) {
     const int32_t batch = S > MAXSEG ? MAXSEG : (S < 1 ? 1 : S);
-    const int64_t by_tiles = n_total / TILE + 1;
-    *max_chunks = (by_tiles < CTARGET ? by_tiles : CTARGET) + batch + 1;
-    *max_lb = static_cast<int64_t>(batch) * list_blocks_cap(S);
+    const int64_t target = chunk_target(batch);
+    *max_chunks = target;
+    *list_slots = target * (chunk_elems(n_total, batch, target) / LIST_DIV);
 }
 
 // Every kernel launch of the library goes through launch().  The stage names the kernel for the
 // measuring build of this file (ADATOPK_MEASURE_BUILD, a library of its own next to the product
 // library), which gives every launch start / stop events carrying the timestamps of the dispatch
 // itself, as a profiler sees it; the product build launches plainly and keeps no state.
-enum Stage { ST_HIST1, ST_GATHER, ST_HIST3, ST_EMIT, ST_FILL, ST_SCATTER, ST_MERGE, ST_HEADER, ST_SMALL, NSTAGE };
+enum Stage {
+    ST_SPEC, ST_HIST1, ST_SCAN, ST_REFINE, ST_EMIT, ST_FILL, ST_SCATTER, ST_MERGE, ST_HEADER, ST_SMALL, NSTAGE
+};
 #ifdef ADATOPK_MEASURE_BUILD
-const char *const kStageNames[NSTAGE] = {"k_hist1", "k_gather", "k_hist3", "k_emit",
-                                         "k_fill",  "k_scatter", "k_merge", "k_wire_header", "k_small"};
+const char *const kStageNames[NSTAGE] = {"k_scan_spec", "k_hist1", "k_scan", "k_refine", "k_emit",
+                                         "k_fill", "k_scatter", "k_merge", "k_wire_header", "k_small"};
 bool g_measure = false;
 bool g_events_made = false;
 hipEvent_t g_start[NSTAGE], g_stop[NSTAGE];
@@ -1626,13 +1874,21 @@ inline void launch(int stage, K kernel, dim3 grid, hipStream_t st, Args... args)
     hipLaunchKernelGGL(kernel, grid, dim3(BLOCK), 0, st, args...);
 }
 
-template <int VEC> adatopk_status launch_batch(const Launch &a, int total_chunks, int total_lb, hipStream_t st) {
-    if (total_chunks > 0) {
-        launch(ST_HIST1, k_hist1<VEC>, dim3(total_chunks), st, a);
-        launch(ST_GATHER, k_gather<VEC>, dim3(total_chunks), st, a);
+// The kernels of one launch.  With `speculate` the first full read of the input is the speculative
+// scan; the two exact passes behind it return at once for every tensor whose speculation held and
+// do the work for the others, so what reaches k_refine is complete either way.
+template <int VEC> adatopk_status launch_batch(const Launch &a, int total_chunks, bool speculate, hipStream_t st) {
+    const dim3 grid(total_chunks);
+    const bool one_per_cu = total_chunks <= CTARGET_ONE;  // the scan can afford the deeper pipeline
+    if (speculate) {
+        if (one_per_cu) launch(ST_SPEC, k_scan<VEC, true, 3>, grid, st, a);
+        else launch(ST_SPEC, k_scan<VEC, true, 2>, grid, st, a);
     }
-    launch(ST_HIST3, k_hist3<VEC>, dim3(total_lb), st, a);
-    launch(ST_EMIT, k_emit<VEC>, dim3(total_lb), st, a);
+    launch(ST_HIST1, k_hist1<VEC>, grid, st, a);
+    if (one_per_cu) launch(ST_SCAN, k_scan<VEC, false, 3>, grid, st, a);
+    else launch(ST_SCAN, k_scan<VEC, false, 2>, grid, st, a);
+    launch(ST_REFINE, k_refine<VEC>, grid, st, a);
+    launch(ST_EMIT, k_emit<VEC>, grid, st, a);
     return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
 }
 
@@ -1648,6 +1904,34 @@ struct OutSpec {
     const int64_t *offset;
     bool wire;
 };
+
+// Size of the sample and the ranks in it that bracket the k-th key of a tensor of n elements, or
+// false when the speculative pass is not worth it for this tensor (small tensors; keep counts so
+// small that even the largest sample says little about the k-th key; keep counts so large that the
+// candidates would not fit the chunks' lists anyway).  Of ns sampled elements, mu = k * ns / n are
+// expected among the k largest, with a standard deviation of at most sqrt(mu); the bracket is
+// SPEC_SIGMAS of them to either side.  The sample is the smallest of a quarter, half or all of
+// SAMPLE_ELEMS that expects SPEC_GOOD_EXPECTED kept elements, and the largest otherwise.
+bool speculation_ranks(int64_t n, int64_t k, adatopk_dtype dt, bool aligned4, uint32_t *r_lo, uint32_t *r_hi,
+                       uint32_t *batches) {
+    if (!aligned4 || n < SPEC_MIN_N || k <= 0 || k > n / 100 * SPEC_MAX_KEEP_PERCENT) return false;
+    const int epd = 4 / elem_size(dt);
+    const int max_batches = SAMPLE_ELEMS / BLOCK / epd / SAMPLE_BATCH;
+    double mu = 0.0;
+    int nb = max_batches;
+    for (int b = 1; b <= max_batches; b *= 2) {
+        mu = static_cast<double>(k) * (static_cast<double>(b) * SAMPLE_BATCH * BLOCK * epd) / static_cast<double>(n);
+        nb = b;
+        if (mu >= SPEC_GOOD_EXPECTED) break;
+    }
+    if (mu < SPEC_MIN_EXPECTED) return false;
+    const double margin = SPEC_SIGMAS * sqrt(mu) + 2.0;
+    const double lo = ceil(mu + margin), hi = floor(mu - margin);
+    *r_lo = lo > 4.0e9 ? 0xFFFFFFFFu : static_cast<uint32_t>(lo);
+    *r_hi = hi < 1.0 ? 0u : static_cast<uint32_t>(hi);
+    *batches = static_cast<uint32_t>(nb);
+    return true;
+}
 
 adatopk_status compress_impl(const void *const *dense, const int64_t *n, const int64_t *k, int32_t S,
                              adatopk_dtype dt, const OutSpec &out, float *err_out, void *workspace,
@@ -1677,11 +1961,12 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
     const size_t need = adatopk_workspace_bytes(n_total, S, dt);
     if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256) return ADATOPK_EINVAL;
     if (workspace_bytes < need) return ADATOPK_EWORKSPACE;
-    int64_t max_chunks, max_lb;
-    bounds_for(n_total, S, dt, &max_chunks, &max_lb);
-    const Carve cv = carve(max_chunks, max_lb, n_total, S, dt);
+    int64_t max_chunks, list_slots;
+    bounds_for(n_total, S, &max_chunks, &list_slots);
+    const Carve cv = carve(max_chunks, list_slots, S, dt);
     char *ws = static_cast<char *>(workspace);
     if (out.wire) err_out = reinterpret_cast<float *>(ws + cv.wire_err);
+    const int64_t header = out.wire ? static_cast<int64_t>(sizeof(adatopk_wire_header)) : 0;
 
     // Only small tensors: one launch, one workgroup per tensor, no workspace traffic.
     bool all_small = true;
@@ -1692,7 +1977,7 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
             const int32_t cnt = (S - s0 < SMALL_MAXSEG) ? S - s0 : SMALL_MAXSEG;
             for (int32_t i = 0; i < cnt; ++i) {
                 sl.seg[i].x = dense[s0 + i];
-                sl.seg[i].out_off = out_offset[s0 + i] + (out.wire ? static_cast<int64_t>(sizeof(adatopk_wire_header)) : 0);
+                sl.seg[i].out_off = out_offset[s0 + i] + header;
                 sl.seg[i].n = static_cast<int32_t>(n[s0 + i]);
                 sl.seg[i].k = static_cast<int32_t>(k[s0 + i]);
             }
@@ -1712,27 +1997,30 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
     for (int32_t s0 = 0; s0 < S; s0 += MAXSEG) {
         Launch a{};
         a.S = (S - s0 < MAXSEG) ? S - s0 : MAXSEG;
-        // Chunk size of this launch: about CTARGET chunks in all, and not more, so that all workgroups
-        // are resident at once (a few chunks beyond that would run as a second, nearly empty round).
+        // Chunk size of this launch: at most chunk_target() chunks in all, so that all workgroups are
+        // resident at once (a few chunks beyond that would run as a second, nearly empty round).
         int64_t n_batch = 0;
         for (int32_t i = 0; i < a.S; ++i) n_batch += n[s0 + i];
-        const int64_t target = a.S == 1 ? CTARGET_ONE : CTARGET;
-        int64_t E = chunk_elems(n_batch, target);
-        for (int iter = 0; iter < 32; ++iter) {
+        const int64_t target = chunk_target(a.S);
+        const int64_t E_fits = chunk_elems(n_batch, a.S, target);  // fits whatever the tensors' lengths are
+        int64_t E = (n_batch + target - 1) / target;
+        E = E < TILE ? TILE : (E + TILE - 1) / TILE * TILE;
+        auto chunks_at = [&](int64_t e) {
             int64_t count = 0;
-            for (int32_t i = 0; i < a.S; ++i) count += (n[s0 + i] + E - 1) / E;
-            if (count <= target) break;
-            const int64_t grown = ((E * count + target - 1) / target + TILE - 1) / TILE * TILE;
-            E = grown > E ? grown : E + TILE;
-            if (E > (static_cast<int64_t>(1) << 30)) break;
-        }
+            for (int32_t i = 0; i < a.S; ++i) count += n[s0 + i] > 0 ? (n[s0 + i] + e - 1) / e : 1;
+            return count;
+        };
+        while (E < E_fits && chunks_at(E) > target) E += TILE;
         a.E = static_cast<int32_t>(E);
+        a.cap = static_cast<uint32_t>(E / LIST_DIV);
         a.state = reinterpret_cast<SegState *>(ws + cv.state);
         a.G3 = reinterpret_cast<uint32_t *>(ws + cv.G3);
         a.rows1 = reinterpret_cast<uint32_t *>(ws + cv.rows1);
         a.coarse1 = reinterpret_cast<uint32_t *>(ws + cv.coarse1);
-        a.rows2 = reinterpret_cast<uint32_t *>(ws + cv.rows2);
-        a.coarse2 = reinterpret_cast<uint32_t *>(ws + cv.coarse2);
+        a.rowsW = reinterpret_cast<uint32_t *>(ws + cv.rowsW);
+        a.coarseW = reinterpret_cast<uint32_t *>(ws + cv.coarseW);
+        a.cpairA = reinterpret_cast<uint2 *>(ws + cv.cpairA);
+        a.cnt = reinterpret_cast<uint32_t *>(ws + cv.cnt);
         a.chunk_err = reinterpret_cast<double *>(ws + cv.chunk_err);
         a.rows3 = reinterpret_cast<uint32_t *>(ws + cv.rows3);
         a.ldef = reinterpret_cast<uint32_t *>(ws + cv.ldef);
@@ -1744,29 +2032,29 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
         a.wire = out.wire ? 1u : 0u;
         a.val_out = val_out;
         a.err_out = err_out ? err_out + s0 : nullptr;
-        int32_t chunks = 0, lbs = 0;
-        int64_t l_base = 0;
+        int32_t chunks = 0;
+        bool speculate = false;
         for (int32_t i = 0; i < a.S; ++i) {
             SegDesc &d = a.seg[i];
             const int32_t s = s0 + i;
             d.x = dense[s];
-            d.out_off = out_offset[s] + (out.wire ? static_cast<int64_t>(sizeof(adatopk_wire_header)) : 0);
-            d.l_base = l_base;
+            d.out_off = out_offset[s] + header;
             d.n = static_cast<int32_t>(n[s]);
             d.k = static_cast<int32_t>(k[s]);
             d.chunk_begin = chunks;
-            d.nchunks = static_cast<int32_t>((n[s] + E - 1) / E);
-            d.lb_begin = lbs;
-            d.lb_count = list_blocks(n[s], S);
-            d.aligned4 = (reinterpret_cast<uintptr_t>(dense[s]) % 4 == 0) ? 1u : 0u;
+            d.nchunks = n[s] > 0 ? static_cast<int32_t>((n[s] + E - 1) / E) : 1;  // an empty tensor keeps one (empty) chunk
+            const bool aligned4 = reinterpret_cast<uintptr_t>(dense[s]) % 4 == 0;
+            d.flags = aligned4 ? FLAG_ALIGNED4 : 0u;
+            if (speculation_ranks(n[s], k[s], dt, aligned4, &d.r_lo, &d.r_hi, &d.sample_batches)) {
+                d.flags |= FLAG_SPEC;
+                speculate = true;
+            }
             chunks += d.nchunks;
-            lbs += d.lb_count;
-            l_base += n[s];
         }
-        if (chunks > max_chunks || lbs > max_lb) return ADATOPK_ERUNTIME;  // planner invariant
-        const adatopk_status rc = (dt == ADATOPK_F32)    ? launch_batch<TAG_F32>(a, chunks, lbs, st)
-                                  : (dt == ADATOPK_BF16) ? launch_batch<TAG_BF16>(a, chunks, lbs, st)
-                                                         : launch_batch<TAG_F16>(a, chunks, lbs, st);
+        if (chunks > max_chunks || static_cast<int64_t>(chunks) * a.cap > list_slots) return ADATOPK_ERUNTIME;  // planner invariant
+        const adatopk_status rc = (dt == ADATOPK_F32)    ? launch_batch<TAG_F32>(a, chunks, speculate, st)
+                                  : (dt == ADATOPK_BF16) ? launch_batch<TAG_BF16>(a, chunks, speculate, st)
+                                                         : launch_batch<TAG_F16>(a, chunks, speculate, st);
         if (rc != ADATOPK_OK) return rc;
     }
     return ADATOPK_OK;
@@ -2002,10 +2290,10 @@ adatopk_status compress_wire_impl(const void *const *dense, const int64_t *n, co
     // the error norms are in the workspace now (stream order): write the headers around them
     int64_t n_total = 0;
     for (int32_t s = 0; s < S; ++s) n_total += n[s];
-    int64_t max_chunks, max_lb;
-    bounds_for(n_total, S, dt, &max_chunks, &max_lb);
+    int64_t max_chunks, list_slots;
+    bounds_for(n_total, S, &max_chunks, &list_slots);
     const float *err = reinterpret_cast<const float *>(static_cast<char *>(workspace) +
-                                                       carve(max_chunks, max_lb, n_total, S, dt).wire_err);
+                                                       carve(max_chunks, list_slots, S, dt).wire_err);
     for (int32_t s0 = 0; s0 < S; s0 += HDR_MAXSEG) {
         HeaderLaunch a{};
         const int32_t cnt = (S - s0 < HDR_MAXSEG) ? S - s0 : HDR_MAXSEG;
@@ -2057,9 +2345,9 @@ extern "C" {
 
 size_t adatopk_workspace_bytes(int64_t n_total, int32_t num_segments, adatopk_dtype dt) {
     if (n_total < 0 || num_segments < 1 || !dtype_ok(dt)) return 0;
-    int64_t max_chunks, max_lb;
-    bounds_for(n_total, num_segments, dt, &max_chunks, &max_lb);
-    return carve(max_chunks, max_lb, n_total, num_segments, dt).total;
+    int64_t max_chunks, list_slots;
+    bounds_for(n_total, num_segments, &max_chunks, &list_slots);
+    return carve(max_chunks, list_slots, num_segments, dt).total;
 }
 
 adatopk_status adatopk_compress(const void *dense, int64_t n, adatopk_dtype dt, int64_t k, int32_t *idx_out,

@@ -51,10 +51,14 @@ def test_workspace_bytes(lib):
     assert lib.adatopk_workspace_bytes(10, 1, 7) == 0
     small, big = lib.adatopk_workspace_bytes(1000, 1, 0), lib.adatopk_workspace_bytes(25_165_824, 1, 0)
     assert 0 < small < big
-    assert big >= 25_165_824 * 8  # the candidate list can hold every element (all-equal input)
+    # candidate lists for a quarter of the elements (chunks with more are read from the input again) and
+    # a few MB of per-chunk counts: well below the tensor's own size
+    assert 25_165_824 * 8 // 4 <= big <= 25_165_824 * 8 // 4 + (16 << 20)
+    assert big <= 64 << 20  # the headline tensor fits the resident scratch of adatopk_compress_noalloc
     assert lib.adatopk_workspace_bytes(25_165_824, 1, 1) < big  # bf16 values are half the size
     assert lib.adatopk_workspace_bytes(25_165_824, 1, 2) == lib.adatopk_workspace_bytes(25_165_824, 1, 1)  # fp16 too
-    assert lib.adatopk_workspace_bytes(201_326_592, 24, 0) >= 201_326_592 * 8
+    many = lib.adatopk_workspace_bytes(201_326_592, 24, 0)
+    assert 201_326_592 * 8 // 4 <= many <= 201_326_592 * 8 // 3
 
 
 def test_compress_rejects_bad_arguments_before_touching_the_device(lib):
