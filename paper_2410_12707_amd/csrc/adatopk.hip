@@ -90,6 +90,8 @@ constexpr int SAMPLE_ELEMS = 32768;   // elements of a tensor that the speculati
 constexpr int SAMPLE_SH = 18;         // sample histogram: bin = key >> SAMPLE_SH ...
 constexpr int NSB = 1 << (31 - SAMPLE_SH);  // ... 8192 bins, 4 to the binade's eighth (2.2 % in value)
 constexpr int LIST_DIV = 4;           // a chunk's candidate list holds up to a quarter of the chunk
+constexpr int MAXSUB = 8;             // parts that the list kernels cut a chunk's candidates into, at most
+constexpr int SUB_ENTRIES = 8192;     // ... so that a part has about this many
 constexpr int MAXSEG = 64;            // segments per launch (the table travels as kernel arguments)
 constexpr int CTARGET = 512;          // chunks of a launch of several tensors, at most (two workgroups per compute unit)
 // ... and of a single tensor: one workgroup per compute unit.  Half the rows for every prologue to
@@ -138,6 +140,7 @@ struct Launch {
     int32_t S;
     int32_t E;      // elements per chunk (multiple of the tile)
     uint32_t cap;   // list slots per chunk (E / LIST_DIV)
+    uint32_t sub;   // workgroups per chunk in the list kernels (1 .. MAXSUB): long candidate lists are cut into parts
     uint32_t idx64;
     uint32_t wire;  // outputs are wire messages in one buffer (idx_out): values follow the padded index section
     SegState *state;
@@ -147,9 +150,9 @@ struct Launch {
     uint2 *cpairA;                // [chunks] speculative pass only: #candidates, #candidates in the open-ended last bin
     uint32_t *cnt;                // [chunks] #candidates of the chunk; more than cap: the list is incomplete
     double *chunk_err;            // [chunks] sum of squares of the chunk's elements below the window
-    uint32_t *rows3;              // [chunks][NB3] suffix sums of the last digit inside the k-th key's window bin
-    uint32_t *ldef;               // [chunks] #candidates in the window bins above that bin
-    double *lerr;                 // [chunks] squares of the candidates in the window bins below it
+    uint32_t *rows3;              // [chunks * sub][NB3] suffix sums of the last digit inside the k-th key's window bin
+    uint32_t *ldef;               // [chunks * sub] #candidates in the window bins above that bin
+    double *lerr;                 // [chunks * sub] squares of the candidates in the window bins below it
     int32_t *L_idx;               // [chunks][cap] candidate lists, one region per chunk
     void *L_val;
     void *idx_out;     // int32 entries, or int64 when idx64 is set (the paper's index width, Sec. 5.2)
@@ -739,23 +742,66 @@ __device__ __forceinline__ void scan_tile(const uint32_t (&dw)[Stream<VEC>::SLOT
     uint64_t m[SLOTS][EPD];
     bool keep[SLOTS][EPD];  // lives as the compare's lane mask, i.e. the same registers as m
     uint32_t wc = 0;
+    if (VEC != TAG_F32 && FAST) {
+        // Two 16-bit elements per dword, handled as a pair: one AND clears both signs, each half is
+        // compared with the window's lowest pattern (lo is a multiple of 2^16 for these types).  The
+        // squares of the dropped ones: fp16 values are added in fp32 over the tile's 16 elements of the
+        // lane before the sum is widened (a square of an fp16 value is exact in fp32, 22 significant
+        // bits and well inside its range, and 16 additions in fp32 leave the sum within 1e-6 of exact,
+        // far inside the error norm's tolerance); bf16 values have fp32's exponent range, their squares
+        // do not, so they are widened first as fp32 values are.
+        const uint32_t thr16 = lo >> 16;
+        float part = 0.0f;
 #pragma unroll
-    for (int e = 0; e < SLOTS; ++e)
-#pragma unroll
-        for (int hh = 0; hh < EPD; ++hh) {
-            const uint32_t raw = elem_of<VEC>(dw[e], hh);
-            const bool ok = FAST || ((valid[e] >> hh) & 1u);
-            keep[e][hh] = ok && key_of<VEC>(raw) >= lo;
-            m[e][hh] = __ballot(keep[e][hh]);
-            wc += __popcll(m[e][hh]);
-            float xs = (ok && !keep[e][hh]) ? value_of<VEC>(raw) : 0.0f;
-            // The empty statement pins the select to the 32-bit value: left alone, the compiler widens
-            // first and then selects both halves of the double (one more instruction per element in a
-            // loop whose time follows its instruction count: 24.0 -> 22.7 us on the 100 MB tensor).
-            asm("" : "+v"(xs));
-            const double xd = static_cast<double>(xs);
-            acc = fma(xd, xd, acc);
+        for (int e = 0; e < SLOTS; ++e) {
+            const uint32_t k2 = dw[e] & 0x7FFF7FFFu;
+            const uint32_t k_lo = k2 & 0xFFFFu, k_hi = k2 >> 16;
+            keep[e][0] = k_lo >= thr16;
+            keep[e][EPD - 1] = k_hi >= thr16;
+            m[e][0] = __ballot(keep[e][0]);
+            m[e][EPD - 1] = __ballot(keep[e][EPD - 1]);
+            wc += __popcll(m[e][0]) + __popcll(m[e][EPD - 1]);
+            float x_lo, x_hi;  // magnitudes: the signs are gone, the squares do not care
+            if (VEC == TAG_F16) {
+                x_lo = __half2float(__ushort_as_half(static_cast<unsigned short>(k_lo)));
+                x_hi = __half2float(__ushort_as_half(static_cast<unsigned short>(k_hi)));
+            } else {
+                x_lo = __uint_as_float(k2 << 16);
+                x_hi = __uint_as_float(k2 & 0xFFFF0000u);
+            }
+            x_lo = keep[e][0] ? 0.0f : x_lo;
+            x_hi = keep[e][EPD - 1] ? 0.0f : x_hi;
+            if (VEC == TAG_F16) {
+                part = fmaf(x_lo, x_lo, part);
+                part = fmaf(x_hi, x_hi, part);
+            } else {
+                asm("" : "+v"(x_lo));  // keeps the selects on the 32-bit values (see below)
+                asm("" : "+v"(x_hi));
+                const double d_lo = static_cast<double>(x_lo), d_hi = static_cast<double>(x_hi);
+                acc = fma(d_lo, d_lo, acc);
+                acc = fma(d_hi, d_hi, acc);
+            }
         }
+        acc += static_cast<double>(part);
+    } else {
+#pragma unroll
+        for (int e = 0; e < SLOTS; ++e)
+#pragma unroll
+            for (int hh = 0; hh < EPD; ++hh) {
+                const uint32_t raw = elem_of<VEC>(dw[e], hh);
+                const bool ok = FAST || ((valid[e] >> hh) & 1u);
+                keep[e][hh] = ok && key_of<VEC>(raw) >= lo;
+                m[e][hh] = __ballot(keep[e][hh]);
+                wc += __popcll(m[e][hh]);
+                float xs = (ok && !keep[e][hh]) ? value_of<VEC>(raw) : 0.0f;
+                // The empty statement pins the select to the 32-bit value: left alone, the compiler widens
+                // first and then selects both halves of the double (one more instruction per element in a
+                // loop whose time follows its instruction count: 24.0 -> 22.7 us on the 100 MB tensor).
+                asm("" : "+v"(xs));
+                const double xd = static_cast<double>(xs);
+                acc = fma(xd, xd, acc);
+            }
+    }
     if (lane == 0) wcnt[w] = wc;
     __syncthreads();
     uint32_t before, tot;  // wave-uniform, in scalar registers: the branches below are scalar
@@ -932,10 +978,11 @@ __device__ __forceinline__ void sample_window(const SegDesc &sg, uint32_t *hs, u
     __syncthreads();
     lo = b_lo < NSB ? b_lo << SAMPLE_SH : 0u;
     const uint32_t hi = b_hi < NSB ? (b_hi + 1u) << SAMPLE_SH : 0x80000000u;  // first key above the bracket
-    const uint32_t shl = VEC == TAG_F32 ? 0u : 16u;  // keys of the 16-bit types have 16 zero bits below the pattern
+    // fp32: bins as fine as the bracket and a last digit of BITS3 bits allow.  16-bit types: a bin is one
+    // pattern (their keys have 16 zero bits below it), 2047 patterns upwards of lo, no last digit.
     const uint64_t width = hi > lo ? hi - lo : 1u;
-    shw = shl;
-    while (shw < shl + static_cast<uint32_t>(BITS3) && (static_cast<uint64_t>(NBW - 1) << shw) < width) ++shw;
+    shw = VEC == TAG_F32 ? 0u : 16u;
+    while (VEC == TAG_F32 && shw < static_cast<uint32_t>(BITS3) && (static_cast<uint64_t>(NBW - 1) << shw) < width) ++shw;
 }
 
 // DEPTH = register buffers of one tile each that the streaming loop rotates through, i.e. DEPTH - 1
@@ -996,7 +1043,7 @@ __global__ __launch_bounds__(BLOCK, DEPTH == 2 ? 4 : 2) void k_scan(Launch a) {
                                                         a.coarse1 + static_cast<size_t>(sg.chunk_begin) * NC1, sg.nchunks,
                                                         0, static_cast<uint32_t>(sg.k), smem, first_tile);
         lo = p1.B << SH1;  // 2^31 when nothing is kept (k = 0): no key reaches it
-        shw = SH1 - BITS3;
+        shw = VEC == TAG_F32 ? SH1 - BITS3 : 16;  // fp32: the bucket's 2^20 keys in 1024 bins; 16-bit: its 16 patterns in 16
         if (c == 0 && threadIdx.x == 0) {
             a.state[s].loB = lo;
             a.state[s].shwB = shw;
@@ -1097,14 +1144,14 @@ __global__ __launch_bounds__(BLOCK, DEPTH == 2 ? 4 : 2) void k_scan(Launch a) {
 // itself (every element at or above the window's lowest key, in index order: the same sequence).
 template <int VEC> struct ChunkSource {
     using R = typename Raw<VEC>::type;
-    const int32_t *Li;
+    const int32_t *Li;   // the part's first list entry
     const R *Lv;
-    const R *x;          // the chunk's first input element
+    const R *x;          // the part's first input element
     uint32_t base;       // its index in the tensor
-    uint32_t len;        // entries: list entries, or the chunk's elements
+    uint32_t len;        // entries of the part: list entries, or input elements
     uint32_t lo;
     bool from_input;
-    // entry i: its raw pattern, and whether it is a candidate at all
+    // entry i of the part: its raw pattern, and whether it is a candidate at all
     __device__ __forceinline__ uint32_t raw(uint32_t i) const {
         return i < len ? static_cast<uint32_t>(from_input ? x[i] : Lv[i]) : 0u;
     }
@@ -1115,20 +1162,29 @@ template <int VEC> struct ChunkSource {
         return from_input ? static_cast<int32_t>(base + i) : (i < len ? Li[i] : 0);
     }
 };
+// Part `part` of `sub` of chunk g's candidates: the entries are cut into `sub` runs of whole list
+// tiles; the later parts of a short list are empty.
 template <int VEC>
-__device__ __forceinline__ ChunkSource<VEC> chunk_source(const Launch &a, const SegDesc &sg, int g, uint32_t lo) {
+__device__ __forceinline__ ChunkSource<VEC> chunk_source(const Launch &a, const SegDesc &sg, int g, uint32_t part,
+                                                         uint32_t sub, uint32_t lo) {
     using R = typename Raw<VEC>::type;
+    constexpr uint32_t LT = BLOCK * LU;
     ChunkSource<VEC> src;
     const int c = g - sg.chunk_begin;
     const int64_t beg = static_cast<int64_t>(c) * a.E;
     const int64_t end = (beg + a.E < sg.n) ? beg + a.E : sg.n;
     const uint32_t count = a.cnt[g];
     src.from_input = count > a.cap;
-    src.Li = a.L_idx + static_cast<size_t>(g) * a.cap;
-    src.Lv = static_cast<const R *>(a.L_val) + static_cast<size_t>(g) * a.cap;
-    src.x = static_cast<const R *>(sg.x) + beg;
-    src.base = static_cast<uint32_t>(beg);
-    src.len = src.from_input ? static_cast<uint32_t>(end - beg) : count;
+    const uint32_t entries = src.from_input ? static_cast<uint32_t>(end - beg) : count;
+    uint32_t per = (entries + sub - 1) / sub;
+    per = (per + LT - 1) / LT * LT;
+    const uint64_t first = static_cast<uint64_t>(per) * part;
+    const uint32_t off = first < entries ? static_cast<uint32_t>(first) : entries;
+    src.len = (first + per < entries) ? per : entries - off;
+    src.Li = a.L_idx + static_cast<size_t>(g) * a.cap + off;
+    src.Lv = static_cast<const R *>(a.L_val) + static_cast<size_t>(g) * a.cap + off;
+    src.x = static_cast<const R *>(sg.x) + beg + off;
+    src.base = static_cast<uint32_t>(beg) + off;
     src.lo = lo;
     return src;
 }
@@ -1143,7 +1199,8 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_refine(Launch a) {
     __shared__ uint32_t sm[2 * NW];
     __shared__ double smd[NW];
 
-    const int g = blockIdx.x;
+    const int g = blockIdx.x / a.sub;  // chunk
+    const uint32_t part = blockIdx.x % a.sub;
     const int s = find_segment(a, g);
     const SegDesc &sg = a.seg[s];
     const int c = g - sg.chunk_begin;
@@ -1151,7 +1208,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_refine(Launch a) {
     const uint32_t lo = spec ? a.state[s].loA : a.state[s].loB;
     const uint32_t shw = spec ? a.state[s].shwA : a.state[s].shwB;
     const uint32_t shl = VEC == TAG_F32 ? 0u : 16u;
-    const ChunkSource<VEC> src = chunk_source<VEC>(a, sg, g, lo);
+    const ChunkSource<VEC> src = chunk_source<VEC>(a, sg, g, part, a.sub, lo);
 
     // The first LU entries of every thread do not depend on the prologue: their loads are in flight
     // while it runs (a typical chunk has no more than these), issued behind its first loads.
@@ -1164,7 +1221,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_refine(Launch a) {
                                                 a.coarseW + static_cast<size_t>(sg.chunk_begin) * NCW, sg.nchunks, 0,
                                                 static_cast<uint32_t>(sg.k), h, first_entries);
     const uint32_t Bw = pw.B;  // NBW when nothing is kept
-    if (c == 0 && threadIdx.x == 0) {
+    if (c == 0 && part == 0 && threadIdx.x == 0) {
         a.state[s].Bw = Bw;
         a.state[s].c_gtw = pw.above;
     }
@@ -1195,16 +1252,16 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_refine(Launch a) {
         for (int j = 0; j < LU; ++j) count_entry(i0 + j * BLOCK + threadIdx.x, more[j]);
     }
     const double bsum = block_sum_f64(acc, smd);
-    if (threadIdx.x == 0) a.lerr[g] = bsum;
+    if (threadIdx.x == 0) a.lerr[blockIdx.x] = bsum;
     __syncthreads();
     flush_bins<NB3>(h3, a.G3 + s * NB3);
     __syncthreads();
     block_suffix_inplace<NB3>(h3, sm);
-    uint32_t *row = a.rows3 + static_cast<size_t>(g) * NB3;
+    uint32_t *row = a.rows3 + static_cast<size_t>(blockIdx.x) * NB3;
     for (int b = threadIdx.x; b < NB3; b += BLOCK) row[b] = h3[b];
     uint32_t deftot;
     block_incl_scan(def, sm, &deftot);
-    if (threadIdx.x == 0) a.ldef[g] = deftot;
+    if (threadIdx.x == 0) a.ldef[blockIdx.x] = deftot;
 }
 
 // k_emit.  Prologue: G3 -> the last digit B3 of the k-th key, hence the threshold key T and the tie
@@ -1214,7 +1271,8 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_refine(Launch a) {
 // kernels, in a fixed order.
 template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     using R = typename Raw<VEC>::type;
-    __shared__ uint32_t h[NB3];
+    // fp32: the last digit's histogram; 16-bit types: the global suffix sums of the window bins up to Bw
+    __shared__ uint32_t h[VEC == TAG_F32 ? NB3 : NBW + 1];
     __shared__ uint32_t wcnt[2][2][LU * NW];
     __shared__ uint32_t sm[2 * NW];
     __shared__ double smd[NW];
@@ -1222,17 +1280,19 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     __shared__ uint32_t s_off[2];
 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int g = blockIdx.x;
+    const uint32_t sub = VEC == TAG_F32 ? a.sub : 1u;  // 16-bit types: one workgroup per chunk (their counts are per chunk)
+    const int g = blockIdx.x / sub;  // chunk
+    const uint32_t part = blockIdx.x % sub;
     const int s = find_segment(a, g);
     const SegDesc &sg = a.seg[s];
     const int c = g - sg.chunk_begin;
     const bool spec = a.state[s].spec_held != 0;
     const uint32_t lo = spec ? a.state[s].loA : a.state[s].loB;
     const uint32_t shw = spec ? a.state[s].shwA : a.state[s].shwB;
-    const uint32_t shl = VEC == TAG_F32 ? 0u : 16u;
-    const uint32_t Bw = a.state[s].Bw, c_gtw = a.state[s].c_gtw;
     const uint32_t kout = static_cast<uint32_t>(sg.k);
-    const ChunkSource<VEC> src = chunk_source<VEC>(a, sg, g, lo);
+    const ChunkSource<VEC> src = chunk_source<VEC>(a, sg, g, part, sub, lo);
+    // the tensor's last chunk is the short one, and the last part of a chunk the shortest
+    const bool sums_error = c == sg.nchunks - 1 && part == sub - 1 && a.err_out != nullptr;
 
     uint32_t raw[LU];
     int32_t id[LU];
@@ -1244,70 +1304,153 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
             id[j] = src.index(i);
         }
     };
+    auto first_tile = [&]() { load_tile(0); };
 
-    // Prologue: last digit -> threshold key T and tie quota q.  The loads of the last digit's
-    // histogram go first, the chunk's first tile behind them (the wavefront's load counter is in order).
-    uint32_t B3, above3;
-    uint32_t my_bins[NB3 / BLOCK];  // raw counts of the last-digit bins this thread owns
+    // Prologue -> threshold key T, tie quota q, and per chunk the number of keys above T and equal to
+    // T among its candidates (gt_of / eq_of below).  The chunk's first tile is loaded behind the
+    // prologue's first loads (the wavefront's load counter is in order).
+    uint32_t T, q;
+    bool any_kept;
+    const uint32_t *cnt_rows;  // per-chunk rows of suffix sums in which T's counts are entries t_bin and t_bin + 1
+    uint32_t row_len, t_bin, t_bins;
+    const uint32_t *extra_gt;  // per-chunk count that is above T whatever the row says (fp32: the higher window bins)
+    if (VEC == TAG_F32) {
+        // last digit (k_refine's G3) -> T.  All candidates of one last-digit bin share one key.
+        const uint32_t Bw = a.state[s].Bw, c_gtw = a.state[s].c_gtw;
+        uint32_t my_bins[NB3 / BLOCK];  // raw counts of the last-digit bins this thread owns
 #pragma unroll
-    for (int j = 0; j < NB3 / BLOCK; ++j) my_bins[j] = a.G3[s * NB3 + threadIdx.x * (NB3 / BLOCK) + j];
-    __builtin_amdgcn_sched_barrier(0);
-    load_tile(0);
-    __builtin_amdgcn_sched_barrier(0);
+        for (int j = 0; j < NB3 / BLOCK; ++j) my_bins[j] = a.G3[s * NB3 + threadIdx.x * (NB3 / BLOCK) + j];
+        __builtin_amdgcn_sched_barrier(0);
+        first_tile();
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int j = 0; j < NB3 / BLOCK; ++j) h[threadIdx.x * (NB3 / BLOCK) + j] = my_bins[j];
-    __syncthreads();
-    block_suffix_inplace<NB3>(h, sm);
-    block_pick_bucket<NB3>(h, kout - c_gtw, s_pick);
-    __syncthreads();
-    B3 = s_pick[0];
-    above3 = s_pick[1];
-    __syncthreads();
-    const bool any_kept = Bw < NBW && B3 < NB3;
-    const uint32_t bin_key = lo + (Bw << shw);  // lowest key of window bin Bw
-    const uint32_t T = any_kept ? bin_key + (B3 << shl) : 0xFFFFFFFFu;
-    const uint32_t q = kout - (c_gtw + above3);
+        for (int j = 0; j < NB3 / BLOCK; ++j) h[threadIdx.x * (NB3 / BLOCK) + j] = my_bins[j];
+        __syncthreads();
+        block_suffix_inplace<NB3>(h, sm);
+        block_pick_bucket<NB3>(h, kout - c_gtw, s_pick);
+        __syncthreads();
+        const uint32_t B3 = s_pick[0], above3 = s_pick[1];
+        __syncthreads();
+        any_kept = Bw < NBW && B3 < NB3;
+        const uint32_t bin_key = lo + (Bw << shw);  // lowest key of window bin Bw
+        T = any_kept ? bin_key + B3 : 0xFFFFFFFFu;
+        q = kout - (c_gtw + above3);
+        cnt_rows = a.rows3;
+        row_len = NB3;
+        t_bin = B3;
+        t_bins = NB3;
+        extra_gt = a.ldef;
 
-    // Error norm of the tensor, by its last chunk's workgroup only (that chunk is the short one).
-    // Everything it needs was stored by earlier kernels: per-chunk sums of squares below the window
-    // (k_scan), per-chunk sums of squares of the candidates below bin Bw (k_refine), and the counts of
-    // the candidates in bin Bw: all entries of one last-digit bin share one key, hence one square, so
-    // the dropped ones among them add count * value^2.  Fixed summation order.
-    if (c == sg.nchunks - 1 && a.err_out != nullptr) {
-        double part = 0.0;
-        for (int cc = threadIdx.x; cc < sg.nchunks; cc += BLOCK)
-            part += a.chunk_err[sg.chunk_begin + cc] + a.lerr[sg.chunk_begin + cc];
-#pragma unroll
-        for (int j = 0; j < NB3 / BLOCK; ++j) {
-            const uint32_t b = threadIdx.x * (NB3 / BLOCK) + j;
-            uint32_t dropped = 0;
-            if (b < B3 || B3 >= NB3) dropped = my_bins[j];
-            else if (b == B3) dropped = my_bins[j] - q;
-            if (dropped) {
-                const uint32_t key = bin_key + (b << shl);  // 16-bit types carry their pattern in the key's upper half
-                const double v = static_cast<double>(value_of<VEC>(VEC == TAG_F32 ? key : (key >> 16)));
-                part = fma(static_cast<double>(dropped) * v, v, part);
+        // Error norm of the tensor, by one workgroup.  Everything it needs was stored by earlier kernels:
+        // per-chunk sums of squares below the window (k_scan), per-chunk sums of squares of the candidates
+        // below bin Bw (k_refine), and the counts of the candidates in bin Bw by last digit: the dropped
+        // ones of a bin add count * value^2.  Fixed summation order.
+        if (sums_error) {
+            double sum = 0.0;
+            for (int cc = threadIdx.x; cc < sg.nchunks; cc += BLOCK) {
+                sum += a.chunk_err[sg.chunk_begin + cc];
+                for (uint32_t pp = 0; pp < sub; ++pp) sum += a.lerr[static_cast<size_t>(sg.chunk_begin + cc) * sub + pp];
             }
+#pragma unroll
+            for (int j = 0; j < NB3 / BLOCK; ++j) {
+                const uint32_t b = threadIdx.x * (NB3 / BLOCK) + j;
+                uint32_t dropped = 0;
+                if (b < B3 || B3 >= NB3) dropped = my_bins[j];
+                else if (b == B3) dropped = my_bins[j] - q;
+                if (dropped) {
+                    const double v = static_cast<double>(value_of<VEC>(bin_key + b));
+                    sum = fma(static_cast<double>(dropped) * v, v, sum);
+                }
+            }
+            const double tot = block_sum_f64(sum, smd);
+            if (threadIdx.x == 0) a.err_out[s] = static_cast<float>(sqrt(tot));
         }
-        const double tot = block_sum_f64(part, smd);
-        if (threadIdx.x == 0) a.err_out[s] = static_cast<float>(sqrt(tot));
+    } else {
+        // 16-bit types: a window bin is one pattern (the window's shift is the 16 zero bits below the
+        // pattern), so the bin of the k-th key is the threshold itself and no last digit exists:
+        // k_refine is not launched.  The column sums of the chunks' window rows give the bin.
+        const ColumnPick pw = column_pick<NBW, NCW>(a.rowsW + static_cast<size_t>(sg.chunk_begin) * NBW,
+                                                    a.coarseW + static_cast<size_t>(sg.chunk_begin) * NCW, sg.nchunks,
+                                                    0, kout, h, first_tile);
+        const uint32_t Bw = pw.B;
+        any_kept = Bw < NBW;
+        T = any_kept ? lo + (Bw << shw) : 0xFFFFFFFFu;
+        q = kout - pw.above;
+        cnt_rows = a.rowsW;
+        row_len = NBW;
+        t_bin = Bw;
+        t_bins = NBW;
+        extra_gt = nullptr;
+
+        // Error norm: the squares below the window (k_scan) and, for every window bin below Bw and for
+        // the dropped part of bin Bw, count * value^2.  The counts are differences of the global suffix
+        // sums S[0 .. Bw + 1], which this one workgroup adds up from the chunks' rows: 64 columns at a
+        // time, eight row groups side by side.
+        if (sums_error) {
+            // nothing kept means k = 0, for which the window starts above every key: no candidates at all
+            const uint32_t ncols = any_kept ? Bw + 2 : 0u;  // S[Bw + 1] is the last one needed (0 past the last bin)
+            for (uint32_t b = threadIdx.x; b < NBW + 1; b += BLOCK) h[b] = 0;
+            __syncthreads();
+            const uint32_t col = threadIdx.x & 63, rg = threadIdx.x >> 6;
+            for (uint32_t c0 = 0; c0 < ncols && c0 < NBW; c0 += 64) {
+                const uint32_t b = c0 + col;
+                if (b < ncols && b < NBW) {
+                    const uint32_t *p = a.rowsW + static_cast<size_t>(sg.chunk_begin) * NBW + b;
+                    uint32_t sum = 0;
+                    for (int r0 = rg; r0 < sg.nchunks; r0 += NW * 8) {
+                        uint32_t v[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const int rr = r0 + u * NW;
+                            v[u] = rr < sg.nchunks ? p[static_cast<size_t>(rr) * NBW] : 0u;
+                        }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) sum += v[u];
+                    }
+                    atomicAdd(&h[b], sum);
+                }
+            }
+            __syncthreads();
+            double sum = 0.0;
+            for (int cc = threadIdx.x; cc < sg.nchunks; cc += BLOCK) sum += a.chunk_err[sg.chunk_begin + cc];
+            for (uint32_t b = threadIdx.x; any_kept && b <= Bw; b += BLOCK) {
+                uint32_t dropped = h[b] - h[b + 1];
+                if (b == Bw) dropped -= q;
+                if (dropped) {  // the open-ended last bin is never below Bw: a dropped bin is one pattern
+                    const double v = static_cast<double>(value_of<VEC>((lo + (b << shw)) >> 16));
+                    sum = fma(static_cast<double>(dropped) * v, v, sum);
+                }
+            }
+            const double tot = block_sum_f64(sum, smd);
+            if (threadIdx.x == 0) a.err_out[s] = static_cast<float>(sqrt(tot));
+            __syncthreads();
+        }
     }
 
-    // Output offsets of this chunk = scan over the earlier chunks of (#keys above T, #keys equal to T).
+    // Output offsets of this part = sums over the earlier chunks, and over the earlier parts of this
+    // chunk, of (#keys above T, #keys equal to T).  Thread t takes chunk t.
     {
-        uint32_t gt = 0, eq = 0;
+        uint32_t gt = 0, eq = 0, gt_mine = 0, eq_mine = 0;  // totals of chunk t; what its parts before `part` hold
         if (static_cast<int>(threadIdx.x) < sg.nchunks && any_kept) {
-            const uint32_t *r = a.rows3 + static_cast<size_t>(sg.chunk_begin + threadIdx.x) * NB3;
-            const uint32_t above = (B3 + 1 < NB3) ? r[B3 + 1] : 0u;
-            gt = a.ldef[sg.chunk_begin + threadIdx.x] + above;
-            eq = r[B3] - above;
+            for (uint32_t pp = 0; pp < sub; ++pp) {
+                const size_t e = static_cast<size_t>(sg.chunk_begin + threadIdx.x) * sub + pp;
+                const uint32_t *r = cnt_rows + e * row_len;
+                const uint32_t above = (t_bin + 1 < t_bins) ? r[t_bin + 1] : 0u;
+                const uint32_t g1 = (extra_gt != nullptr ? extra_gt[e] : 0u) + above, e1 = r[t_bin] - above;
+                if (pp < part) {
+                    gt_mine += g1;
+                    eq_mine += e1;
+                }
+                gt += g1;
+                eq += e1;
+            }
         }
         uint32_t tot;
         const uint32_t inc_gt = block_incl_scan(gt, sm, &tot);
         const uint32_t inc_eq = block_incl_scan(eq, sm, &tot);
         if (static_cast<int>(threadIdx.x) == c) {
-            s_off[0] = inc_gt - gt;
-            s_off[1] = inc_eq - eq;
+            s_off[0] = inc_gt - gt + gt_mine;
+            s_off[1] = inc_eq - eq + eq_mine;
         }
         __syncthreads();
     }
@@ -1825,9 +1968,9 @@ Carve carve(int64_t max_chunks, int64_t list_slots, int32_t S, adatopk_dtype dt)
     c.cpairA = take(sizeof(uint2) * max_chunks);
     c.cnt = take(sizeof(uint32_t) * max_chunks);
     c.chunk_err = take(sizeof(double) * max_chunks);
-    c.rows3 = take(sizeof(uint32_t) * NB3 * max_chunks);
-    c.ldef = take(sizeof(uint32_t) * max_chunks);
-    c.lerr = take(sizeof(double) * max_chunks);
+    c.rows3 = take(sizeof(uint32_t) * NB3 * max_chunks * MAXSUB);
+    c.ldef = take(sizeof(uint32_t) * max_chunks * MAXSUB);
+    c.lerr = take(sizeof(double) * max_chunks * MAXSUB);
     c.wire_err = take(sizeof(float) * static_cast<size_t>(S < 1 ? 1 : S));  // error norms on their way into message headers
     c.L_idx = take(sizeof(int32_t) * static_cast<size_t>(list_slots));
     c.L_val = take(static_cast<size_t>(elem_size(dt)) * static_cast<size_t>(list_slots));
@@ -1887,8 +2030,9 @@ template <int VEC> adatopk_status launch_batch(const Launch &a, int total_chunks
     launch(ST_HIST1, k_hist1<VEC>, grid, st, a);
     if (one_per_cu) launch(ST_SCAN, k_scan<VEC, false, 3>, grid, st, a);
     else launch(ST_SCAN, k_scan<VEC, false, 2>, grid, st, a);
-    launch(ST_REFINE, k_refine<VEC>, grid, st, a);
-    launch(ST_EMIT, k_emit<VEC>, grid, st, a);
+    const dim3 parts(total_chunks * (VEC == TAG_F32 ? a.sub : 1u));
+    if (VEC == TAG_F32) launch(ST_REFINE, k_refine<VEC>, parts, st, a);  // the 16-bit types have no last digit to refine
+    launch(ST_EMIT, k_emit<VEC>, parts, st, a);
     return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
 }
 
@@ -2034,6 +2178,7 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
         a.err_out = err_out ? err_out + s0 : nullptr;
         int32_t chunks = 0;
         bool speculate = false;
+        double densest = 0.0;  // largest keep fraction of the launch
         for (int32_t i = 0; i < a.S; ++i) {
             SegDesc &d = a.seg[i];
             const int32_t s = s0 + i;
@@ -2050,6 +2195,15 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
                 speculate = true;
             }
             chunks += d.nchunks;
+            if (n[s] > 0 && static_cast<double>(k[s]) / static_cast<double>(n[s]) > densest)
+                densest = static_cast<double>(k[s]) / static_cast<double>(n[s]);
+        }
+        // parts per chunk for the list kernels: a chunk's candidates are about a third more than its kept
+        // elements; a part gets about SUB_ENTRIES of them
+        {
+            const double per_chunk = 1.35 * densest * static_cast<double>(E);
+            int sub = static_cast<int>(per_chunk / SUB_ENTRIES) + 1;
+            a.sub = static_cast<uint32_t>(sub > MAXSUB ? MAXSUB : sub);
         }
         if (chunks > max_chunks || static_cast<int64_t>(chunks) * a.cap > list_slots) return ADATOPK_ERUNTIME;  // planner invariant
         const adatopk_status rc = (dt == ADATOPK_F32)    ? launch_batch<TAG_F32>(a, chunks, speculate, st)
