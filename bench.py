@@ -64,7 +64,10 @@ def write_traffic(fetch_db: str, write_db: str, copy_bytes: int) -> int:
         out = {}
         for name, value, count in con.execute(
                 "select kernel_name, avg(value), count(*) from %s group by kernel_name" % view):
-            short = name.replace("(anonymous namespace)::", "").replace("void ", "").split("(")[0].split("<")[0]
+            full = name.replace("(anonymous namespace)::", "").replace("void ", "").split("(")[0]
+            short = full.split("<")[0]
+            if short == "k_scan" and "true" in full:  # k_scan<dtype, speculative, depth>: the measuring build's stage names
+                short = "k_scan_spec"
             out[short] = (float(value), int(count))
         return out
 
@@ -395,6 +398,9 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run the plain copy kernel on the workload-sized buffer (the known-size kernel that "
                          "hardware-counter readings are scaled by)")
+    ap.add_argument("--min-timed", type=int, default=MIN_TIMED,
+                    help="launches behind every median (default %d; hardware-counter runs, where every dispatch is "
+                         "slow and only the counters matter, use fewer)" % MIN_TIMED)
     ap.add_argument("--write-traffic", nargs=2, metavar=("FETCH_DB", "WRITE_DB"),
                     help="no benchmark: read the results databases of two counter runs of the default workload "
                          "(rocprofv3 --pmc FETCH_SIZE / --pmc WRITE_SIZE -- python3 bench.py --calibrate-copy ...) and "
@@ -424,7 +430,7 @@ def main() -> int:
     bench = Bench(B, torch, np, w, graph_timed)
     S, n, k, esize = bench.S, bench.n, bench.k, bench.esize
     dense_bytes = n * esize
-    reps = max(args.steps, MIN_TIMED)
+    reps = max(args.steps, args.min_timed)
 
     # the contract's number: wall clock around exactly --steps steps, inputs rotating
     sec_per_step = bench.wall_clock(args.steps, args.warmup)
@@ -439,7 +445,7 @@ def main() -> int:
     step_us = bench.event_timed(bench.run, reps)
     # one buffer only (the input may then be served by the last-level cache): reported aside
     warm_us = bench.event_timed(lambda i: bench.run(0), reps)
-    stages = bench.stage_medians(reps) if not graph_timed else bench.stage_medians(MIN_TIMED)
+    stages = bench.stage_medians(reps)
     stage_us = {nm: v["median_us"] for nm, v in stages.items()}
 
     # the two calls of a step timed apart

@@ -90,7 +90,8 @@ constexpr int SAMPLE_ELEMS = 32768;   // elements of a tensor that the speculati
 constexpr int SAMPLE_SH = 18;         // sample histogram: bin = key >> SAMPLE_SH ...
 constexpr int NSB = 1 << (31 - SAMPLE_SH);  // ... 8192 bins, 4 to the binade's eighth (2.2 % in value)
 constexpr int LIST_DIV = 4;           // a chunk's candidate list holds up to a quarter of the chunk
-constexpr int MAXSUB = 8;             // parts that the list kernels cut a chunk's candidates into, at most
+constexpr int MAXSUB = 8;             // parts that the list kernels cut a chunk's candidates into, at most ...
+constexpr int MAXSUB_ONE = 4;         // ... and for a single tensor, whose chunks are a quarter as long as a large batch's
 constexpr int SUB_ENTRIES = 8192;     // ... so that a part has about this many
 constexpr int MAXSEG = 64;            // segments per launch (the table travels as kernel arguments)
 constexpr int CTARGET = 512;          // chunks of a launch of several tensors, at most (two workgroups per compute unit)
@@ -1952,6 +1953,7 @@ struct Carve {
 
 // Workspace layout for up to max_chunks chunks and list_slots candidate-list slots.
 Carve carve(int64_t max_chunks, int64_t list_slots, int32_t S, adatopk_dtype dt) {
+    const int64_t max_parts = max_chunks * (S == 1 ? MAXSUB_ONE : MAXSUB);
     Carve c;
     size_t p = 0;
     auto take = [&](size_t bytes) {
@@ -1968,9 +1970,9 @@ Carve carve(int64_t max_chunks, int64_t list_slots, int32_t S, adatopk_dtype dt)
     c.cpairA = take(sizeof(uint2) * max_chunks);
     c.cnt = take(sizeof(uint32_t) * max_chunks);
     c.chunk_err = take(sizeof(double) * max_chunks);
-    c.rows3 = take(sizeof(uint32_t) * NB3 * max_chunks * MAXSUB);
-    c.ldef = take(sizeof(uint32_t) * max_chunks * MAXSUB);
-    c.lerr = take(sizeof(double) * max_chunks * MAXSUB);
+    c.rows3 = take(sizeof(uint32_t) * NB3 * max_parts);
+    c.ldef = take(sizeof(uint32_t) * max_parts);
+    c.lerr = take(sizeof(double) * max_parts);
     c.wire_err = take(sizeof(float) * static_cast<size_t>(S < 1 ? 1 : S));  // error norms on their way into message headers
     c.L_idx = take(sizeof(int32_t) * static_cast<size_t>(list_slots));
     c.L_val = take(static_cast<size_t>(elem_size(dt)) * static_cast<size_t>(list_slots));
@@ -2203,7 +2205,8 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
         {
             const double per_chunk = 1.35 * densest * static_cast<double>(E);
             int sub = static_cast<int>(per_chunk / SUB_ENTRIES) + 1;
-            a.sub = static_cast<uint32_t>(sub > MAXSUB ? MAXSUB : sub);
+            const int most = S == 1 ? MAXSUB_ONE : MAXSUB;  // what the workspace of this call was laid out for
+            a.sub = static_cast<uint32_t>(sub > most ? most : sub);
         }
         if (chunks > max_chunks || static_cast<int64_t>(chunks) * a.cap > list_slots) return ADATOPK_ERUNTIME;  // planner invariant
         const adatopk_status rc = (dt == ADATOPK_F32)    ? launch_batch<TAG_F32>(a, chunks, speculate, st)
