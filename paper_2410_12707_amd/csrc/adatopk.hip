@@ -87,8 +87,8 @@ constexpr int BITS2 = 31 - BITS1 - BITS3;  // the one-workgroup path selects on 
 constexpr int NB2 = 1 << BITS2;
 constexpr int SH2 = BITS3;
 constexpr int SAMPLE_ELEMS = 32768;   // elements of a tensor that the speculative pass looks at first
-constexpr int SAMPLE_SH = 18;         // sample histogram: bin = key >> SAMPLE_SH ...
-constexpr int NSB = 1 << (31 - SAMPLE_SH);  // ... 8192 bins, 4 to the binade's eighth (2.2 % in value)
+constexpr int SAMPLE_SH = 19;         // sample histogram: bin = key >> SAMPLE_SH ...
+constexpr int NSB = 1 << (31 - SAMPLE_SH);  // ... 4096 bins, 16 to the binade (4.4 % in value)
 constexpr int LIST_DIV = 4;           // a chunk's candidate list holds up to a quarter of the chunk
 constexpr int MAXSUB = 8;             // parts that the list kernels cut a chunk's candidates into, at most ...
 constexpr int MAXSUB_ONE = 4;         // ... and for a single tensor, whose chunks are a quarter as long as a large batch's
@@ -860,7 +860,7 @@ __device__ __forceinline__ void scan_tile(const uint32_t (&dw)[Stream<VEC>::SLOT
 }
 
 // The speculative pass's window, from a sample.  Every workgroup of the tensor reads the same
-// SAMPLE_ELEMS elements (runs of 64 dwords spread evenly over the tensor; after the first
+// SAMPLE_ELEMS elements (runs of 1 KB spread evenly over the tensor; after the first
 // workgroup they come from the cache), counts their keys in a histogram of NSB bins and takes from
 // it the keys at two ranks that the host derived from k: r_lo, a few standard deviations of the
 // sampling noise below where the k-th key is expected in the sample (the window's lowest key: the
@@ -875,7 +875,8 @@ __device__ __forceinline__ void scan_tile(const uint32_t (&dw)[Stream<VEC>::SLOT
 // handful of instructions: one compare against a floor below which nothing needs counting, one add.
 // The bins holding the two ranks are found while the suffix sums are formed in registers.
 constexpr int NSB_PADDED = NSB + NSB / 32;
-constexpr uint32_t SAMPLE_SKEW = 128;  // runs: the sample's runs are shifted by up to this many run lengths
+constexpr int SCAN_SMEM_WORDS = 2 * STAGE_CAP + NBW;  // k_scan's stage and window histogram; its prologue's scratch fits inside
+constexpr uint32_t SAMPLE_SKEW = 32;   // runs: the sample's runs are shifted by up to this many run lengths
 constexpr int SAMPLE_BATCH = 16;  // dword loads per thread and batch; the host picks 1, 2 or 4 batches (fp32: 8192 elements each)
 __device__ __forceinline__ uint32_t padded(uint32_t bin) { return bin + (bin >> 5); }
 template <int VEC, typename Prefetch>
@@ -888,21 +889,26 @@ __device__ __forceinline__ void sample_window(const SegDesc &sg, uint32_t *hs, u
     const int lane = threadIdx.x & 63;
     const uint32_t w = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));  // in a scalar register
     const int nbatch = static_cast<int>(sg.sample_batches);           // uniform; 1 .. MAXB
-    // nbatch * SAMPLE_BATCH * NW runs of 64 consecutive dwords, a power of two
-    const int run_shift = __builtin_ctz(SAMPLE_BATCH * NW) + (nbatch >= 4 ? 2 : (nbatch >= 2 ? 1 : 0));
-    const uint64_t nruns = (static_cast<uint64_t>(sg.n) / EPD) / 64;  // at least as many as sampled: the host checks the size
-    const uint32_t *x = static_cast<const uint32_t *>(sg.x) + lane;
+    // 16-byte loads: a run is 64 lanes x 16 bytes = 1 KB; nbatch * (SAMPLE_BATCH / 4) * NW runs, a power of two
+    constexpr int QUADS = SAMPLE_BATCH / 4;
+    const int run_shift = __builtin_ctz(QUADS * NW) + (nbatch >= 4 ? 2 : (nbatch >= 2 ? 1 : 0));
+    const uint64_t nruns = (static_cast<uint64_t>(sg.n) / EPD) / 256;  // far more than are sampled: the host checks the size
+    const dword4 *x = static_cast<const dword4 *>(sg.x) + lane;
     uint32_t v[MAXB][SAMPLE_BATCH];
 #pragma unroll
     for (int b = 0; b < MAXB; ++b)
         if (b < nbatch) {
 #pragma unroll
-            for (int j = 0; j < SAMPLE_BATCH; ++j) {
+            for (int j = 0; j < QUADS; ++j) {
                 // evenly spaced, plus a small run-dependent offset: an even spacing alone can put every
                 // run on the same memory channel
-                const uint32_t r = static_cast<uint32_t>(b * SAMPLE_BATCH + j) * NW + w;
+                const uint32_t r = static_cast<uint32_t>(b * QUADS + j) * NW + w;
                 const uint64_t run = ((static_cast<uint64_t>(r) * (nruns - SAMPLE_SKEW)) >> run_shift) + (r * 37u) % SAMPLE_SKEW;
-                v[b][j] = x[run * 64];
+                const dword4 q = x[run * 64];
+                v[b][4 * j] = q.x;
+                v[b][4 * j + 1] = q.y;
+                v[b][4 * j + 2] = q.z;
+                v[b][4 * j + 3] = q.w;
             }
         }
     __builtin_amdgcn_sched_barrier(0);
@@ -998,14 +1004,14 @@ __global__ __launch_bounds__(BLOCK, DEPTH == 2 ? 4 : 2) void k_scan(Launch a) {
     static_assert(DEPTH == 2 || DEPTH == 3, "one or two tiles ahead");
     using R = typename Raw<VEC>::type;
     using St = Stream<VEC>;
-    // 32 KB used in turn as: the sample histogram or the bucket search's scratch (prologue), then the
+    // 24 KB used in turn as: the sample histogram or the bucket search's scratch (prologue), then the
     // stage (STAGE_CAP pairs) followed by the window histogram
-    __shared__ __attribute__((aligned(16))) uint32_t smem[NSB_PADDED];
+    __shared__ __attribute__((aligned(16))) uint32_t smem[SCAN_SMEM_WORDS];
     __shared__ uint32_t wcnt[2][NW];
     __shared__ uint32_t sm[2 * NW];
     __shared__ double smd[NW];
     __shared__ uint32_t s_pick[4];
-    static_assert(2 * STAGE_CAP + NBW <= NSB_PADDED && NC1 + 2 * FINE1 <= NSB_PADDED, "shared scratch fits");
+    static_assert(NSB_PADDED <= SCAN_SMEM_WORDS && NC1 + 2 * FINE1 <= SCAN_SMEM_WORDS, "shared scratch fits");
 
     const int g = blockIdx.x;
     const int s = find_segment(a, g);
@@ -1163,6 +1169,24 @@ template <int VEC> struct ChunkSource {
         return from_input ? static_cast<int32_t>(base + i) : (i < len ? Li[i] : 0);
     }
 };
+// Entries of part `part` of `sub` of chunk g's candidates (list entries, or the chunk's elements when
+// its list overflowed): the same cut as chunk_source below.  A short list leaves its later parts empty;
+// the list kernels return at once for those and skip what they would have stored.
+__device__ __forceinline__ uint32_t part_entries(const Launch &a, const SegDesc &sg, int g, uint32_t part, uint32_t sub) {
+    constexpr uint32_t LT = BLOCK * LU;
+    const int c = g - sg.chunk_begin;
+    const int64_t beg = static_cast<int64_t>(c) * a.E;
+    const int64_t end = (beg + a.E < sg.n) ? beg + a.E : sg.n;
+    const uint32_t count = a.cnt[g];
+    const uint32_t entries = count > a.cap ? static_cast<uint32_t>(end - beg) : count;
+    if (sub == 1) return entries;
+    uint32_t per = (entries + sub - 1) / sub;
+    per = (per + LT - 1) / LT * LT;
+    const uint64_t first = static_cast<uint64_t>(per) * part;
+    if (first >= entries) return 0u;
+    return (first + per < entries) ? per : entries - static_cast<uint32_t>(first);
+}
+
 // Part `part` of `sub` of chunk g's candidates: the entries are cut into `sub` runs of whole list
 // tiles; the later parts of a short list are empty.
 template <int VEC>
@@ -1210,6 +1234,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_refine(Launch a) {
     const uint32_t shw = spec ? a.state[s].shwA : a.state[s].shwB;
     const uint32_t shl = VEC == TAG_F32 ? 0u : 16u;
     const ChunkSource<VEC> src = chunk_source<VEC>(a, sg, g, part, a.sub, lo);
+    if (src.len == 0 && !(c == 0 && part == 0)) return;  // an empty part (the tensor's first part still reports Bw)
 
     // The first LU entries of every thread do not depend on the prologue: their loads are in flight
     // while it runs (a typical chunk has no more than these), issued behind its first loads.
@@ -1244,13 +1269,24 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_refine(Launch a) {
     };
 #pragma unroll
     for (int j = 0; j < LU; ++j) count_entry(j * BLOCK + threadIdx.x, first[j]);
-    // longer chunks (large k, many ties, a chunk read from the input): LU entries per thread at a time
-    for (uint32_t i0 = LU * BLOCK; i0 < src.len; i0 += LU * BLOCK) {
-        uint32_t more[LU];
+    // longer parts (large k, many ties, a chunk read from the input): LONG entries per thread at a time and the
+    // next LONG in flight while these are counted; with fewer loads in flight the loop waits for memory
+    // (a constant tensor, every chunk read from the input again: 78 us at 4 + 4 entries per thread)
+    if (LU * BLOCK < src.len) {
+        constexpr int LONG = 4 * LU;
+        uint32_t more[LONG];
 #pragma unroll
-        for (int j = 0; j < LU; ++j) more[j] = src.raw(i0 + j * BLOCK + threadIdx.x);
+        for (int j = 0; j < LONG; ++j) more[j] = src.raw((LU + j) * BLOCK + threadIdx.x);
+        for (uint32_t i0 = LU * BLOCK; i0 < src.len; i0 += LONG * BLOCK) {
+            uint32_t now[LONG];
 #pragma unroll
-        for (int j = 0; j < LU; ++j) count_entry(i0 + j * BLOCK + threadIdx.x, more[j]);
+            for (int j = 0; j < LONG; ++j) now[j] = more[j];
+#pragma unroll
+            for (int j = 0; j < LONG; ++j) more[j] = src.raw(i0 + (LONG + j) * BLOCK + threadIdx.x);  // 0 past the end, nothing loaded
+#pragma unroll
+            for (int j = 0; j < LONG; ++j)
+                if (i0 + j * BLOCK < src.len) count_entry(i0 + j * BLOCK + threadIdx.x, now[j]);  // uniform
+        }
     }
     const double bsum = block_sum_f64(acc, smd);
     if (threadIdx.x == 0) a.lerr[blockIdx.x] = bsum;
@@ -1278,7 +1314,7 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     __shared__ uint32_t sm[2 * NW];
     __shared__ double smd[NW];
     __shared__ uint32_t s_pick[2];
-    __shared__ uint32_t s_off[2];
+    __shared__ uint32_t s_off[4];
 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const uint32_t sub = VEC == TAG_F32 ? a.sub : 1u;  // 16-bit types: one workgroup per chunk (their counts are per chunk)
@@ -1350,7 +1386,9 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
             double sum = 0.0;
             for (int cc = threadIdx.x; cc < sg.nchunks; cc += BLOCK) {
                 sum += a.chunk_err[sg.chunk_begin + cc];
-                for (uint32_t pp = 0; pp < sub; ++pp) sum += a.lerr[static_cast<size_t>(sg.chunk_begin + cc) * sub + pp];
+                for (uint32_t pp = 0; pp < sub; ++pp)
+                    if (part_entries(a, sg, sg.chunk_begin + cc, pp, sub) != 0)  // an empty part stored nothing
+                        sum += a.lerr[static_cast<size_t>(sg.chunk_begin + cc) * sub + pp];
             }
 #pragma unroll
             for (int j = 0; j < NB3 / BLOCK; ++j) {
@@ -1432,8 +1470,10 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     // chunk, of (#keys above T, #keys equal to T).  Thread t takes chunk t.
     {
         uint32_t gt = 0, eq = 0, gt_mine = 0, eq_mine = 0;  // totals of chunk t; what its parts before `part` hold
+        uint32_t gt_own = 0, eq_own = 0;                    // what part `part` itself holds
         if (static_cast<int>(threadIdx.x) < sg.nchunks && any_kept) {
             for (uint32_t pp = 0; pp < sub; ++pp) {
+                if (part_entries(a, sg, sg.chunk_begin + threadIdx.x, pp, sub) == 0) continue;  // nothing stored for it, nothing in it
                 const size_t e = static_cast<size_t>(sg.chunk_begin + threadIdx.x) * sub + pp;
                 const uint32_t *r = cnt_rows + e * row_len;
                 const uint32_t above = (t_bin + 1 < t_bins) ? r[t_bin + 1] : 0u;
@@ -1441,6 +1481,10 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
                 if (pp < part) {
                     gt_mine += g1;
                     eq_mine += e1;
+                }
+                if (pp == part) {
+                    gt_own = g1;
+                    eq_own = e1;
                 }
                 gt += g1;
                 eq += e1;
@@ -1452,9 +1496,14 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
         if (static_cast<int>(threadIdx.x) == c) {
             s_off[0] = inc_gt - gt + gt_mine;
             s_off[1] = inc_eq - eq + eq_mine;
+            s_off[2] = gt_own;
+            s_off[3] = eq_own;
         }
         __syncthreads();
     }
+    // Nothing of this part is kept (no key above T in it, and its keys equal to T, if any, come after the
+    // quota is used up): sorted or constant tensors leave most parts like this.
+    if (src.len == 0 || (s_off[2] == 0 && (s_off[3] == 0 || s_off[1] >= q))) return;
     uint32_t run_gt = s_off[0], run_eq = s_off[1];
 
     const bool wide = a.idx64 != 0;
@@ -1463,15 +1512,17 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     int64_t *oi64 = op.i64;
     R *ov = static_cast<R *>(op.val);
 
+    // One tile (LU entries per thread) is compacted at a time; the tiles are loaded GROUP at a time, the
+    // next group in flight while this one is compacted: a long part (large k, many ties, a chunk read from
+    // the input) otherwise waits for memory at every tile.
     int buf = 0;
-    for (uint32_t t0 = 0; t0 < src.len; t0 += BLOCK * LU, buf ^= 1) {
-        if (t0 != 0) load_tile(t0);
+    auto compact_tile = [&](uint32_t t0, const uint32_t(&now_raw)[LU], const int32_t(&now_id)[LU]) {
         uint32_t pre_gt[LU], pre_eq[LU], cls[LU];  // cls: 0 not kept for sure, 1 equal to T, 2 above T
 #pragma unroll
         for (int j = 0; j < LU; ++j) {
             const uint32_t i = t0 + j * BLOCK + threadIdx.x;
             const bool valid = i < src.len;
-            const uint32_t key = key_of<VEC>(raw[j]);
+            const uint32_t key = key_of<VEC>(now_raw[j]);
             const bool gt = valid && key > T, eq = valid && key == T;
             cls[j] = gt ? 2u : (eq ? 1u : 0u);
             const uint64_t bg = __ballot(gt), be = __ballot(eq);
@@ -1494,14 +1545,48 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
             if (cls[j] == 2u || (cls[j] == 1u && eq_before < q)) {
                 const uint32_t pos = gt_before + (eq_before < q ? eq_before : q);
                 if (pos < kout) {
-                    if (wide) oi64[pos] = id[j];
-                    else oi[pos] = id[j];
-                    ov[pos] = static_cast<R>(raw[j]);
+                    if (wide) oi64[pos] = now_id[j];
+                    else oi[pos] = now_id[j];
+                    ov[pos] = static_cast<R>(now_raw[j]);
                 }
             }
         }
         run_gt += tg;
         run_eq += te;
+        buf ^= 1;
+    };
+    compact_tile(0, raw, id);  // the tile that was loaded behind the prologue
+    constexpr int GROUP = 4;
+    constexpr uint32_t LT = BLOCK * LU;
+    if (LT < src.len) {
+        uint32_t next_raw[GROUP][LU];
+        int32_t next_id[GROUP][LU];
+        auto load_group = [&](uint32_t t0) {
+#pragma unroll
+            for (int u = 0; u < GROUP; ++u)
+#pragma unroll
+                for (int j = 0; j < LU; ++j) {
+                    const uint32_t i = t0 + u * LT + j * BLOCK + threadIdx.x;
+                    next_raw[u][j] = src.raw(i);  // 0 past the end, nothing loaded
+                    next_id[u][j] = src.index(i);
+                }
+        };
+        load_group(LT);
+        for (uint32_t t0 = LT; t0 < src.len; t0 += GROUP * LT) {
+            uint32_t now_raw[GROUP][LU];
+            int32_t now_id[GROUP][LU];
+#pragma unroll
+            for (int u = 0; u < GROUP; ++u)
+#pragma unroll
+                for (int j = 0; j < LU; ++j) {
+                    now_raw[u][j] = next_raw[u][j];
+                    now_id[u][j] = next_id[u][j];
+                }
+            load_group(t0 + GROUP * LT);
+#pragma unroll
+            for (int u = 0; u < GROUP; ++u)
+                if (t0 + u * LT < src.len) compact_tile(t0 + u * LT, now_raw[u], now_id[u]);  // uniform
+        }
     }
 }
 
@@ -2058,9 +2143,9 @@ struct OutSpec {
 // expected among the k largest, with a standard deviation of at most sqrt(mu); the bracket is
 // SPEC_SIGMAS of them to either side.  The sample is the smallest of a quarter, half or all of
 // SAMPLE_ELEMS that expects SPEC_GOOD_EXPECTED kept elements, and the largest otherwise.
-bool speculation_ranks(int64_t n, int64_t k, adatopk_dtype dt, bool aligned4, uint32_t *r_lo, uint32_t *r_hi,
+bool speculation_ranks(int64_t n, int64_t k, adatopk_dtype dt, bool aligned16, uint32_t *r_lo, uint32_t *r_hi,
                        uint32_t *batches) {
-    if (!aligned4 || n < SPEC_MIN_N || k <= 0 || k > n / 100 * SPEC_MAX_KEEP_PERCENT) return false;
+    if (!aligned16 || n < SPEC_MIN_N || k <= 0 || k > n / 100 * SPEC_MAX_KEEP_PERCENT) return false;
     const int epd = 4 / elem_size(dt);
     const int max_batches = SAMPLE_ELEMS / BLOCK / epd / SAMPLE_BATCH;
     double mu = 0.0;
@@ -2192,7 +2277,8 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
             d.nchunks = n[s] > 0 ? static_cast<int32_t>((n[s] + E - 1) / E) : 1;  // an empty tensor keeps one (empty) chunk
             const bool aligned4 = reinterpret_cast<uintptr_t>(dense[s]) % 4 == 0;
             d.flags = aligned4 ? FLAG_ALIGNED4 : 0u;
-            if (speculation_ranks(n[s], k[s], dt, aligned4, &d.r_lo, &d.r_hi, &d.sample_batches)) {
+            const bool aligned16 = reinterpret_cast<uintptr_t>(dense[s]) % 16 == 0;  // the sample is read with 16-byte loads
+            if (speculation_ranks(n[s], k[s], dt, aligned16, &d.r_lo, &d.r_hi, &d.sample_batches)) {
                 d.flags |= FLAG_SPEC;
                 speculate = true;
             }

@@ -286,3 +286,61 @@ def test_error_norm_is_optional(n):
     si, sv, off, se = H.gpu_compress_segmented(xs, ks, want_err=False)
     qi, qv, qoff, _ = orc.compress_segmented(xs, ks)
     assert se is None and np.array_equal(si, qi) and np.array_equal(H.bits(sv), H.bits(qv))
+
+
+def _sampled_elements(n, esize):
+    """Element indices that the speculative scan may look at before it reads the tensor: runs of 1 KB,
+    evenly spaced with a small run-dependent shift, for each of its sample sizes (mirrors the kernel's
+    sampling on purpose: the test below plants values exactly there)."""
+    dwords = n * esize // 4
+    nruns = dwords // 256
+    idx = []
+    for nbatch in ((1, 2, 4) if esize == 4 else (1, 2)):
+        runs = nbatch * 4 * 8
+        shift = runs.bit_length() - 1
+        for r in range(runs):
+            run = ((r * (nruns - 32)) >> shift) + (r * 37) % 32
+            first = run * 1024 // esize
+            idx.append(np.arange(first, first + 1024 // esize))
+    return np.unique(np.concatenate(idx))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("scale", [64.0, 1.0 / 64.0])
+def test_speculation_misled_by_its_sample_falls_back_to_the_exact_select(dtype, scale):
+    # The one-read path brackets the k-th key from a sample and must never be trusted: here the sampled
+    # places hold values 64 times larger (the bracket lands far above the k-th key: too few candidates) or
+    # 64 times smaller (far below: the k-th key falls into the window's open-ended last bin) than the rest
+    # of the tensor.  The exact passes behind the speculative scan have to notice and redo the selection.
+    import torch
+
+    import gpu_harness as H
+    from paper_2410_12707_amd import binding as B
+
+    n, k = 4_200_003, 42_000
+    esize = 4 if dtype == "f32" else 2
+    x = wl.small_case("normal", n, seed=321, dtype="f32")
+    at = _sampled_elements(n, esize)
+    x[at] *= np.float32(scale)
+    if dtype == "bf16":
+        x = wl.f32_to_bf16_bits(x)
+    elif dtype == "f16":
+        x = x.astype(np.float16)
+    # (a 16-bit window spans 2047 patterns, 16 binades of bf16 but two of fp16, upwards of its lowest key:
+    # a bracket that is 64 times too low still contains the k-th key in bf16, at the price of candidate
+    # lists that overflow)
+    misled = 1 if (dtype == "bf16" and scale < 1.0) else 0
+    for data, expect_held in ((x, misled), (wl.small_case("normal", n, seed=321, dtype=dtype), 1)):
+        d = H.to_device(data)
+        idx = torch.full((k,), -7, dtype=torch.int32, device="cuda")
+        val = torch.zeros(k, dtype=d.dtype, device="cuda")
+        err = torch.full((1,), -1.0, dtype=torch.float32, device="cuda")
+        ws = B.new_workspace(n, 1, d.dtype)
+        B.adatopk_compress(d, k, idx, val, err, ws)
+        torch.cuda.synchronize()
+        # the tensor's state record opens the workspace; its seventh word says whether the speculation held
+        held = int(ws[:64].view(torch.int32)[6].item())
+        assert held == expect_held, (dtype, scale, held)
+        ri, rv, re = orc.compress(data, k)
+        assert np.array_equal(H.to_host(idx), ri) and np.array_equal(H.bits(H.to_host(val)), H.bits(rv))
+        assert H.same_err(H.to_host(err)[0], re, ERR_RTOL)
