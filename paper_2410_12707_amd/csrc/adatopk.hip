@@ -1269,24 +1269,13 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_refine(Launch a) {
     };
 #pragma unroll
     for (int j = 0; j < LU; ++j) count_entry(j * BLOCK + threadIdx.x, first[j]);
-    // longer parts (large k, many ties, a chunk read from the input): LONG entries per thread at a time and the
-    // next LONG in flight while these are counted; with fewer loads in flight the loop waits for memory
-    // (a constant tensor, every chunk read from the input again: 78 us at 4 + 4 entries per thread)
-    if (LU * BLOCK < src.len) {
-        constexpr int LONG = 4 * LU;
-        uint32_t more[LONG];
+    // longer parts (large k, many ties, a chunk read from the input): LU entries per thread at a time
+    for (uint32_t i0 = LU * BLOCK; i0 < src.len; i0 += LU * BLOCK) {
+        uint32_t more[LU];
 #pragma unroll
-        for (int j = 0; j < LONG; ++j) more[j] = src.raw((LU + j) * BLOCK + threadIdx.x);
-        for (uint32_t i0 = LU * BLOCK; i0 < src.len; i0 += LONG * BLOCK) {
-            uint32_t now[LONG];
+        for (int j = 0; j < LU; ++j) more[j] = src.raw(i0 + j * BLOCK + threadIdx.x);
 #pragma unroll
-            for (int j = 0; j < LONG; ++j) now[j] = more[j];
-#pragma unroll
-            for (int j = 0; j < LONG; ++j) more[j] = src.raw(i0 + (LONG + j) * BLOCK + threadIdx.x);  // 0 past the end, nothing loaded
-#pragma unroll
-            for (int j = 0; j < LONG; ++j)
-                if (i0 + j * BLOCK < src.len) count_entry(i0 + j * BLOCK + threadIdx.x, now[j]);  // uniform
-        }
+        for (int j = 0; j < LU; ++j) count_entry(i0 + j * BLOCK + threadIdx.x, more[j]);
     }
     const double bsum = block_sum_f64(acc, smd);
     if (threadIdx.x == 0) a.lerr[blockIdx.x] = bsum;
@@ -1512,17 +1501,15 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     int64_t *oi64 = op.i64;
     R *ov = static_cast<R *>(op.val);
 
-    // One tile (LU entries per thread) is compacted at a time; the tiles are loaded GROUP at a time, the
-    // next group in flight while this one is compacted: a long part (large k, many ties, a chunk read from
-    // the input) otherwise waits for memory at every tile.
     int buf = 0;
-    auto compact_tile = [&](uint32_t t0, const uint32_t(&now_raw)[LU], const int32_t(&now_id)[LU]) {
+    for (uint32_t t0 = 0; t0 < src.len; t0 += BLOCK * LU, buf ^= 1) {
+        if (t0 != 0) load_tile(t0);
         uint32_t pre_gt[LU], pre_eq[LU], cls[LU];  // cls: 0 not kept for sure, 1 equal to T, 2 above T
 #pragma unroll
         for (int j = 0; j < LU; ++j) {
             const uint32_t i = t0 + j * BLOCK + threadIdx.x;
             const bool valid = i < src.len;
-            const uint32_t key = key_of<VEC>(now_raw[j]);
+            const uint32_t key = key_of<VEC>(raw[j]);
             const bool gt = valid && key > T, eq = valid && key == T;
             cls[j] = gt ? 2u : (eq ? 1u : 0u);
             const uint64_t bg = __ballot(gt), be = __ballot(eq);
@@ -1545,48 +1532,14 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
             if (cls[j] == 2u || (cls[j] == 1u && eq_before < q)) {
                 const uint32_t pos = gt_before + (eq_before < q ? eq_before : q);
                 if (pos < kout) {
-                    if (wide) oi64[pos] = now_id[j];
-                    else oi[pos] = now_id[j];
-                    ov[pos] = static_cast<R>(now_raw[j]);
+                    if (wide) oi64[pos] = id[j];
+                    else oi[pos] = id[j];
+                    ov[pos] = static_cast<R>(raw[j]);
                 }
             }
         }
         run_gt += tg;
         run_eq += te;
-        buf ^= 1;
-    };
-    compact_tile(0, raw, id);  // the tile that was loaded behind the prologue
-    constexpr int GROUP = 4;
-    constexpr uint32_t LT = BLOCK * LU;
-    if (LT < src.len) {
-        uint32_t next_raw[GROUP][LU];
-        int32_t next_id[GROUP][LU];
-        auto load_group = [&](uint32_t t0) {
-#pragma unroll
-            for (int u = 0; u < GROUP; ++u)
-#pragma unroll
-                for (int j = 0; j < LU; ++j) {
-                    const uint32_t i = t0 + u * LT + j * BLOCK + threadIdx.x;
-                    next_raw[u][j] = src.raw(i);  // 0 past the end, nothing loaded
-                    next_id[u][j] = src.index(i);
-                }
-        };
-        load_group(LT);
-        for (uint32_t t0 = LT; t0 < src.len; t0 += GROUP * LT) {
-            uint32_t now_raw[GROUP][LU];
-            int32_t now_id[GROUP][LU];
-#pragma unroll
-            for (int u = 0; u < GROUP; ++u)
-#pragma unroll
-                for (int j = 0; j < LU; ++j) {
-                    now_raw[u][j] = next_raw[u][j];
-                    now_id[u][j] = next_id[u][j];
-                }
-            load_group(t0 + GROUP * LT);
-#pragma unroll
-            for (int u = 0; u < GROUP; ++u)
-                if (t0 + u * LT < src.len) compact_tile(t0 + u * LT, now_raw[u], now_id[u]);  // uniform
-        }
     }
 }
 
