@@ -404,6 +404,35 @@ __device__ __forceinline__ void hist_add(uint32_t *h, uint32_t bin, bool active)
     if (active) atomicAdd(&h[bin], 1u);
 }
 
+// Histogram counts of a wavefront that works through dense, ordered data (a chunk that is read
+// again from the input because nearly all of it are candidates: a constant tensor, sorted values):
+// the lanes then hit one bin after another, and hist_add's two ballots, leader search and four
+// branches per element are the whole cost of the pass.  A run keeps the current bin and the counts
+// owed to it in scalar registers; lanes on that bin cost one compare and one ballot, the LDS add
+// happens when the bin changes and in flush().  Lanes on neither the old nor the new bin of a step
+// add for themselves.  Every lane of the wavefront has to make every call (no divergent callers).
+struct BinRun {
+    uint32_t ref = 0xFFFFFFFFu;  // wave-uniform: the bin of the run (no bin is that large)
+    uint32_t pend = 0;           // wave-uniform: counts not yet added to it
+    __device__ __forceinline__ void flush(uint32_t *h) {
+        if (pend != 0 && (threadIdx.x & 63) == 0) atomicAdd(&h[ref], pend);
+        pend = 0;
+    }
+    __device__ __forceinline__ void add(uint32_t *h, uint32_t bin, bool active) {
+        const uint64_t act = __ballot(active);
+        const uint64_t same = __ballot(active && bin == ref);
+        pend += static_cast<uint32_t>(__popcll(same));
+        if (same != act) {  // wave-uniform: a lane is on another bin, the run moves there
+            flush(h);
+            const int leader = __ffsll(static_cast<unsigned long long>(act & ~same)) - 1;
+            ref = __builtin_amdgcn_readlane(bin, leader);
+            const uint64_t moved = __ballot(active && bin == ref);
+            pend = static_cast<uint32_t>(__popcll(moved));
+            if (active && bin != ref && !((same >> (threadIdx.x & 63)) & 1ull)) atomicAdd(&h[bin], 1u);
+        }
+    }
+};
+
 // Adds the non-zero bins of an LDS histogram into a global one.
 template <int NB> __device__ __forceinline__ void flush_bins(const uint32_t *h, uint32_t *G) {
     for (int b = threadIdx.x; b < NB; b += BLOCK) {
@@ -730,7 +759,7 @@ __device__ __forceinline__ void flush_stage(const uint2 *stage, uint32_t from, u
     }
 }
 
-template <int VEC, bool FAST>
+template <int VEC, bool FAST, bool RUNS>
 __device__ __forceinline__ void scan_tile(const uint32_t (&dw)[Stream<VEC>::SLOTS],
                                           const uint32_t (&valid)[Stream<VEC>::SLOTS], int64_t t0, uint32_t lo,
                                           uint32_t shw, uint32_t *hw, uint32_t *wcnt, uint2 *stage, uint32_t &running,
@@ -834,6 +863,44 @@ __device__ __forceinline__ void scan_tile(const uint32_t (&dw)[Stream<VEC>::SLOT
                 slot_base += __popcll(m[e][hh]);
             }
         }
+    } else if (RUNS) {
+        // A dense tile in the variant with one workgroup per compute unit, whose register budget has
+        // room for it: the stores only while the list has room, then the window bins by runs.
+        if (running < cap) {  // uniform
+#pragma unroll
+            for (int e = 0; e < SLOTS; ++e) {
+                uint32_t pos = slot_base;
+#pragma unroll
+                for (int hh = 0; hh < EPD; ++hh) pos = lanes_below_plus(m[e][hh], pos);
+#pragma unroll
+                for (int hh = 0; hh < EPD; ++hh) {
+                    if (keep[e][hh] && pos < cap) {
+                        Li[pos] = static_cast<int32_t>(i_lane + e * 64 * EPD + hh);
+                        Lv[pos] = static_cast<R>(elem_of<VEC>(dw[e], hh));
+                    }
+                    pos += keep[e][hh] ? 1u : 0u;
+                    slot_base += __popcll(m[e][hh]);
+                }
+            }
+        }
+        // A wavefront whose whole share of the tile is kept and sits in one bin (a constant tensor) adds once.
+        const uint32_t bin0 = __builtin_amdgcn_readfirstlane(window_bin(key_of<VEC>(elem_of<VEC>(dw[0], 0)), lo, shw));
+        uint32_t other = 0;
+#pragma unroll
+        for (int e = 0; e < SLOTS; ++e)
+#pragma unroll
+            for (int hh = 0; hh < EPD; ++hh) other |= window_bin(key_of<VEC>(elem_of<VEC>(dw[e], hh)), lo, shw) ^ bin0;
+        if (wc == 64u * SLOTS * EPD && __ballot(other != 0) == 0) {  // wave-uniform
+            if (lane == 0) atomicAdd(&hw[bin0], wc);
+        } else {
+            BinRun run;
+#pragma unroll
+            for (int e = 0; e < SLOTS; ++e)
+#pragma unroll
+                for (int hh = 0; hh < EPD; ++hh)
+                    run.add(hw, window_bin(key_of<VEC>(elem_of<VEC>(dw[e], hh)), lo, shw), keep[e][hh]);
+            run.flush(hw);
+        }
     } else {
 #pragma unroll
         for (int e = 0; e < SLOTS; ++e) {
@@ -925,7 +992,7 @@ __device__ __forceinline__ void sample_window(const SegDesc &sg, uint32_t *hs, u
     // Bin 0 (zeros and the smallest denormals) is never counted: a rank that falls into it is not
     // found, which puts the window's lower end at key 0 just the same, and a tensor that is mostly
     // zeros does not pile its lanes onto one word.
-    uint32_t mine = 0;
+    uint32_t mine = 0, least = 0xFFFFFFFFu;
 #pragma unroll
     for (int b = 0; b < MAXB; ++b)
         if (b < nbatch) {
@@ -935,6 +1002,7 @@ __device__ __forceinline__ void sample_window(const SegDesc &sg, uint32_t *hs, u
                 for (int hh = 0; hh < EPD; ++hh) {
                     const uint32_t key = key_of<VEC>(elem_of<VEC>(v[b][j], hh));
                     mine = key > mine ? key : mine;
+                    least = key < least ? key : least;
                 }
         }
     uint32_t floor_key = mine;
@@ -950,17 +1018,25 @@ __device__ __forceinline__ void sample_window(const SegDesc &sg, uint32_t *hs, u
     if (sg.r_lo > BLOCK) floor_key = 0;
     uint32_t floor_bin = floor_key >> SAMPLE_SH;
     floor_bin = floor_bin < 1 ? 1 : floor_bin;
+    // A thread whose sampled keys all lie in one bin (a constant tensor) adds them with one add:
+    // element by element the whole sample would go to one LDS word, one key after the other.
+    const uint32_t top_bin = mine >> SAMPLE_SH;
+    const bool one_bin = (least >> SAMPLE_SH) == top_bin;
+    if (one_bin) {
+        if (top_bin >= floor_bin) atomicAdd(&hs[padded(top_bin)], static_cast<uint32_t>(nbatch * SAMPLE_BATCH * EPD));
+    } else {
 #pragma unroll
-    for (int b = 0; b < MAXB; ++b)
-        if (b < nbatch) {
+        for (int b = 0; b < MAXB; ++b)
+            if (b < nbatch) {
 #pragma unroll
-            for (int j = 0; j < SAMPLE_BATCH; ++j)
+                for (int j = 0; j < SAMPLE_BATCH; ++j)
 #pragma unroll
-                for (int hh = 0; hh < EPD; ++hh) {
-                    const uint32_t bin = key_of<VEC>(elem_of<VEC>(v[b][j], hh)) >> SAMPLE_SH;
-                    if (bin >= floor_bin) atomicAdd(&hs[padded(bin)], 1u);
-                }
-        }
+                    for (int hh = 0; hh < EPD; ++hh) {
+                        const uint32_t bin = key_of<VEC>(elem_of<VEC>(v[b][j], hh)) >> SAMPLE_SH;
+                        if (bin >= floor_bin) atomicAdd(&hs[padded(bin)], 1u);
+                    }
+            }
+    }
     __syncthreads();
     // thread t owns bins [t * PER, (t + 1) * PER); higher bins hold larger keys
     uint32_t cnt[PER], own = 0;
@@ -1074,7 +1150,7 @@ __global__ __launch_bounds__(BLOCK, DEPTH == 2 ? 4 : 2) void k_scan(Launch a) {
     int64_t t0 = beg;
     int64_t rem = ntiles;
     auto tile = [&](const uint32_t(&dw)[St::SLOTS]) {
-        scan_tile<VEC, true>(dw, valid, t0, lo, shw, hw, wcnt[wb], stage, running, flushed, cap, Li, Lv, acc);
+        scan_tile<VEC, true, DEPTH == 3>(dw, valid, t0, lo, shw, hw, wcnt[wb], stage, running, flushed, cap, Li, Lv, acc);
         t0 += TILE;
         wb ^= 1;
     };
@@ -1126,7 +1202,7 @@ __global__ __launch_bounds__(BLOCK, DEPTH == 2 ? 4 : 2) void k_scan(Launch a) {
     }
     for (; t0 < end; t0 += TILE, wb ^= 1) {
         St::load_slow(sg.x, t0, end, cur, valid);
-        scan_tile<VEC, false>(cur, valid, t0, lo, shw, hw, wcnt[wb], stage, running, flushed, cap, Li, Lv, acc);
+        scan_tile<VEC, false, DEPTH == 3>(cur, valid, t0, lo, shw, hw, wcnt[wb], stage, running, flushed, cap, Li, Lv, acc);
     }
     __syncthreads();
     flush_stage<VEC>(stage, flushed, running, cap, lo, shw, hw, Li, Lv);
@@ -1214,12 +1290,143 @@ __device__ __forceinline__ ChunkSource<VEC> chunk_source(const Launch &a, const 
     return src;
 }
 
+// A part that is read from the input is long (a quarter of the chunk's elements were candidates, or
+// more), and a loop that loads LU entries per thread and then works on them moves 8 KB per
+// workgroup and memory round trip: 1.8 TB/s over the whole chip when every chunk is dense (a
+// constant tensor), and far less when only a few are (sorted data: the chunks at one end).  With one
+// workgroup per compute unit nothing else hides the round trips.  The list kernels therefore come
+// in two forms.  WIDE, for a launch with one workgroup per chunk and at most one per compute unit
+// (a single tensor, lists of one part): a part from the input is read as tiles of U 16-byte loads
+// per thread (thread t takes the t-th, (BLOCK + t)-th ... 16 bytes of the tile) with the next tiles'
+// loads in flight; what is left after the last whole tile goes through the entry loop.  Needs the
+// part to start on a 16-byte boundary (chunks are whole tiles, so this is the alignment of the
+// tensor's base).  Plain, for every other launch: several workgroups per compute unit hide the
+// round trips, and registers (occupancy) are worth more than wide tiles; entry loop only.
+constexpr int WIDE_U = 4;
+template <int VEC> struct Wide {
+    static constexpr int EPV = 16 / static_cast<int>(sizeof(typename Raw<VEC>::type));  // elements per load
+    static constexpr uint32_t ELEMS = BLOCK * WIDE_U * EPV;                              // elements per tile
+    // whole tiles of the part, 0 when it is not read this way
+    static __device__ __forceinline__ uint32_t tiles(const ChunkSource<VEC> &src) {
+        const bool ok = src.from_input && (reinterpret_cast<uintptr_t>(src.x) & 15u) == 0;
+        return ok ? src.len / ELEMS : 0u;
+    }
+    static __device__ __forceinline__ void load(const ChunkSource<VEC> &src, uint32_t tile, dword4 (&v)[WIDE_U]) {
+        const dword4 *p = reinterpret_cast<const dword4 *>(src.x) + static_cast<size_t>(tile) * (BLOCK * WIDE_U) + threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < WIDE_U; ++u) v[u] = __builtin_nontemporal_load(p + u * BLOCK);
+    }
+    // element e (0 .. EPV) of a load, as the raw pattern of one element
+    static __device__ __forceinline__ uint32_t elem(const dword4 &v, int e) {
+        const int epd = EPV / 4;
+        const uint32_t d = e / epd == 0 ? v.x : (e / epd == 1 ? v.y : (e / epd == 2 ? v.z : v.w));
+        return elem_of<VEC>(d, e % epd);
+    }
+};
+// That is k_refine's form, which only counts (WIDE_U loads per thread and tile, two tiles ahead).
+// k_emit also places what it keeps, and 16-byte loads would leave a wavefront's store with four
+// bytes every sixteen, in sixteen cache lines: its wide tiles (DENSE_SLOTS elements per thread) use
+// the streaming layout of the scan instead: a wavefront owns a contiguous eighth of the tile and
+// reads it 64 consecutive elements at a time, so consecutive lanes place consecutive elements, and
+// only the wavefronts' totals are exchanged per tile; one tile ahead, since a wait for loads cannot
+// pass the stores issued behind them (one counter, in order).  No alignment needed.
+constexpr int DENSE_SLOTS = 16;
+constexpr uint32_t DENSE_ELEMS = BLOCK * DENSE_SLOTS;
+
+// f(tile, registers of the tile) for the wide tiles [0, t_end) of a part, in order, with two tiles
+// of loads in flight behind the one worked on: three register buffers used in turn, the loop body
+// written out per buffer so that none is ever copied (a copy would wait for its loads).  b0 holds
+// tile 0 already.  Same shape as the streaming loop of the scan.
+template <int VEC, typename F>
+__device__ __forceinline__ void wide_tiles_three(const ChunkSource<VEC> &src, uint32_t t_end, dword4 (&b0)[WIDE_U], F &&f) {
+    using W = Wide<VEC>;
+    dword4 b1[WIDE_U], b2[WIDE_U];
+    uint32_t t = 0, rem = t_end;
+    if (rem == 0) return;
+    if (rem >= 2) W::load(src, 1, b1);
+    while (rem >= 5) {
+        W::load(src, t + 2, b2);
+        __builtin_amdgcn_sched_barrier(0);
+        f(t++, b0);
+        W::load(src, t + 2, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        f(t++, b1);
+        W::load(src, t + 2, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        f(t++, b2);
+        rem -= 3;
+    }
+    // one to four tiles left: b0 is loaded, b1 is if there are two
+    if (rem >= 3) W::load(src, t + 2, b2);
+    __builtin_amdgcn_sched_barrier(0);
+    f(t++, b0);
+    if (rem >= 2) {
+        if (rem >= 4) W::load(src, t + 2, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        f(t++, b1);
+        if (rem >= 3) f(t++, b2);
+        if (rem >= 4) f(t++, b0);
+    }
+}
+// f(tile, registers of the tile) for tiles [0, t_end) in order, one tile of loads ahead: two
+// register buffers of N words used in turn; load(tile, buffer) fills one.  b0 holds tile 0 already.
+template <int N, typename L, typename F>
+__device__ __forceinline__ void tiles_two(uint32_t t_end, uint32_t (&b0)[N], L &&load, F &&f) {
+    uint32_t b1[N];
+    uint32_t t = 0;
+    while (t + 2 <= t_end) {
+        load(t + 1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        f(t++, b0);
+        if (t + 1 < t_end) load(t + 1, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        f(t++, b1);
+    }
+    if (t < t_end) f(t, b0);
+}
+
+// k_refine's counts over the wide tiles of a part read from the input.  Out of line: inlined, its seven
+// copies of the tile body sit in the middle of the kernel and the path of an ordinary part (a list of a
+// few hundred entries, microseconds in all) pays for them in instruction fetch and register allocation.
+struct DenseCounts {
+    uint32_t def;  // candidates above bin Bw
+    double acc;    // squares of the candidates below bin Bw
+};
+template <int VEC>
+__device__ __attribute__((noinline)) DenseCounts refine_wide_tiles(const ChunkSource<VEC> src, uint32_t wide_tiles, uint32_t lo,
+                                                                   uint32_t shw, uint32_t Bw, uint32_t *h3) {
+    using WR = Wide<VEC>;
+    const uint32_t shl = VEC == TAG_F32 ? 0u : 16u;
+    const uint32_t in_bin = (1u << shw) - 1u;
+    DenseCounts out = {0u, 0.0};
+    dword4 cur[WIDE_U];
+    WR::load(src, 0, cur);
+    BinRun run;
+    wide_tiles_three<VEC>(src, wide_tiles, cur, [&](uint32_t, const dword4(&v)[WIDE_U]) {
+#pragma unroll
+        for (int u = 0; u < WIDE_U; ++u)
+#pragma unroll
+            for (int e = 0; e < WR::EPV; ++e) {
+                const uint32_t raw = WR::elem(v[u], e);
+                const uint32_t key = key_of<VEC>(raw);
+                const bool cand = key >= lo;
+                const uint32_t bin = window_bin(key, lo, shw);
+                out.def += (cand && bin > Bw) ? 1u : 0u;
+                run.add(h3, ((key - lo) & in_bin) >> shl, cand && bin == Bw);
+                const double xd = (cand && bin < Bw) ? static_cast<double>(value_of<VEC>(raw)) : 0.0;
+                out.acc = fma(xd, xd, out.acc);
+            }
+    });
+    run.flush(h3);
+    return out;
+}
+
 // k_refine.  Prologue (every workgroup of the tensor, redundantly): the column sums of the chunks'
 // window rows give the window bin Bw that holds the k-th key.  Then, over the chunk's candidates:
 // the last digit (the position inside bin Bw) of those in Bw is counted, globally (G3) and as a row
 // of suffix sums per chunk; candidates in higher bins are counted (kept whatever the last digit
 // is), the squares of those in lower bins are summed (dropped whatever it is).
-template <int VEC> __global__ __launch_bounds__(BLOCK) void k_refine(Launch a) {
+template <int VEC, bool WIDE> __global__ __launch_bounds__(BLOCK) void k_refine(Launch a) {
     __shared__ uint32_t h[NB3 > NCW + 2 * (NBW / NCW) ? NB3 : NCW + 2 * (NBW / NCW)];
     __shared__ uint32_t sm[2 * NW];
     __shared__ double smd[NW];
@@ -1267,10 +1474,19 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_refine(Launch a) {
         const double xd = (cand && bin < Bw) ? static_cast<double>(value_of<VEC>(raw)) : 0.0;
         acc = fma(xd, xd, acc);
     };
+    uint32_t i_next = LU * BLOCK;  // where the entry loop goes on
+    const uint32_t wide_tiles = WIDE ? Wide<VEC>::tiles(src) : 0u;  // uniform over the workgroup
+    if (WIDE && __builtin_expect(wide_tiles != 0, 0)) {
+        const DenseCounts dc = refine_wide_tiles<VEC>(src, wide_tiles, lo, shw, Bw, h3);
+        def = dc.def;
+        acc = dc.acc;
+        i_next = wide_tiles * Wide<VEC>::ELEMS;
+    } else {
 #pragma unroll
-    for (int j = 0; j < LU; ++j) count_entry(j * BLOCK + threadIdx.x, first[j]);
-    // longer parts (large k, many ties, a chunk read from the input): LU entries per thread at a time
-    for (uint32_t i0 = LU * BLOCK; i0 < src.len; i0 += LU * BLOCK) {
+        for (int j = 0; j < LU; ++j) count_entry(j * BLOCK + threadIdx.x, first[j]);
+    }
+    // longer parts (large k, many ties), the end of a part read from the input: LU entries per thread at a time
+    for (uint32_t i0 = i_next; i0 < src.len; i0 += LU * BLOCK) {
         uint32_t more[LU];
 #pragma unroll
         for (int j = 0; j < LU; ++j) more[j] = src.raw(i0 + j * BLOCK + threadIdx.x);
@@ -1290,12 +1506,93 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_refine(Launch a) {
     if (threadIdx.x == 0) a.ldef[blockIdx.x] = deftot;
 }
 
+// k_emit's placing over the whole dense tiles of a part read from the input; returns the counts of
+// keys above T and equal to T after them.  Out of line for the same reason as refine_wide_tiles.
+// Per slot the lane masks of "above T" and "equal to T" give a lane its two counts inside the
+// wavefront's run (two 16-bit counts in one word); the wavefronts exchange their totals once per tile
+// (totals: 2 * NW words of LDS, two buffers used in turn).
+template <int VEC>
+__device__ __attribute__((noinline)) uint2 emit_dense_tiles(const ChunkSource<VEC> src, uint32_t dense_tiles, uint32_t T, uint32_t q,
+                                                            uint32_t kout, uint32_t run_gt, uint32_t run_eq, bool no_gt,
+                                                            int32_t *oi, int64_t *oi64, typename Raw<VEC>::type *ov, bool wide,
+                                                            uint32_t *totals) {
+    using R = typename Raw<VEC>::type;
+    static_assert(DENSE_ELEMS < 65536, "two 16-bit counts travel in one word");
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    // element (slot j, this lane) of dense tile t of the part: wavefront w owns the w-th eighth of the tile
+    auto dense_entry = [&](uint32_t t, int j) { return t * DENSE_ELEMS + (static_cast<uint32_t>(w) * DENSE_SLOTS + j) * 64 + lane; };
+    auto dense_load = [&](uint32_t t, uint32_t(&r)[DENSE_SLOTS]) {
+        const R *p = src.x + dense_entry(t, 0);
+#pragma unroll
+        for (int j = 0; j < DENSE_SLOTS; ++j) r[j] = __builtin_nontemporal_load(p + j * 64);
+    };
+    uint32_t cur[DENSE_SLOTS];
+    dense_load(0, cur);
+    int buf = 0;
+    tiles_two<DENSE_SLOTS>(dense_tiles, cur, dense_load, [&](uint32_t t, const uint32_t(&r)[DENSE_SLOTS]) {
+        if (no_gt && run_eq >= q) return;  // uniform: nothing above T in the part and the quota of ties used up
+        uint32_t before[DENSE_SLOTS];  // (above T, equal to T) before this lane's element within the wavefront's run
+        uint32_t wave_run = 0;          // wave-uniform: the same over the slots done so far
+#pragma unroll
+        for (int j = 0; j < DENSE_SLOTS; ++j) {
+            const uint32_t key = key_of<VEC>(r[j]);
+            const uint64_t bg = __ballot(key > T), be = __ballot(key == T);
+            before[j] = wave_run + lanes_below(bg) + (lanes_below(be) << 16);
+            wave_run += static_cast<uint32_t>(__popcll(bg)) + (static_cast<uint32_t>(__popcll(be)) << 16);
+        }
+        uint32_t *tot = totals + buf * NW;
+        if (lane == 0) tot[w] = wave_run;
+        __syncthreads();
+        uint32_t lower, tile_total;  // wave-uniform
+        wave_counts(tot, lower, tile_total);
+        buf ^= 1;
+        const uint32_t tile_gt = tile_total & 0xFFFFu, tile_eq = tile_total >> 16;
+        const uint32_t first_pos = run_gt + run_eq;  // of the tile's first kept element while the quota lasts
+        if (tile_gt + tile_eq == DENSE_ELEMS && run_eq + tile_eq <= q && first_pos + DENSE_ELEMS <= kout) {
+            // Every element of the tile is kept (uniform): the tile goes out as it came in, which is
+            // what a constant tensor or the dense end of sorted data consists of.  The placing below
+            // costs some sixty instructions per element, and with one workgroup on the compute unit
+            // their issue is what the tile waits for.
+            const uint32_t in_tile = dense_entry(0, 0);
+            const int32_t index0 = static_cast<int32_t>(src.base + dense_entry(t, 0));
+            if (wide) {
+#pragma unroll
+                for (int j = 0; j < DENSE_SLOTS; ++j) oi64[first_pos + in_tile + j * 64] = index0 + j * 64;
+            } else {
+#pragma unroll
+                for (int j = 0; j < DENSE_SLOTS; ++j) oi[first_pos + in_tile + j * 64] = index0 + j * 64;
+            }
+#pragma unroll
+            for (int j = 0; j < DENSE_SLOTS; ++j) ov[first_pos + in_tile + j * 64] = static_cast<R>(r[j]);
+        } else if (tile_total != 0) {  // uniform over the workgroup
+#pragma unroll
+            for (int j = 0; j < DENSE_SLOTS; ++j) {
+                const uint32_t key = key_of<VEC>(r[j]);
+                const uint32_t mine = lower + before[j];
+                const uint32_t gt_before = run_gt + (mine & 0xFFFFu), eq_before = run_eq + (mine >> 16);
+                if (key > T || (key == T && eq_before < q)) {
+                    const uint32_t pos = gt_before + (eq_before < q ? eq_before : q);
+                    if (pos < kout) {
+                        const int32_t index = static_cast<int32_t>(src.base + dense_entry(t, j));
+                        if (wide) oi64[pos] = index;
+                        else oi[pos] = index;
+                        ov[pos] = static_cast<R>(r[j]);
+                    }
+                }
+            }
+        }
+        run_gt += tile_gt;
+        run_eq += tile_eq;
+    });
+    return make_uint2(run_gt, run_eq);
+}
+
 // k_emit.  Prologue: G3 -> the last digit B3 of the k-th key, hence the threshold key T and the tie
 // quota q; output offsets of the chunk from the rows of the earlier chunks.  Stable compaction of
 // the chunk's candidates into idx_out / val_out (key > T, plus the first q keys equal to T).  The
 // tensor's last chunk also adds up the error norm from the partial sums stored by the earlier
 // kernels, in a fixed order.
-template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
+template <int VEC, bool WIDE> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     using R = typename Raw<VEC>::type;
     // fp32: the last digit's histogram; 16-bit types: the global suffix sums of the window bins up to Bw
     __shared__ uint32_t h[VEC == TAG_F32 ? NB3 : NBW + 1];
@@ -1502,7 +1799,16 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_emit(Launch a) {
     R *ov = static_cast<R *>(op.val);
 
     int buf = 0;
-    for (uint32_t t0 = 0; t0 < src.len; t0 += BLOCK * LU, buf ^= 1) {
+    // A part read from the input: its whole dense tiles first (out of line, see emit_dense_tiles).
+    const uint32_t dense_tiles = (WIDE && src.from_input) ? src.len / DENSE_ELEMS : 0u;  // uniform over the workgroup
+    if (WIDE && __builtin_expect(dense_tiles != 0, 0)) {
+        const uint2 run = emit_dense_tiles<VEC>(src, dense_tiles, T, q, kout, run_gt, run_eq, s_off[2] == 0, oi, oi64, ov, wide,
+                                                &wcnt[0][0][0]);
+        run_gt = run.x;
+        run_eq = run.y;
+        __syncthreads();  // the count array changes hands
+    }
+    for (uint32_t t0 = dense_tiles * DENSE_ELEMS; t0 < src.len; t0 += BLOCK * LU, buf ^= 1) {
         if (t0 != 0) load_tile(t0);
         uint32_t pre_gt[LU], pre_eq[LU], cls[LU];  // cls: 0 not kept for sure, 1 equal to T, 2 above T
 #pragma unroll
@@ -1818,10 +2124,22 @@ __device__ __forceinline__ void merge_span(const I *idx, const R *val, uint32_t 
     for (size_t i = va + nvec * 16 + threadIdx.x; i < byte_b; i += BLOCK) y[i] = 0;
     __syncthreads();  // also orders this workgroup's zero stores before its value stores
     R *out = reinterpret_cast<R *>(y);
+    // Four entries per thread at a time, loads first: a span that holds many entries (indices bunched
+    // together: a constant tensor keeps its first k elements, sorted data one end) would otherwise be a
+    // chain of one memory round trip per BLOCK entries.
     const uint32_t jb = s_range[1];
-    for (uint32_t j = s_range[0] + threadIdx.x; j < jb; j += BLOCK) {
-        const int64_t i = idx[j];
-        if (i >= ea && i < eb) out[i] = val[j];
+    for (uint32_t j0 = s_range[0] + threadIdx.x; j0 < jb; j0 += 4 * BLOCK) {
+        int64_t i[4];
+        R v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t j = j0 + u * BLOCK;
+            i[u] = j < jb ? static_cast<int64_t>(idx[j]) : -1;  // -1 lies in no span
+            v[u] = j < jb ? val[j] : R(0);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i[u] >= ea && i[u] < eb) out[i[u]] = v[u];
     }
 }
 
@@ -2071,8 +2389,13 @@ template <int VEC> adatopk_status launch_batch(const Launch &a, int total_chunks
     if (one_per_cu) launch(ST_SCAN, k_scan<VEC, false, 3>, grid, st, a);
     else launch(ST_SCAN, k_scan<VEC, false, 2>, grid, st, a);
     const dim3 parts(total_chunks * (VEC == TAG_F32 ? a.sub : 1u));
-    if (VEC == TAG_F32) launch(ST_REFINE, k_refine<VEC>, parts, st, a);  // the 16-bit types have no last digit to refine
-    launch(ST_EMIT, k_emit<VEC>, parts, st, a);
+    if (one_per_cu && parts.x == grid.x) {  // one workgroup per chunk, at most one per compute unit: see Wide
+        if constexpr (VEC == TAG_F32) launch(ST_REFINE, k_refine<VEC, true>, parts, st, a);  // the 16-bit types have no last digit to refine
+        launch(ST_EMIT, k_emit<VEC, true>, parts, st, a);
+    } else {
+        if constexpr (VEC == TAG_F32) launch(ST_REFINE, k_refine<VEC, false>, parts, st, a);
+        launch(ST_EMIT, k_emit<VEC, false>, parts, st, a);
+    }
     return hipGetLastError() == hipSuccess ? ADATOPK_OK : ADATOPK_ERUNTIME;
 }
 

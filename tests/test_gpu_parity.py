@@ -62,6 +62,27 @@ def test_misaligned_base_pointer(dtype):
         check_one(x, n // 50, offset_elems=off, label="offset %d" % off)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_dense_chunks_of_a_large_tensor_are_read_again_from_the_input(dtype):
+    # One tensor of 11M elements: chunks of 40960+ elements, i.e. five and more tiles each.  Where more
+    # than a quarter of a chunk are candidates its list overflows and the later kernels read the chunk
+    # from the input again, tile after tile with loads in flight ahead (every branch of those loops
+    # needs five tiles or more).  Constant tensor: every chunk, the quota of ties ends inside a tile.
+    # Sorted: only the chunks at one end.  Clipped: ties at the largest value, spread over all chunks.
+    n = 11_000_013
+    rng = np.random.Generator(np.random.PCG64(17))
+    clipped = np.clip(rng.standard_normal(n, dtype=np.float32), -0.5, 0.5)
+    cases = [("all_equal", wl.small_case("all_equal", n, 3, dtype), n // 100 + 5),
+             ("descending", wl.small_case("descending", n, 3, dtype), n // 100),
+             ("ascending", wl.small_case("ascending", n, 3, dtype), n // 64 + 1),
+             ("clipped", clipped if dtype == "f32" else (wl.f32_to_bf16_bits(clipped) if dtype == "bf16"
+                                                         else clipped.astype(np.float16)), n // 50)]
+    for name, x, k in cases:
+        check_one(x, k, label="%s %s" % (name, dtype))
+    # base pointer off the 16-byte grid: the counting kernel then takes the entry loop for the same chunks
+    check_one(cases[0][1][: n // 2], n // 300, offset_elems=1, label="all_equal offset 1 %s" % dtype)
+
+
 def test_ties_straddling_tiles_and_chunks():
     # the tied value sits on both sides of every tile and chunk boundary; the quota ends mid-way
     n = 300_000
