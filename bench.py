@@ -259,6 +259,9 @@ def micro_batch_pipeline(bench, n_b=4, rounds=25, pair_matrix=False):
     memory, where a network stack would pick it up.  Serial: both on one stream.  Overlapped: the copy
     of micro-batch j runs on a second stream while the next micro-batches are compressed (n_b message buffers).
 
+    In the overlapped form the host waits for a message buffer's copy before it enqueues the compress that
+    fills the buffer again, so it is never more than n_b micro-batches ahead of the GPU (a sender with n_b
+    buffers has to; run far ahead, the enqueue calls themselves were seen to get 2.3 times slower for whole runs).
     The overlapped form is bound by the host, not by the GPU: one micro-batch costs the host six kernel
     launches, two event records, two cross-stream waits and one asynchronous copy, 60 to 73 us of enqueue
     time against about 50 us of GPU time per micro-batch, so the time the host spends in the loop is
@@ -288,8 +291,11 @@ def micro_batch_pipeline(bench, n_b=4, rounds=25, pair_matrix=False):
         t0 = time.perf_counter()
         for j in range(n_b * reps):
             b = j % nbuf
+            if copy is not None and j >= nbuf:
+                freed[b].synchronize()  # the sender owns n_b message buffers: it waits for one before it fills it again
             with torch.cuda.stream(comp):
-                comp.wait_event(freed[b])
+                if copy is None or j < nbuf:
+                    comp.wait_event(freed[b])
                 B.adatopk_compress_wire(xs[j % len(xs)][0], k, 4, float(n) / max(k, 1), wire[b], ws)
                 done[b].record(comp)
             with torch.cuda.stream(copy if copy is not None else comp):
@@ -406,6 +412,59 @@ def other_config_line(B, torch, np, wl, orc, name):
     return line
 
 
+def value_structures(B, torch, np, wl, n=32 * 1024 * 768, reps=30):
+    """Compress + decompress of one fp32 tensor of config 2's size at k = 1 % for value structures that a
+    radix select or a compaction can be slow on (constant, all zero, sorted, few distinct values, one narrow
+    bucket, mostly zeros) beside the two benign ones.  Per structure: the median step (event pairs), whether the
+    sample-based window held, and the median duration of every kernel (measuring build)."""
+    k = n // 100
+    rng = np.random.Generator(np.random.PCG64(5))
+    kinds = {"normal": lambda: rng.standard_normal(n, dtype=np.float32),
+             "uniform": lambda: rng.random(n, dtype=np.float32),
+             "few_levels": lambda: wl.small_case("few_levels", n, 3),
+             "mostly_zero_97pct": lambda: wl.small_case("sparse", n, 3),
+             "ascending": lambda: np.arange(1, n + 1, dtype=np.float32),
+             "descending": lambda: np.arange(n, 0, -1, dtype=np.float32),
+             "one_bucket": lambda: (1.0 + rng.random(n, dtype=np.float32) * 0.08).astype(np.float32),
+             "all_equal": lambda: np.full(n, 1.5, dtype=np.float32),
+             "all_zero": lambda: np.zeros(n, dtype=np.float32)}
+    idx = torch.empty(k, dtype=torch.int32, device="cuda")
+    val = torch.empty(k, device="cuda")
+    err = torch.empty(1, device="cuda")
+    y = torch.empty(n, device="cuda")
+    ws = B.new_workspace(n, 1, torch.float32)
+    out = []
+    for kind, make in kinds.items():
+        x = torch.from_numpy(make()).cuda()
+
+        def step():
+            B.adatopk_compress(x, k, idx, val, err, ws)
+            B.adatopk_decompress_sorted(idx, val, k, y)
+
+        for _ in range(5):
+            step()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        torch.cuda.synchronize()
+        for a, b in evs:
+            a.record()
+            step()
+            b.record()
+        torch.cuda.synchronize()
+        us = median([a.elapsed_time(b) * 1e3 for a, b in evs])
+        held = int(ws[:64].view(torch.int32)[6].item())  # the tensor's state record: did the sample-based window hold
+        seen = {}
+        with B.measuring():
+            for _ in range(10):
+                step()
+                for name, ms in zip(B.measure_stage_names(), B.measure_read()):
+                    if ms >= 0:
+                        seen.setdefault(name, []).append(ms * 1e3)
+        out.append({"values": kind, "step_us_median": round(us, 1), "sample_window_held": bool(held),
+                    "stage_us": {name: round(median(v), 1) for name, v in seen.items()}})
+        del x
+    return {"n": n, "k": k, "dtype": "f32", "structures": out}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -428,6 +487,9 @@ def main() -> int:
     ap.add_argument("--stream-pairs", action="store_true",
                     help="no benchmark line: time the micro-batch pipeline (compress on one stream, message copies on "
                          "another) for every pair of eight streams and print the matrix")
+    ap.add_argument("--value-structures", action="store_true",
+                    help="no benchmark line: compress + decompress of a 25 M-element fp32 tensor at k = 1 %% for constant, "
+                         "zero, sorted, few-valued, narrow-range and mostly-zero tensors, with the kernels' durations")
     ap.add_argument("--min-timed", type=int, default=MIN_TIMED,
                     help="launches behind every median (default %d; hardware-counter runs, where every dispatch is "
                          "slow and only the counters matter, use fewer)" % MIN_TIMED)
@@ -455,6 +517,13 @@ def main() -> int:
     torch.cuda.set_device(0)
     B.load_library()  # fails loudly when the HIP library is not built
 
+    if args.value_structures:
+        r = value_structures(B, torch, np, wl)
+        print(json.dumps(r))
+        for row in r["structures"]:
+            print("%-18s %7.1f us  window held: %-5s %s" % (row["values"], row["step_us_median"], row["sample_window_held"],
+                                                          "  ".join("%s %.1f" % kv for kv in row["stage_us"].items())))
+        return 0
     w = load_workload(wl, args.config)
     graph_timed = args.config in ("small", "r18")
     bench = Bench(B, torch, np, w, graph_timed)

@@ -6,27 +6,32 @@
 // the launch is segmented: S tensors, each with its own k, one launch per pass for all.
 //
 // Method.  key(x) = bits(x) with the sign cleared (a 16-bit pattern, bf16 or fp16, is moved to
-// the upper half, so all types share one 31-bit key).  The exact k-th largest key T is found by a 3-level
-// MSD radix select with digits of 11 / 10 / 10 bits:
-//   k_hist1   one read of the input: per-chunk LDS histogram of the top digit; every chunk stores
-//             the suffix sums of its histogram (one row per chunk, plus every 32nd entry of it
-//             once more, contiguously).  No global atomics, nothing to zero beforehand
-//   k_gather  prologue (every block, redundantly): the column sums of the chunk rows are the
-//             global suffix sums; two steps (64 coarse columns, then the 32 fine columns of the
-//             interval found) give the digit bucket B1 that holds the k-th key, and the same fine
-//             sums restricted to the earlier chunks give this chunk's offset in the candidate
-//             list L.  Then the second read of the input: every element whose top digit is >= B1
-//             goes, in index order, into L (index, value), staged in LDS and written out with
-//             full-width stores; members of bucket B1 are histogrammed on the second digit (a row per chunk);
-//             squares of the elements below the bucket are summed in fp64 per chunk
-//   k_hist3   over L only (about k + the bucket population).  Prologue: column sums of those rows -> second digit B2.
-//             Histogram of the third digit of the entries matching (B1,B2) into G3, one row of
-//             suffix sums per list block
-//   k_emit    over L.  Prologue: G3 -> threshold key T and tie quota q; output offsets of the
-//             list block from the rows of the earlier blocks.  Stable compaction into idx_out /
-//             val_out (key > T, plus the first q keys equal to T).  One list block (an otherwise
-//             idle one when there is one) adds up the error norm from partials stored by the
-//             earlier kernels, in a fixed order
+// the upper half, so all types share one 31-bit key).  The exact k-th largest key T is found
+// with one read of the input when a sample of it predicts where T lies, and with two otherwise.
+// A tensor is cut into chunks of whole tiles, one workgroup per chunk in the kernels that read it:
+//   k_scan<spec>   (tensors of 2^20 elements and more, k up to 21 % of them)  Prologue, every
+//             workgroup alike: a histogram of 8 to 32 thousand sampled keys gives two ranks that
+//             bracket the k-th key by five standard deviations of the sampling noise; the key
+//             window starts at the lower one and spans the bracket in 2048 bins.  Then the one
+//             read of the input: every element with a key inside or above the window goes, in
+//             index order, into the candidate list of its chunk (LDS stage, full-width stores)
+//             and is counted in its window bin (one row of suffix sums per chunk); squares of the
+//             others are summed in fp64 per chunk.  A chunk with more candidates than its list
+//             holds (a quarter of its elements) is read from the input again by the later kernels
+//   k_hist1   sums the chunks' candidate counts: the guess holds when at least k keys reached the
+//             window and fewer than k lie above its bins.  Then it returns at once, and so does the
+//             kernel after it.  Otherwise (and for tensors that never speculate) it is the first of
+//             the two exact passes: per-chunk histogram of the top 11 key bits, rows of suffix sums
+//   k_scan<exact>  prologue: column sums of those rows -> the bucket of the k-th key, which is the
+//             window; then the same scan as above
+//   k_refine  (fp32 only) prologue: column sums of the window rows -> window bin Bw of the k-th
+//             key.  Over the chunk's candidates: histogram of the position inside bin Bw (at most
+//             10 bits: the last digit) into G3, one row of suffix sums per list part
+//   k_emit    prologue: G3 -> threshold key T and tie quota q (16-bit types: a window bin is one
+//             pattern, so T comes from the window rows and k_refine is not launched); output
+//             offsets from the rows of the earlier chunks.  Stable compaction into idx_out /
+//             val_out (key > T, plus the first q keys equal to T).  The tensor's last workgroup
+//             adds up the error norm from the partial sums the earlier kernels stored, in a fixed order
 // Cross-block order comes only from counts that an EARLIER kernel stored and that every block
 // of the next kernel scans for itself: no block waits for another block (no launch can hang),
 // no block needs a release fence (on this chip an agent-scope fence writes back the L2 of its
@@ -1849,6 +1854,33 @@ template <int VEC, bool WIDE> __global__ __launch_bounds__(BLOCK) void k_emit(La
     }
 }
 
+// ------------------------------------------------------------------ k = n
+// A tensor of which everything is kept (the rule of Sec. 5.2 gives a fast link the ratio 1, "no
+// compression") has nothing to select: its pairs are (i, x[i]) for every i and its error norm is 0.
+// One launch for all such tensors of a batch: the segment table's chunks are tiles here, one
+// workgroup per tile, 16 elements per thread, consecutive lanes on consecutive elements.
+template <int VEC> __global__ __launch_bounds__(BLOCK) void k_keep_all(Launch a) {
+    using R = typename Raw<VEC>::type;
+    const int g = blockIdx.x;
+    const int s = find_segment(a, g);
+    const SegDesc &sg = a.seg[s];
+    const int c = g - sg.chunk_begin;
+    const uint32_t beg = static_cast<uint32_t>(c) * TILE;
+    const uint32_t n = static_cast<uint32_t>(sg.n);
+    const uint32_t end = beg + TILE < n ? beg + TILE : n;
+    const bool wide = a.idx64 != 0;
+    const OutPtrs op = out_ptrs(a.idx_out, a.val_out, sg.out_off, n, wide, a.wire != 0, sizeof(R));
+    const R *x = static_cast<const R *>(sg.x);
+    R *ov = static_cast<R *>(op.val);
+    if (c == 0 && threadIdx.x == 0 && a.err_out != nullptr) a.err_out[s] = 0.0f;
+    if (wide) {
+        for (uint32_t i = beg + threadIdx.x; i < end; i += BLOCK) op.i64[i] = static_cast<int64_t>(i);
+    } else {
+        for (uint32_t i = beg + threadIdx.x; i < end; i += BLOCK) op.i32[i] = static_cast<int32_t>(i);
+    }
+    for (uint32_t i = beg + threadIdx.x; i < end; i += BLOCK) ov[i] = x[i];
+}
+
 // ------------------------------------------------------------------ small tensors: one launch
 // Many small messages (a few thousand elements each) are bound by launch latency in the
 // four-kernel path: about 5 us per kernel whatever the size.  Here one workgroup does the whole
@@ -2351,11 +2383,11 @@ void bounds_for(int64_t n_total, int32_t S, int64_t *max_chunks, int64_t *list_s
 // library), which gives every launch start / stop events carrying the timestamps of the dispatch
 // itself, as a profiler sees it; the product build launches plainly and keeps no state.
 enum Stage {
-    ST_SPEC, ST_HIST1, ST_SCAN, ST_REFINE, ST_EMIT, ST_FILL, ST_SCATTER, ST_MERGE, ST_HEADER, ST_SMALL, NSTAGE
+    ST_SPEC, ST_HIST1, ST_SCAN, ST_REFINE, ST_EMIT, ST_FILL, ST_SCATTER, ST_MERGE, ST_HEADER, ST_SMALL, ST_ALL, NSTAGE
 };
 #ifdef ADATOPK_MEASURE_BUILD
 const char *const kStageNames[NSTAGE] = {"k_scan_spec", "k_hist1", "k_scan", "k_refine", "k_emit",
-                                         "k_fill", "k_scatter", "k_merge", "k_wire_header", "k_small"};
+                                         "k_fill", "k_scatter", "k_merge", "k_wire_header", "k_small", "k_keep_all"};
 bool g_measure = false;
 bool g_events_made = false;
 hipEvent_t g_start[NSTAGE], g_stop[NSTAGE];
@@ -2506,15 +2538,23 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
         a.S = (S - s0 < MAXSEG) ? S - s0 : MAXSEG;
         // Chunk size of this launch: at most chunk_target() chunks in all, so that all workgroups are
         // resident at once (a few chunks beyond that would run as a second, nearly empty round).
+        // Tensors kept whole (k = n) take no part in the selection: they go through it as empty tensors
+        // (one empty chunk each) and get their pairs from k_keep_all below.
+        auto kept_whole = [&](int32_t s) { return n[s] > 0 && k[s] == n[s]; };
+        auto n_select = [&](int32_t s) { return kept_whole(s) ? static_cast<int64_t>(0) : n[s]; };
         int64_t n_batch = 0;
-        for (int32_t i = 0; i < a.S; ++i) n_batch += n[s0 + i];
+        int32_t whole = 0;
+        for (int32_t i = 0; i < a.S; ++i) {
+            n_batch += n_select(s0 + i);
+            whole += kept_whole(s0 + i) ? 1 : 0;
+        }
         const int64_t target = chunk_target(a.S);
         const int64_t E_fits = chunk_elems(n_batch, a.S, target);  // fits whatever the tensors' lengths are
         int64_t E = (n_batch + target - 1) / target;
         E = E < TILE ? TILE : (E + TILE - 1) / TILE * TILE;
         auto chunks_at = [&](int64_t e) {
             int64_t count = 0;
-            for (int32_t i = 0; i < a.S; ++i) count += n[s0 + i] > 0 ? (n[s0 + i] + e - 1) / e : 1;
+            for (int32_t i = 0; i < a.S; ++i) count += n_select(s0 + i) > 0 ? (n_select(s0 + i) + e - 1) / e : 1;
             return count;
         };
         while (E < E_fits && chunks_at(E) > target) E += TILE;
@@ -2547,20 +2587,21 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
             const int32_t s = s0 + i;
             d.x = dense[s];
             d.out_off = out_offset[s] + header;
-            d.n = static_cast<int32_t>(n[s]);
-            d.k = static_cast<int32_t>(k[s]);
+            const int64_t ns = n_select(s), ks = kept_whole(s) ? 0 : k[s];
+            d.n = static_cast<int32_t>(ns);
+            d.k = static_cast<int32_t>(ks);
             d.chunk_begin = chunks;
-            d.nchunks = n[s] > 0 ? static_cast<int32_t>((n[s] + E - 1) / E) : 1;  // an empty tensor keeps one (empty) chunk
+            d.nchunks = ns > 0 ? static_cast<int32_t>((ns + E - 1) / E) : 1;  // an empty tensor keeps one (empty) chunk
             const bool aligned4 = reinterpret_cast<uintptr_t>(dense[s]) % 4 == 0;
             d.flags = aligned4 ? FLAG_ALIGNED4 : 0u;
             const bool aligned16 = reinterpret_cast<uintptr_t>(dense[s]) % 16 == 0;  // the sample is read with 16-byte loads
-            if (speculation_ranks(n[s], k[s], dt, aligned16, &d.r_lo, &d.r_hi, &d.sample_batches)) {
+            if (speculation_ranks(ns, ks, dt, aligned16, &d.r_lo, &d.r_hi, &d.sample_batches)) {
                 d.flags |= FLAG_SPEC;
                 speculate = true;
             }
             chunks += d.nchunks;
-            if (n[s] > 0 && static_cast<double>(k[s]) / static_cast<double>(n[s]) > densest)
-                densest = static_cast<double>(k[s]) / static_cast<double>(n[s]);
+            if (ns > 0 && static_cast<double>(ks) / static_cast<double>(ns) > densest)
+                densest = static_cast<double>(ks) / static_cast<double>(ns);
         }
         // parts per chunk for the list kernels: a chunk's candidates are about a third more than its kept
         // elements; a part gets about SUB_ENTRIES of them
@@ -2571,10 +2612,30 @@ adatopk_status compress_impl(const void *const *dense, const int64_t *n, const i
             a.sub = static_cast<uint32_t>(sub > most ? most : sub);
         }
         if (chunks > max_chunks || static_cast<int64_t>(chunks) * a.cap > list_slots) return ADATOPK_ERUNTIME;  // planner invariant
-        const adatopk_status rc = (dt == ADATOPK_F32)    ? launch_batch<TAG_F32>(a, chunks, speculate, st)
-                                  : (dt == ADATOPK_BF16) ? launch_batch<TAG_BF16>(a, chunks, speculate, st)
-                                                         : launch_batch<TAG_F16>(a, chunks, speculate, st);
-        if (rc != ADATOPK_OK) return rc;
+        if (whole < a.S) {  // something to select
+            const adatopk_status rc = (dt == ADATOPK_F32)    ? launch_batch<TAG_F32>(a, chunks, speculate, st)
+                                      : (dt == ADATOPK_BF16) ? launch_batch<TAG_BF16>(a, chunks, speculate, st)
+                                                             : launch_batch<TAG_F16>(a, chunks, speculate, st);
+            if (rc != ADATOPK_OK) return rc;
+        }
+        if (whole > 0) {
+            // the same table with the kept-whole tensors at their true length, tile by tile, and the others empty
+            Launch w = a;
+            int32_t tiles = 0;
+            for (int32_t i = 0; i < a.S; ++i) {
+                SegDesc &d = w.seg[i];
+                const int32_t s = s0 + i;
+                d.n = kept_whole(s) ? static_cast<int32_t>(n[s]) : 0;
+                d.k = d.n;
+                d.chunk_begin = tiles;
+                d.nchunks = static_cast<int32_t>((static_cast<int64_t>(d.n) + TILE - 1) / TILE);
+                tiles += d.nchunks;
+            }
+            if (dt == ADATOPK_F32) launch(ST_ALL, k_keep_all<TAG_F32>, dim3(tiles), st, w);
+            else if (dt == ADATOPK_BF16) launch(ST_ALL, k_keep_all<TAG_BF16>, dim3(tiles), st, w);
+            else launch(ST_ALL, k_keep_all<TAG_F16>, dim3(tiles), st, w);
+            if (hipGetLastError() != hipSuccess) return ADATOPK_ERUNTIME;
+        }
     }
     return ADATOPK_OK;
 }
