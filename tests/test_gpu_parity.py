@@ -365,3 +365,29 @@ def test_speculation_misled_by_its_sample_falls_back_to_the_exact_select(dtype, 
         ri, rv, re = orc.compress(data, k)
         assert np.array_equal(H.to_host(idx), ri) and np.array_equal(H.bits(H.to_host(val)), H.bits(rv))
         assert H.same_err(H.to_host(err)[0], re, ERR_RTOL)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_midsize_tensors_value_structures_and_boundaries(dtype):
+    # between the one-launch path for small tensors and the sizes at which a sample of the tensor is taken
+    # first (2^20 elements): the exact two-pass select with tens to hundreds of chunks, around powers of two,
+    # with value structures whose candidate lists overflow (constant, few levels), keep counts of 0 and 1
+    for n, k in ((65_535, 600), (65_536, 655), (65_537, 1), (300_000, 6144), (300_000, 6145), (1_048_575, 6000),
+                 (1_048_576, 6000), (1_048_577, 6000), (524_288, 0), (200_001, 2000)):
+        for kind in ("normal", "few_levels", "all_equal", "sparse", "descending", "nonfinite"):
+            check_one(wl.small_case(kind, n, seed=n % 1000 + k, dtype=dtype), k, label="%s %s n=%d k=%d" % (kind, dtype, n, k))
+
+
+def test_midsize_tensors_in_one_segmented_call():
+    import gpu_harness as H
+
+    lens = [70_000, 0, 8192, 150_001, 65_536, 9_000, 400_000, 1, 262_144]
+    kinds = ["normal", "normal", "few_levels", "sparse", "normal", "all_equal", "normal", "normal", "descending"]
+    xs = [wl.small_case(kd, n, seed=60 + i) for i, (kd, n) in enumerate(zip(kinds, lens))]
+    ks = [700, 0, 8192, 1500, 650, 90, 4000, 1, 0]
+    gi, gv, off, ge = H.gpu_compress_segmented(xs, ks)
+    ri, rv, roff, re = orc.compress_segmented(xs, ks)
+    assert np.array_equal(off, roff) and np.array_equal(gi, ri) and np.array_equal(H.bits(gv), H.bits(rv))
+    for s in range(len(xs)):
+        assert H.same_err(ge[s], re[s], ERR_RTOL), (s, ge[s], re[s])
+    check_segmented_decompress(gi, gv, off, lens)
