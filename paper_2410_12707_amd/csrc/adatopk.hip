@@ -1333,8 +1333,9 @@ template <int VEC> struct Wide {
 // bytes every sixteen, in sixteen cache lines: its wide tiles (DENSE_SLOTS elements per thread) use
 // the streaming layout of the scan instead: a wavefront owns a contiguous eighth of the tile and
 // reads it 64 consecutive elements at a time, so consecutive lanes place consecutive elements, and
-// only the wavefronts' totals are exchanged per tile; one tile ahead, since a wait for loads cannot
-// pass the stores issued behind them (one counter, in order).  No alignment needed.
+// only the wavefronts' totals are exchanged per tile; two tiles ahead, so that a tile's loads are
+// issued before the stores of the tile two before it (one counter, in order: a wait for loads lets
+// everything issued before them drain).  No alignment needed.
 constexpr int DENSE_SLOTS = 16;
 constexpr uint32_t DENSE_ELEMS = BLOCK * DENSE_SLOTS;
 
@@ -1373,21 +1374,38 @@ __device__ __forceinline__ void wide_tiles_three(const ChunkSource<VEC> &src, ui
         if (rem >= 4) f(t++, b0);
     }
 }
-// f(tile, registers of the tile) for tiles [0, t_end) in order, one tile of loads ahead: two
-// register buffers of N words used in turn; load(tile, buffer) fills one.  b0 holds tile 0 already.
+// f(tile, registers of the tile) for tiles [0, t_end) in order, two tiles of loads ahead: three register
+// buffers of N words used in turn (see wide_tiles_three); load(tile, buffer) fills one.  b0 holds tile 0
+// already.  For a loop that also stores: the loads of a tile are issued before the stores of the tile two
+// before it, so the wait for them does not have to let those stores drain first.
 template <int N, typename L, typename F>
-__device__ __forceinline__ void tiles_two(uint32_t t_end, uint32_t (&b0)[N], L &&load, F &&f) {
-    uint32_t b1[N];
-    uint32_t t = 0;
-    while (t + 2 <= t_end) {
-        load(t + 1, b1);
+__device__ __forceinline__ void tiles_three(uint32_t t_end, uint32_t (&b0)[N], L &&load, F &&f) {
+    uint32_t b1[N], b2[N];
+    uint32_t t = 0, rem = t_end;
+    if (rem == 0) return;
+    if (rem >= 2) load(1, b1);
+    while (rem >= 5) {
+        load(t + 2, b2);
         __builtin_amdgcn_sched_barrier(0);
         f(t++, b0);
-        if (t + 1 < t_end) load(t + 1, b0);
+        load(t + 2, b0);
         __builtin_amdgcn_sched_barrier(0);
         f(t++, b1);
+        load(t + 2, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        f(t++, b2);
+        rem -= 3;
     }
-    if (t < t_end) f(t, b0);
+    if (rem >= 3) load(t + 2, b2);
+    __builtin_amdgcn_sched_barrier(0);
+    f(t++, b0);
+    if (rem >= 2) {
+        if (rem >= 4) load(t + 2, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        f(t++, b1);
+        if (rem >= 3) f(t++, b2);
+        if (rem >= 4) f(t++, b0);
+    }
 }
 
 // k_refine's counts over the wide tiles of a part read from the input.  Out of line: inlined, its seven
@@ -1408,6 +1426,27 @@ __device__ __attribute__((noinline)) DenseCounts refine_wide_tiles(const ChunkSo
     WR::load(src, 0, cur);
     BinRun run;
     wide_tiles_three<VEC>(src, wide_tiles, cur, [&](uint32_t, const dword4(&v)[WIDE_U]) {
+        // a wavefront whose whole share of the tile is one key (a constant tensor) counts it once
+        const uint32_t raw0 = __builtin_amdgcn_readfirstlane(WR::elem(v[0], 0));
+        uint32_t other = 0;
+#pragma unroll
+        for (int u = 0; u < WIDE_U; ++u)
+#pragma unroll
+            for (int e = 0; e < WR::EPV; ++e) other |= WR::elem(v[u], e) ^ raw0;
+        if (__ballot(other != 0) == 0) {  // wave-uniform
+            constexpr uint32_t PER_LANE = WIDE_U * WR::EPV;
+            const uint32_t key = key_of<VEC>(raw0);
+            const uint32_t bin = window_bin(key, lo, shw);
+            if (key >= lo) {
+                if (bin > Bw) out.def += PER_LANE;
+                if (bin == Bw && (threadIdx.x & 63) == 0) atomicAdd(&h3[((key - lo) & in_bin) >> shl], 64u * PER_LANE);
+                if (bin < Bw) {
+                    const double xd = static_cast<double>(value_of<VEC>(raw0));
+                    out.acc = fma(static_cast<double>(PER_LANE) * xd, xd, out.acc);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int u = 0; u < WIDE_U; ++u)
 #pragma unroll
@@ -1534,7 +1573,7 @@ __device__ __attribute__((noinline)) uint2 emit_dense_tiles(const ChunkSource<VE
     uint32_t cur[DENSE_SLOTS];
     dense_load(0, cur);
     int buf = 0;
-    tiles_two<DENSE_SLOTS>(dense_tiles, cur, dense_load, [&](uint32_t t, const uint32_t(&r)[DENSE_SLOTS]) {
+    tiles_three<DENSE_SLOTS>(dense_tiles, cur, dense_load, [&](uint32_t t, const uint32_t(&r)[DENSE_SLOTS]) {
         if (no_gt && run_eq >= q) return;  // uniform: nothing above T in the part and the quota of ties used up
         uint32_t before[DENSE_SLOTS];  // (above T, equal to T) before this lane's element within the wavefront's run
         uint32_t wave_run = 0;          // wave-uniform: the same over the slots done so far
