@@ -105,7 +105,9 @@ constexpr int CTARGET = 512;          // chunks of a launch of several tensors, 
 constexpr int CTARGET_ONE = 256;
 constexpr int64_t SPEC_MIN_N = 1 << 20;    // tensors below this are not worth a speculative pass
 constexpr double SPEC_MIN_EXPECTED = 32.0; // ... nor are keep counts that leave fewer than this many kept elements in the largest sample
-constexpr double SPEC_GOOD_EXPECTED = 96.0; // a smaller sample will do when it still expects this many
+constexpr double SPEC_GOOD_EXPECTED = 96.0; // a smaller sample will do when it still expects this many (fp32)
+constexpr double SPEC_GOOD_EXPECTED_16 = 64.0; // 16-bit types: their sample costs twice the instructions per dword, and the wider window
+                                              // of a smaller sample costs them nothing (a window bin is one pattern, no last digit to refine)
 constexpr double SPEC_SIGMAS = 5.0;        // width of the sample's rank bracket in standard deviations
 constexpr int64_t SPEC_MAX_KEEP_PERCENT = 21;  // beyond this the candidates (k and the bracket's margin) may not fit a quarter of a chunk
 constexpr size_t MERGE_SPANS = 1024;       // output spans aimed at by the one-kernel decompress
@@ -2500,7 +2502,7 @@ bool speculation_ranks(int64_t n, int64_t k, adatopk_dtype dt, bool aligned16, u
     for (int b = 1; b <= max_batches; b *= 2) {
         mu = static_cast<double>(k) * (static_cast<double>(b) * SAMPLE_BATCH * BLOCK * epd) / static_cast<double>(n);
         nb = b;
-        if (mu >= SPEC_GOOD_EXPECTED) break;
+        if (mu >= (epd == 2 ? SPEC_GOOD_EXPECTED_16 : SPEC_GOOD_EXPECTED)) break;
     }
     if (mu < SPEC_MIN_EXPECTED) return false;
     const double margin = SPEC_SIGMAS * sqrt(mu) + 2.0;
