@@ -131,6 +131,16 @@ struct SegState {  // one per segment; 64 bytes
 };
 static_assert(sizeof(SegState) == 64, "state record size");
 
+// The first eight words of a state record in two 16-byte loads (one memory round trip; field by field, the
+// window's fields are asked for only after spec_held has arrived).
+struct SegStateWords {
+    uint32_t loA, shwA, loB, shwB, Bw, c_gtw, spec_held;
+};
+__device__ __forceinline__ SegStateWords read_state(const SegState *st) {
+    const uint4 a = reinterpret_cast<const uint4 *>(st)[0], b = reinterpret_cast<const uint4 *>(st)[1];
+    return SegStateWords{a.x, a.y, a.z, a.w, b.x, b.y, b.z};
+}
+
 constexpr uint32_t FLAG_ALIGNED4 = 1u;  // tensor base is 4-byte aligned (always for fp32): dword loads allowed
 constexpr uint32_t FLAG_SPEC = 2u;      // the speculative pass runs for this tensor
 struct SegDesc {
@@ -458,6 +468,18 @@ __device__ __forceinline__ int find_segment(const Launch &a, int g) {
     const uint64_t owner_or_before = __ballot(g >= begin);  // begins never decrease and the first is 0
     return 63 - __builtin_clzll(owner_or_before | 1ull);
 }
+
+// An index the compiler knows nothing about.  For loads that are to be issued whatever a condition says
+// (an element past the end reads a valid stand-in and the value is dropped afterwards): if the compiler can
+// connect the stand-in with the condition it turns the load back into a guarded one, in a branch of its
+// own, and loads in neighbouring branches were seen to wait for one another.
+__device__ __forceinline__ uint32_t opaque(uint32_t i) {
+    asm("" : "+v"(i));
+    return i;
+}
+// All ones if keep, else zero, as a value the compiler cannot trace back to the condition: and-ing a loaded
+// value with it drops the value without making the load depend on the condition.
+__device__ __forceinline__ uint32_t keep_mask(bool keep) { return opaque(keep ? 0xFFFFFFFFu : 0u); }
 
 // Bucket search on per-block rows of suffix sums.  rows[r][NB] holds, for block r, the number of
 // its keys whose digit is >= d at entry d; coarse[r][NC] repeats every (NB / NC)-th entry
@@ -1242,25 +1264,34 @@ template <int VEC> struct ChunkSource {
     uint32_t lo;
     bool from_input;
     // entry i of the part: its raw pattern, and whether it is a candidate at all
+    // (Loads without a condition: an entry past the end reads the last one, or the first slot of an empty list,
+    // and is masked out.  Guarded, the four loads of a tile, or the eight of k_emit's, sit in branches of their
+    // own and were seen to wait for one another: a memory round trip per load instead of one for all.)
     __device__ __forceinline__ uint32_t raw(uint32_t i) const {
-        return i < len ? static_cast<uint32_t>(from_input ? x[i] : Lv[i]) : 0u;
+        const R *p = (from_input && len != 0) ? x : Lv;  // (an empty part of the input may start at the tensor's end)
+        const uint32_t v = static_cast<uint32_t>(p[opaque(i < len ? i : (len ? len - 1 : 0))]);
+        return v & keep_mask(i < len);
     }
+    // the same for an entry known to exist (whole tiles of a long part): no stand-in, no mask
+    __device__ __forceinline__ uint32_t raw_inside(uint32_t i) const { return static_cast<uint32_t>((from_input ? x : Lv)[i]); }
+    __device__ __forceinline__ int32_t index_inside(uint32_t i) const { return from_input ? static_cast<int32_t>(base + i) : Li[i]; }
     __device__ __forceinline__ bool is_candidate(uint32_t i, uint32_t r) const {
         return i < len && (!from_input || key_of<VEC>(r) >= lo);
     }
     __device__ __forceinline__ int32_t index(uint32_t i) const {
-        return from_input ? static_cast<int32_t>(base + i) : (i < len ? Li[i] : 0);
+        const uint32_t v = static_cast<uint32_t>(Li[opaque(from_input ? 0u : (i < len ? i : (len ? len - 1 : 0)))]);
+        return static_cast<int32_t>((v & keep_mask(!from_input && i < len)) | ((base + i) & keep_mask(from_input)));
     }
 };
 // Entries of part `part` of `sub` of chunk g's candidates (list entries, or the chunk's elements when
 // its list overflowed): the same cut as chunk_source below.  A short list leaves its later parts empty;
 // the list kernels return at once for those and skip what they would have stored.
-__device__ __forceinline__ uint32_t part_entries(const Launch &a, const SegDesc &sg, int g, uint32_t part, uint32_t sub) {
+__device__ __forceinline__ uint32_t part_entries(const Launch &a, const SegDesc &sg, int g, uint32_t count, uint32_t part,
+                                                 uint32_t sub) {  // count = a.cnt[g], loaded by the caller
     constexpr uint32_t LT = BLOCK * LU;
     const int c = g - sg.chunk_begin;
     const int64_t beg = static_cast<int64_t>(c) * a.E;
     const int64_t end = (beg + a.E < sg.n) ? beg + a.E : sg.n;
-    const uint32_t count = a.cnt[g];
     const uint32_t entries = count > a.cap ? static_cast<uint32_t>(end - beg) : count;
     if (sub == 1) return entries;
     uint32_t per = (entries + sub - 1) / sub;
@@ -1289,8 +1320,11 @@ __device__ __forceinline__ ChunkSource<VEC> chunk_source(const Launch &a, const 
     const uint64_t first = static_cast<uint64_t>(per) * part;
     const uint32_t off = first < entries ? static_cast<uint32_t>(first) : entries;
     src.len = (first + per < entries) ? per : entries - off;
-    src.Li = a.L_idx + static_cast<size_t>(g) * a.cap + off;
-    src.Lv = static_cast<const R *>(a.L_val) + static_cast<size_t>(g) * a.cap + off;
+    // (an empty part, or one that is read from the input, points at the start of the chunk's list: the loads
+    // that ChunkSource issues without a condition then stay inside the chunk's own region)
+    const uint32_t list_off = (src.from_input || src.len == 0) ? 0u : off;
+    src.Li = a.L_idx + static_cast<size_t>(g) * a.cap + list_off;
+    src.Lv = static_cast<const R *>(a.L_val) + static_cast<size_t>(g) * a.cap + list_off;
     src.x = static_cast<const R *>(sg.x) + beg + off;
     src.base = static_cast<uint32_t>(beg) + off;
     src.lo = lo;
@@ -1482,9 +1516,10 @@ template <int VEC, bool WIDE> __global__ __launch_bounds__(BLOCK) void k_refine(
     const int s = find_segment(a, g);
     const SegDesc &sg = a.seg[s];
     const int c = g - sg.chunk_begin;
-    const bool spec = a.state[s].spec_held != 0;
-    const uint32_t lo = spec ? a.state[s].loA : a.state[s].loB;
-    const uint32_t shw = spec ? a.state[s].shwA : a.state[s].shwB;
+    const SegStateWords stw = read_state(&a.state[s]);
+    const bool spec = stw.spec_held != 0;
+    const uint32_t lo = spec ? stw.loA : stw.loB;
+    const uint32_t shw = spec ? stw.shwA : stw.shwB;
     const uint32_t shl = VEC == TAG_F32 ? 0u : 16u;
     const ChunkSource<VEC> src = chunk_source<VEC>(a, sg, g, part, a.sub, lo);
     if (src.len == 0 && !(c == 0 && part == 0)) return;  // an empty part (the tensor's first part still reports Bw)
@@ -1534,8 +1569,13 @@ template <int VEC, bool WIDE> __global__ __launch_bounds__(BLOCK) void k_refine(
     // longer parts (large k, many ties), the end of a part read from the input: LU entries per thread at a time
     for (uint32_t i0 = i_next; i0 < src.len; i0 += LU * BLOCK) {
         uint32_t more[LU];
+        if (i0 + LU * BLOCK <= src.len) {  // uniform: a whole tile
 #pragma unroll
-        for (int j = 0; j < LU; ++j) more[j] = src.raw(i0 + j * BLOCK + threadIdx.x);
+            for (int j = 0; j < LU; ++j) more[j] = src.raw_inside(i0 + j * BLOCK + threadIdx.x);
+        } else {
+#pragma unroll
+            for (int j = 0; j < LU; ++j) more[j] = src.raw(i0 + j * BLOCK + threadIdx.x);
+        }
 #pragma unroll
         for (int j = 0; j < LU; ++j) count_entry(i0 + j * BLOCK + threadIdx.x, more[j]);
     }
@@ -1655,9 +1695,13 @@ template <int VEC, bool WIDE> __global__ __launch_bounds__(BLOCK) void k_emit(La
     const int s = find_segment(a, g);
     const SegDesc &sg = a.seg[s];
     const int c = g - sg.chunk_begin;
-    const bool spec = a.state[s].spec_held != 0;
-    const uint32_t lo = spec ? a.state[s].loA : a.state[s].loB;
-    const uint32_t shw = spec ? a.state[s].shwA : a.state[s].shwB;
+    const SegStateWords stw = read_state(&a.state[s]);
+    // thread t: the candidate count of the tensor's chunk t, for the offsets and the error sum further down
+    // (asked for here, with the state record: one memory round trip less in front of the rows' loads)
+    const uint32_t count_t = static_cast<int>(threadIdx.x) < sg.nchunks ? a.cnt[sg.chunk_begin + threadIdx.x] : 0u;
+    const bool spec = stw.spec_held != 0;
+    const uint32_t lo = spec ? stw.loA : stw.loB;
+    const uint32_t shw = spec ? stw.shwA : stw.shwB;
     const uint32_t kout = static_cast<uint32_t>(sg.k);
     const ChunkSource<VEC> src = chunk_source<VEC>(a, sg, g, part, sub, lo);
     // the tensor's last chunk is the short one, and the last part of a chunk the shortest
@@ -1666,11 +1710,20 @@ template <int VEC, bool WIDE> __global__ __launch_bounds__(BLOCK) void k_emit(La
     uint32_t raw[LU];
     int32_t id[LU];
     auto load_tile = [&](uint32_t t0) {
+        if (t0 + LU * BLOCK <= src.len) {  // uniform: a whole tile
 #pragma unroll
-        for (int j = 0; j < LU; ++j) {
-            const uint32_t i = t0 + j * BLOCK + threadIdx.x;
-            raw[j] = src.raw(i);
-            id[j] = src.index(i);
+            for (int j = 0; j < LU; ++j) {
+                const uint32_t i = t0 + j * BLOCK + threadIdx.x;
+                raw[j] = src.raw_inside(i);
+                id[j] = src.index_inside(i);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < LU; ++j) {
+                const uint32_t i = t0 + j * BLOCK + threadIdx.x;
+                raw[j] = src.raw(i);
+                id[j] = src.index(i);
+            }
         }
     };
     auto first_tile = [&]() { load_tile(0); };
@@ -1685,7 +1738,7 @@ template <int VEC, bool WIDE> __global__ __launch_bounds__(BLOCK) void k_emit(La
     const uint32_t *extra_gt;  // per-chunk count that is above T whatever the row says (fp32: the higher window bins)
     if (VEC == TAG_F32) {
         // last digit (k_refine's G3) -> T.  All candidates of one last-digit bin share one key.
-        const uint32_t Bw = a.state[s].Bw, c_gtw = a.state[s].c_gtw;
+        const uint32_t Bw = stw.Bw, c_gtw = stw.c_gtw;
         uint32_t my_bins[NB3 / BLOCK];  // raw counts of the last-digit bins this thread owns
 #pragma unroll
         for (int j = 0; j < NB3 / BLOCK; ++j) my_bins[j] = a.G3[s * NB3 + threadIdx.x * (NB3 / BLOCK) + j];
@@ -1716,10 +1769,12 @@ template <int VEC, bool WIDE> __global__ __launch_bounds__(BLOCK) void k_emit(La
         // ones of a bin add count * value^2.  Fixed summation order.
         if (sums_error) {
             double sum = 0.0;
-            for (int cc = threadIdx.x; cc < sg.nchunks; cc += BLOCK) {
+            static_assert(CTARGET <= BLOCK, "thread t has chunk t");
+            if (static_cast<int>(threadIdx.x) < sg.nchunks) {
+                const int cc = threadIdx.x;
                 sum += a.chunk_err[sg.chunk_begin + cc];
                 for (uint32_t pp = 0; pp < sub; ++pp)
-                    if (part_entries(a, sg, sg.chunk_begin + cc, pp, sub) != 0)  // an empty part stored nothing
+                    if (part_entries(a, sg, sg.chunk_begin + cc, count_t, pp, sub) != 0)  // an empty part stored nothing
                         sum += a.lerr[static_cast<size_t>(sg.chunk_begin + cc) * sub + pp];
             }
 #pragma unroll
@@ -1771,9 +1826,10 @@ template <int VEC, bool WIDE> __global__ __launch_bounds__(BLOCK) void k_emit(La
                     for (int r0 = rg; r0 < sg.nchunks; r0 += NW * 8) {
                         uint32_t v[8];
 #pragma unroll
-                        for (int u = 0; u < 8; ++u) {
+                        for (int u = 0; u < 8; ++u) {  // (loads without a condition, see ChunkSource)
                             const int rr = r0 + u * NW;
-                            v[u] = rr < sg.nchunks ? p[static_cast<size_t>(rr) * NBW] : 0u;
+                            const uint32_t t = p[static_cast<size_t>(opaque(static_cast<uint32_t>(rr < sg.nchunks ? rr : sg.nchunks - 1))) * NBW];
+                            v[u] = t & keep_mask(rr < sg.nchunks);
                         }
 #pragma unroll
                         for (int u = 0; u < 8; ++u) sum += v[u];
@@ -1805,7 +1861,7 @@ template <int VEC, bool WIDE> __global__ __launch_bounds__(BLOCK) void k_emit(La
         uint32_t gt_own = 0, eq_own = 0;                    // what part `part` itself holds
         if (static_cast<int>(threadIdx.x) < sg.nchunks && any_kept) {
             for (uint32_t pp = 0; pp < sub; ++pp) {
-                if (part_entries(a, sg, sg.chunk_begin + threadIdx.x, pp, sub) == 0) continue;  // nothing stored for it, nothing in it
+                if (part_entries(a, sg, sg.chunk_begin + threadIdx.x, count_t, pp, sub) == 0) continue;  // nothing stored for it, nothing in it
                 const size_t e = static_cast<size_t>(sg.chunk_begin + threadIdx.x) * sub + pp;
                 const uint32_t *r = cnt_rows + e * row_len;
                 const uint32_t above = (t_bin + 1 < t_bins) ? r[t_bin + 1] : 0u;
@@ -2197,11 +2253,33 @@ __device__ __forceinline__ void merge_span(const I *idx, const R *val, uint32_t 
     for (size_t i = va + nvec * 16 + threadIdx.x; i < byte_b; i += BLOCK) y[i] = 0;
     __syncthreads();  // also orders this workgroup's zero stores before its value stores
     R *out = reinterpret_cast<R *>(y);
-    // Four entries per thread at a time, loads first: a span that holds many entries (indices bunched
-    // together: a constant tensor keeps its first k elements, sorted data one end) would otherwise be a
-    // chain of one memory round trip per BLOCK entries.
-    const uint32_t jb = s_range[1];
-    for (uint32_t j0 = s_range[0] + threadIdx.x; j0 < jb; j0 += 4 * BLOCK) {
+    const uint32_t ja = s_range[0], jb = s_range[1];
+    if (jb - ja > 4 * BLOCK) {  // uniform over the workgroup
+        // A span that holds many entries although the tensor holds few (indices bunched together: a constant
+        // tensor keeps its first k elements, sorted data one end): twelve entries per thread at a time, with
+        // loads that do not depend on a condition (an entry past the end is read as the last one and not
+        // used), so that all of them are in flight together; guarded loads are issued one after the other,
+        // each waiting for the one before, and such a span took twice the whole kernel's usual time.
+        constexpr int AT_ONCE = 12;
+        const uint32_t last = jb - 1;
+        for (uint32_t j0 = ja + threadIdx.x; j0 < jb; j0 += AT_ONCE * BLOCK) {
+            int64_t i[AT_ONCE];
+            R v[AT_ONCE];
+#pragma unroll
+            for (int u = 0; u < AT_ONCE; ++u) {
+                const uint32_t j = j0 + u * BLOCK;
+                const uint32_t jc = j < last ? j : last;
+                i[u] = static_cast<int64_t>(idx[jc]);
+                v[u] = val[jc];
+            }
+#pragma unroll
+            for (int u = 0; u < AT_ONCE; ++u)
+                if (j0 + u * BLOCK < jb && i[u] >= ea && i[u] < eb) out[i[u]] = v[u];
+        }
+        return;
+    }
+    // the usual span: at most four entries per thread (one, mostly)
+    for (uint32_t j0 = ja + threadIdx.x; j0 < jb; j0 += 4 * BLOCK) {
         int64_t i[4];
         R v[4];
 #pragma unroll
@@ -2215,7 +2293,6 @@ __device__ __forceinline__ void merge_span(const I *idx, const R *val, uint32_t 
             if (i[u] >= ea && i[u] < eb) out[i[u]] = v[u];
     }
 }
-
 // The same for many entries per line (k / n of a few per cent and more), where k_merge's value
 // stores would rewrite most output lines a second time: same spans, same search, but the span is
 // built piece by piece in LDS (zeros, then the entries that fall into the piece) and every
