@@ -2063,11 +2063,17 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_small(const SmallL
     const R *x = static_cast<const R *>(sg.x);
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
 
+    // the whole tensor in one round of loads without conditions (see ChunkSource): an element past the end
+    // reads the last one and is masked out
     uint32_t raw[SMALL_EPT];
 #pragma unroll
-    for (int e = 0; e < SMALL_EPT; ++e) {
-        const int i = e * BLOCK + static_cast<int>(threadIdx.x);
-        raw[e] = (i < n) ? static_cast<uint32_t>(x[i]) : 0u;
+    for (int e = 0; e < SMALL_EPT; ++e) raw[e] = 0;
+    if (n > 0) {  // uniform
+#pragma unroll
+        for (int e = 0; e < SMALL_EPT; ++e) {
+            const int i = e * BLOCK + static_cast<int>(threadIdx.x);
+            raw[e] = static_cast<uint32_t>(x[opaque(static_cast<uint32_t>(i < n ? i : n - 1))]) & keep_mask(i < n);
+        }
     }
 
     // threshold key T, number of keys above it, tie quota q
