@@ -423,8 +423,8 @@ def value_structures(B, torch, np, wl, n=32 * 1024 * 768, reps=30):
              "uniform": lambda: rng.random(n, dtype=np.float32),
              "few_levels": lambda: wl.small_case("few_levels", n, 3),
              "mostly_zero_97pct": lambda: wl.small_case("sparse", n, 3),
-             "ascending": lambda: np.arange(1, n + 1, dtype=np.float32),
-             "descending": lambda: np.arange(n, 0, -1, dtype=np.float32),
+             "ascending": lambda: np.arange(1, n + 1, dtype=np.float64).astype(np.float32),
+             "descending": lambda: np.arange(n, 0, -1, dtype=np.float64).astype(np.float32),  # (in fp32 the step rounds to 0 above 2^24)
              "one_bucket": lambda: (1.0 + rng.random(n, dtype=np.float32) * 0.08).astype(np.float32),
              "all_equal": lambda: np.full(n, 1.5, dtype=np.float32),
              "all_zero": lambda: np.zeros(n, dtype=np.float32)}

@@ -431,11 +431,15 @@ __device__ __forceinline__ void hist_add(uint32_t *h, uint32_t bin, bool active)
 struct BinRun {
     uint32_t ref = 0xFFFFFFFFu;  // wave-uniform: the bin of the run (no bin is that large)
     uint32_t pend = 0;           // wave-uniform: counts not yet added to it
-    __device__ __forceinline__ void flush(uint32_t *h) {
-        if (pend != 0 && (threadIdx.x & 63) == 0) atomicAdd(&h[ref], pend);
+    // (h: the histogram in LDS, as a plain pointer or as one that names its address space)
+    template <typename P> static __device__ __forceinline__ void bin_add(P h, uint32_t bin, uint32_t count) {
+        __hip_atomic_fetch_add(&h[bin], count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    template <typename P> __device__ __forceinline__ void flush(P h) {
+        if (pend != 0 && (threadIdx.x & 63) == 0) bin_add(h, ref, pend);
         pend = 0;
     }
-    __device__ __forceinline__ void add(uint32_t *h, uint32_t bin, bool active) {
+    template <typename P> __device__ __forceinline__ void add(P h, uint32_t bin, bool active) {
         const uint64_t act = __ballot(active);
         const uint64_t same = __ballot(active && bin == ref);
         pend += static_cast<uint32_t>(__popcll(same));
@@ -445,7 +449,7 @@ struct BinRun {
             ref = __builtin_amdgcn_readlane(bin, leader);
             const uint64_t moved = __ballot(active && bin == ref);
             pend = static_cast<uint32_t>(__popcll(moved));
-            if (active && bin != ref && !((same >> (threadIdx.x & 63)) & 1ull)) atomicAdd(&h[bin], 1u);
+            if (active && bin != ref && !((same >> (threadIdx.x & 63)) & 1ull)) bin_add(h, bin, 1u);
         }
     }
 };
@@ -1352,11 +1356,6 @@ template <int VEC> struct Wide {
         const bool ok = src.from_input && (reinterpret_cast<uintptr_t>(src.x) & 15u) == 0;
         return ok ? src.len / ELEMS : 0u;
     }
-    static __device__ __forceinline__ void load(const ChunkSource<VEC> &src, uint32_t tile, dword4 (&v)[WIDE_U]) {
-        const dword4 *p = reinterpret_cast<const dword4 *>(src.x) + static_cast<size_t>(tile) * (BLOCK * WIDE_U) + threadIdx.x;
-#pragma unroll
-        for (int u = 0; u < WIDE_U; ++u) v[u] = __builtin_nontemporal_load(p + u * BLOCK);
-    }
     // element e (0 .. EPV) of a load, as the raw pattern of one element
     static __device__ __forceinline__ uint32_t elem(const dword4 &v, int e) {
         const int epd = EPV / 4;
@@ -1375,48 +1374,15 @@ template <int VEC> struct Wide {
 constexpr int DENSE_SLOTS = 16;
 constexpr uint32_t DENSE_ELEMS = BLOCK * DENSE_SLOTS;
 
-// f(tile, registers of the tile) for the wide tiles [0, t_end) of a part, in order, with two tiles
-// of loads in flight behind the one worked on: three register buffers used in turn, the loop body
-// written out per buffer so that none is ever copied (a copy would wait for its loads).  b0 holds
-// tile 0 already.  Same shape as the streaming loop of the scan.
-template <int VEC, typename F>
-__device__ __forceinline__ void wide_tiles_three(const ChunkSource<VEC> &src, uint32_t t_end, dword4 (&b0)[WIDE_U], F &&f) {
-    using W = Wide<VEC>;
-    dword4 b1[WIDE_U], b2[WIDE_U];
-    uint32_t t = 0, rem = t_end;
-    if (rem == 0) return;
-    if (rem >= 2) W::load(src, 1, b1);
-    while (rem >= 5) {
-        W::load(src, t + 2, b2);
-        __builtin_amdgcn_sched_barrier(0);
-        f(t++, b0);
-        W::load(src, t + 2, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        f(t++, b1);
-        W::load(src, t + 2, b1);
-        __builtin_amdgcn_sched_barrier(0);
-        f(t++, b2);
-        rem -= 3;
-    }
-    // one to four tiles left: b0 is loaded, b1 is if there are two
-    if (rem >= 3) W::load(src, t + 2, b2);
-    __builtin_amdgcn_sched_barrier(0);
-    f(t++, b0);
-    if (rem >= 2) {
-        if (rem >= 4) W::load(src, t + 2, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        f(t++, b1);
-        if (rem >= 3) f(t++, b2);
-        if (rem >= 4) f(t++, b0);
-    }
-}
-// f(tile, registers of the tile) for tiles [0, t_end) in order, two tiles of loads ahead: three register
-// buffers of N words used in turn (see wide_tiles_three); load(tile, buffer) fills one.  b0 holds tile 0
-// already.  For a loop that also stores: the loads of a tile are issued before the stores of the tile two
-// before it, so the wait for them does not have to let those stores drain first.
-template <int N, typename L, typename F>
-__device__ __forceinline__ void tiles_three(uint32_t t_end, uint32_t (&b0)[N], L &&load, F &&f) {
-    uint32_t b1[N], b2[N];
+// f(tile, registers of the tile) for tiles [0, t_end) in order, with two tiles of loads in flight behind
+// the one worked on: three register buffers of N loads used in turn, the loop body written out per buffer
+// so that none is ever copied (a copy would wait for its loads); load(tile, buffer) fills one.  b0 holds
+// tile 0 already.  Same shape as the streaming loop of the scan.  For a loop that also stores: the loads
+// of a tile are issued before the stores of the tile two before it, so the wait for them does not have to
+// let those stores drain first.
+template <typename E, int N, typename L, typename F>
+__device__ __forceinline__ void tiles_three(uint32_t t_end, E (&b0)[N], L &&load, F &&f) {
+    E b1[N], b2[N];
     uint32_t t = 0, rem = t_end;
     if (rem == 0) return;
     if (rem >= 2) load(1, b1);
@@ -1444,6 +1410,16 @@ __device__ __forceinline__ void tiles_three(uint32_t t_end, uint32_t (&b0)[N], L
     }
 }
 
+// A pointer argument of a function that is not inlined is generic, and loads through it are flat
+// loads: the hardware may serve them from LDS or from memory, out of order, so a wait for one tile
+// is a wait for every load in flight, and the tiles ahead are not ahead at all (measured: the dense
+// tiles of k_emit 2.4 us per call slower).  The two out-of-line passes below say where their memory
+// is: they convert their pointer arguments to these types before they use them.
+template <typename T> using GlobalPtr = T __attribute__((address_space(1))) *;
+template <typename T> using LdsPtr = T __attribute__((address_space(3))) *;
+template <typename T> __device__ __forceinline__ GlobalPtr<T> in_global(T *p) { return (GlobalPtr<T>)p; }
+template <typename T> __device__ __forceinline__ LdsPtr<T> in_lds(T *p) { return (LdsPtr<T>)p; }
+
 // k_refine's counts over the wide tiles of a part read from the input.  Out of line: inlined, its seven
 // copies of the tile body sit in the middle of the kernel and the path of an ordinary part (a list of a
 // few hundred entries, microseconds in all) pays for them in instruction fetch and register allocation.
@@ -1453,15 +1429,21 @@ struct DenseCounts {
 };
 template <int VEC>
 __device__ __attribute__((noinline)) DenseCounts refine_wide_tiles(const ChunkSource<VEC> src, uint32_t wide_tiles, uint32_t lo,
-                                                                   uint32_t shw, uint32_t Bw, uint32_t *h3) {
+                                                                   uint32_t shw, uint32_t Bw, uint32_t *h3_arg) {
     using WR = Wide<VEC>;
+    const GlobalPtr<const dword4> x = in_global(reinterpret_cast<const dword4 *>(src.x)) + threadIdx.x;
+    const LdsPtr<uint32_t> h3 = in_lds(h3_arg);
+    auto load = [&](uint32_t tile, dword4(&v)[WIDE_U]) {  // thread t: the t-th, (BLOCK + t)-th ... 16 bytes of the tile
+#pragma unroll
+        for (int u = 0; u < WIDE_U; ++u) v[u] = __builtin_nontemporal_load(x + static_cast<size_t>(tile) * (BLOCK * WIDE_U) + u * BLOCK);
+    };
     const uint32_t shl = VEC == TAG_F32 ? 0u : 16u;
     const uint32_t in_bin = (1u << shw) - 1u;
     DenseCounts out = {0u, 0.0};
     dword4 cur[WIDE_U];
-    WR::load(src, 0, cur);
+    load(0, cur);
     BinRun run;
-    wide_tiles_three<VEC>(src, wide_tiles, cur, [&](uint32_t, const dword4(&v)[WIDE_U]) {
+    tiles_three(wide_tiles, cur, load, [&](uint32_t, const dword4(&v)[WIDE_U]) {
         // a wavefront whose whole share of the tile is one key (a constant tensor) counts it once
         const uint32_t raw0 = __builtin_amdgcn_readfirstlane(WR::elem(v[0], 0));
         uint32_t other = 0;
@@ -1475,7 +1457,7 @@ __device__ __attribute__((noinline)) DenseCounts refine_wide_tiles(const ChunkSo
             const uint32_t bin = window_bin(key, lo, shw);
             if (key >= lo) {
                 if (bin > Bw) out.def += PER_LANE;
-                if (bin == Bw && (threadIdx.x & 63) == 0) atomicAdd(&h3[((key - lo) & in_bin) >> shl], 64u * PER_LANE);
+                if (bin == Bw && (threadIdx.x & 63) == 0) BinRun::bin_add(h3, ((key - lo) & in_bin) >> shl, 64u * PER_LANE);
                 if (bin < Bw) {
                     const double xd = static_cast<double>(value_of<VEC>(raw0));
                     out.acc = fma(static_cast<double>(PER_LANE) * xd, xd, out.acc);
@@ -1483,6 +1465,32 @@ __device__ __attribute__((noinline)) DenseCounts refine_wide_tiles(const ChunkSo
             }
             return;
         }
+        // Sorted data: a wavefront whose smallest key lies in a bin above Bw only counts (the kept end),
+        // one whose keys are all candidates in bins below Bw only sums squares (the dropped end).
+        uint32_t least = 0xFFFFFFFFu, most = 0;
+#pragma unroll
+        for (int u = 0; u < WIDE_U; ++u)
+#pragma unroll
+            for (int e = 0; e < WR::EPV; ++e) {
+                const uint32_t key = key_of<VEC>(WR::elem(v[u], e));
+                least = key < least ? key : least;
+                most = key > most ? key : most;
+            }
+        if (__ballot(!(least >= lo && window_bin(least, lo, shw) > Bw)) == 0) {  // wave-uniform
+            out.def += WIDE_U * WR::EPV;
+            return;
+        }
+        if (__ballot(!(least >= lo && window_bin(most, lo, shw) < Bw)) == 0) {  // wave-uniform
+#pragma unroll
+            for (int u = 0; u < WIDE_U; ++u)
+#pragma unroll
+                for (int e = 0; e < WR::EPV; ++e) {
+                    const double xd = static_cast<double>(value_of<VEC>(WR::elem(v[u], e)));
+                    out.acc = fma(xd, xd, out.acc);
+                }
+            return;
+        }
+        bool in_Bw = false;
 #pragma unroll
         for (int u = 0; u < WIDE_U; ++u)
 #pragma unroll
@@ -1492,9 +1500,18 @@ __device__ __attribute__((noinline)) DenseCounts refine_wide_tiles(const ChunkSo
                 const bool cand = key >= lo;
                 const uint32_t bin = window_bin(key, lo, shw);
                 out.def += (cand && bin > Bw) ? 1u : 0u;
-                run.add(h3, ((key - lo) & in_bin) >> shl, cand && bin == Bw);
+                in_Bw |= cand && bin == Bw;
                 const double xd = (cand && bin < Bw) ? static_cast<double>(value_of<VEC>(raw)) : 0.0;
                 out.acc = fma(xd, xd, out.acc);
+            }
+        // the last digit is counted only where the wavefront has a key in bin Bw at all (sorted data: one tile)
+        if (__ballot(in_Bw) == 0) return;  // wave-uniform
+#pragma unroll
+        for (int u = 0; u < WIDE_U; ++u)
+#pragma unroll
+            for (int e = 0; e < WR::EPV; ++e) {
+                const uint32_t key = key_of<VEC>(WR::elem(v[u], e));
+                run.add(h3, ((key - lo) & in_bin) >> shl, key >= lo && window_bin(key, lo, shw) == Bw);
             }
     });
     run.flush(h3);
@@ -1600,37 +1617,41 @@ template <int VEC, bool WIDE> __global__ __launch_bounds__(BLOCK) void k_refine(
 template <int VEC>
 __device__ __attribute__((noinline)) uint2 emit_dense_tiles(const ChunkSource<VEC> src, uint32_t dense_tiles, uint32_t T, uint32_t q,
                                                             uint32_t kout, uint32_t run_gt, uint32_t run_eq, bool no_gt,
-                                                            int32_t *oi, int64_t *oi64, typename Raw<VEC>::type *ov, bool wide,
-                                                            uint32_t *totals) {
+                                                            int32_t *oi_arg, int64_t *oi64_arg, typename Raw<VEC>::type *ov_arg, bool wide,
+                                                            uint32_t *totals_arg) {
     using R = typename Raw<VEC>::type;
+    const GlobalPtr<const R> x = in_global(src.x);
+    const GlobalPtr<int32_t> oi = in_global(oi_arg);
+    const GlobalPtr<int64_t> oi64 = in_global(oi64_arg);
+    const GlobalPtr<R> ov = in_global(ov_arg);
+    const LdsPtr<uint32_t> totals = in_lds(totals_arg);
     static_assert(DENSE_ELEMS < 65536, "two 16-bit counts travel in one word");
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     // element (slot j, this lane) of dense tile t of the part: wavefront w owns the w-th eighth of the tile
     auto dense_entry = [&](uint32_t t, int j) { return t * DENSE_ELEMS + (static_cast<uint32_t>(w) * DENSE_SLOTS + j) * 64 + lane; };
     auto dense_load = [&](uint32_t t, uint32_t(&r)[DENSE_SLOTS]) {
-        const R *p = src.x + dense_entry(t, 0);
+        const GlobalPtr<const R> p = x + dense_entry(t, 0);
 #pragma unroll
         for (int j = 0; j < DENSE_SLOTS; ++j) r[j] = __builtin_nontemporal_load(p + j * 64);
     };
     uint32_t cur[DENSE_SLOTS];
     dense_load(0, cur);
     int buf = 0;
-    tiles_three<DENSE_SLOTS>(dense_tiles, cur, dense_load, [&](uint32_t t, const uint32_t(&r)[DENSE_SLOTS]) {
+    tiles_three(dense_tiles, cur, dense_load, [&](uint32_t t, const uint32_t(&r)[DENSE_SLOTS]) {
         if (no_gt && run_eq >= q) return;  // uniform: nothing above T in the part and the quota of ties used up
-        uint32_t before[DENSE_SLOTS];  // (above T, equal to T) before this lane's element within the wavefront's run
-        uint32_t wave_run = 0;          // wave-uniform: the same over the slots done so far
+        // The wavefront's totals first; a lane's own counts inside the wavefront's run only where a tile
+        // is kept in part (further down): a tile kept whole or dropped whole does not need them.
+        uint32_t wave_run = 0;  // wave-uniform
 #pragma unroll
         for (int j = 0; j < DENSE_SLOTS; ++j) {
             const uint32_t key = key_of<VEC>(r[j]);
-            const uint64_t bg = __ballot(key > T), be = __ballot(key == T);
-            before[j] = wave_run + lanes_below(bg) + (lanes_below(be) << 16);
-            wave_run += static_cast<uint32_t>(__popcll(bg)) + (static_cast<uint32_t>(__popcll(be)) << 16);
+            wave_run += static_cast<uint32_t>(__popcll(__ballot(key > T))) + (static_cast<uint32_t>(__popcll(__ballot(key == T))) << 16);
         }
-        uint32_t *tot = totals + buf * NW;
+        const LdsPtr<uint32_t> tot = totals + buf * NW;
         if (lane == 0) tot[w] = wave_run;
         __syncthreads();
         uint32_t lower, tile_total;  // wave-uniform
-        wave_counts(tot, lower, tile_total);
+        wave_counts((const uint32_t *)tot, lower, tile_total);
         buf ^= 1;
         const uint32_t tile_gt = tile_total & 0xFFFFu, tile_eq = tile_total >> 16;
         const uint32_t first_pos = run_gt + run_eq;  // of the tile's first kept element while the quota lasts
@@ -1651,10 +1672,13 @@ __device__ __attribute__((noinline)) uint2 emit_dense_tiles(const ChunkSource<VE
 #pragma unroll
             for (int j = 0; j < DENSE_SLOTS; ++j) ov[first_pos + in_tile + j * 64] = static_cast<R>(r[j]);
         } else if (tile_total != 0) {  // uniform over the workgroup
+            uint32_t slots_before = lower;  // wave-uniform: (above T, equal to T) of the tile before slot j of this wavefront
 #pragma unroll
             for (int j = 0; j < DENSE_SLOTS; ++j) {
                 const uint32_t key = key_of<VEC>(r[j]);
-                const uint32_t mine = lower + before[j];
+                const uint64_t bg = __ballot(key > T), be = __ballot(key == T);
+                const uint32_t mine = slots_before + lanes_below(bg) + (lanes_below(be) << 16);
+                slots_before += static_cast<uint32_t>(__popcll(bg)) + (static_cast<uint32_t>(__popcll(be)) << 16);
                 const uint32_t gt_before = run_gt + (mine & 0xFFFFu), eq_before = run_eq + (mine >> 16);
                 if (key > T || (key == T && eq_before < q)) {
                     const uint32_t pos = gt_before + (eq_before < q ? eq_before : q);

@@ -214,10 +214,10 @@ def small_case(kind: str, n: int, seed: int, dtype: str = "f32") -> np.ndarray:
         u[(pick >= 0.04) & (pick < 0.06)] = rng.integers(1, 1 << 22, size=n, dtype=np.uint32)[(pick >= 0.04) & (pick < 0.06)]
     elif kind == "random_bits":  # every bit pattern equally likely
         x = rng.integers(0, 1 << 32, size=n, dtype=np.uint64).astype(np.uint32).view(np.float32)
-    elif kind == "descending":
-        x = np.arange(n, 0, -1, dtype=np.float32)
+    elif kind == "descending":  # (counted in fp64: an fp32 arange has step 0 once n passes 2^24)
+        x = np.arange(n, 0, -1, dtype=np.float64).astype(np.float32)
     elif kind == "ascending":
-        x = np.arange(1, n + 1, dtype=np.float32)
+        x = np.arange(1, n + 1, dtype=np.float64).astype(np.float32)
     else:
         raise ValueError(kind)
     if dtype == "bf16":

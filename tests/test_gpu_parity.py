@@ -83,6 +83,26 @@ def test_dense_chunks_of_a_large_tensor_are_read_again_from_the_input(dtype):
     check_one(cases[0][1][: n // 2], n // 300, offset_elems=1, label="all_equal offset 1 %s" % dtype)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_chunks_kept_whole_in_a_batch_of_few_chunks(dtype):
+    # Four tensors in one call, under 256 chunks of one tile together: the launch shape in which a batch
+    # takes the list kernels' form for one workgroup per chunk, with dense chunks read in wide tiles.
+    # Constant tensor (whole chunks kept, then the quota ends inside one), sorted either way (the last
+    # chunk of the ascending one is short and kept whole), and an ordinary tensor between them.
+    import gpu_harness as H
+
+    ns = [500_000, 400_003, 300_000, 450_001]
+    xs = [wl.small_case("all_equal", ns[0], 3, dtype), wl.small_case("descending", ns[1], 3, dtype),
+          wl.small_case("normal", ns[2], 3, dtype), wl.small_case("ascending", ns[3], 3, dtype)]
+    ks = [25_000 + 77, 40_000, 3_000, 8192 * 5 + 4321]
+    gi, gv, off, ge = H.gpu_compress_segmented(xs, ks)
+    for s, (x, k) in enumerate(zip(xs, ks)):
+        ri, rv, re = orc.compress(x, k)
+        assert np.array_equal(gi[off[s]:off[s + 1]], ri), "indices differ, tensor %d %s" % (s, dtype)
+        assert np.array_equal(H.bits(gv[off[s]:off[s + 1]]), H.bits(rv)), "values differ, tensor %d %s" % (s, dtype)
+        assert H.same_err(ge[s], re, ERR_RTOL), "err %r vs %r, tensor %d %s" % (ge[s], re, s, dtype)
+
+
 def test_ties_straddling_tiles_and_chunks():
     # the tied value sits on both sides of every tile and chunk boundary; the quota ends mid-way
     n = 300_000

@@ -51,6 +51,24 @@ def test_compress_wire_is_the_oracle_message(dtype, ib):
 
 
 @pytest.mark.parametrize("ib", [4, 8])
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_message_of_a_tensor_with_chunks_kept_whole(dtype, ib):
+    # constant and sorted tensors: whole chunks of the input go into the message as they are (the dense
+    # tiles of the placing kernel), with either index width
+    import gpu_harness as H
+
+    n = 3_000_017
+    for kind, k in (("all_equal", 60_000 + 13), ("ascending", 70_001), ("descending", 16_384 * 3)):
+        x = wl.small_case(kind, n, seed=11, dtype=dtype)
+        ri, rv, re = orc.compress(x, k)
+        ref = wf.pack(ri, rv, n, float(re), 50.0, ib)
+        got = gpu_message(x, k, ib, 50.0)
+        assert len(got) == len(ref)
+        assert got[:12] == ref[:12] and got[16:] == ref[16:], (dtype, ib, kind)
+        assert H.same_err(struct.unpack("<f", got[12:16])[0], re, ERR_RTOL)
+
+
+@pytest.mark.parametrize("ib", [4, 8])
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_decompress_wire_overwrite_and_accumulate(dtype, ib):
     import torch
