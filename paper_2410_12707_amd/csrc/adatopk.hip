@@ -772,9 +772,13 @@ template <int VEC> __global__ __launch_bounds__(BLOCK) void k_hist1(Launch a) {
 // consecutive list slots of the chunk; the stage goes out to memory with full-width stores only
 // when it would overflow and at the end of the chunk, so the streaming loop itself issues loads
 // only (loads and stores share one in-order counter: a store inside the loop would make every wait
-// for the next tile's loads drain it).  A tile that alone holds more than STAGE_CAP pairs (dense
-// input, k close to n) stores directly.  List slots beyond the chunk's capacity are counted, not
-// stored: such a chunk is read from the input again by the kernels that follow.
+// for the next tile's loads drain it).  List slots beyond the chunk's capacity are counted, not
+// stored: such a chunk is read from the input again by the kernels that follow.  A tile that alone
+// holds more than STAGE_CAP pairs (a quarter of its elements: a constant tensor, many ties, the kept
+// end of sorted data) does not go through the stage; in the scan of a single tensor it gives the
+// chunk's list up at once, so that nothing more is stored for a chunk that will be read again
+// (storing such tiles until the list was full cost a constant tensor 50 MB of writes that nobody
+// read); in the scan of a batch it stores directly while the list has room.
 constexpr int STAGE_CAP = 2048;
 
 // Writes list slots [from, to) of the chunk from the stage to memory and counts their window bins.
@@ -796,8 +800,8 @@ template <int VEC, bool FAST, bool RUNS>
 __device__ __forceinline__ void scan_tile(const uint32_t (&dw)[Stream<VEC>::SLOTS],
                                           const uint32_t (&valid)[Stream<VEC>::SLOTS], int64_t t0, uint32_t lo,
                                           uint32_t shw, uint32_t *hw, uint32_t *wcnt, uint2 *stage, uint32_t &running,
-                                          uint32_t &flushed, uint32_t cap, int32_t *Li,
-                                          typename Raw<VEC>::type *Lv, double &acc) {
+                                          uint32_t &flushed, uint32_t &cap, int32_t *Li,
+                                          typename Raw<VEC>::type *Lv, double &acc) {  // cap: 0 once the list is given up
     using St = Stream<VEC>;
     using R = typename Raw<VEC>::type;
     constexpr int EPD = St::EPD, SLOTS = St::SLOTS;
@@ -898,24 +902,8 @@ __device__ __forceinline__ void scan_tile(const uint32_t (&dw)[Stream<VEC>::SLOT
         }
     } else if (RUNS) {
         // A dense tile in the variant with one workgroup per compute unit, whose register budget has
-        // room for it: the stores only while the list has room, then the window bins by runs.
-        if (running < cap) {  // uniform
-#pragma unroll
-            for (int e = 0; e < SLOTS; ++e) {
-                uint32_t pos = slot_base;
-#pragma unroll
-                for (int hh = 0; hh < EPD; ++hh) pos = lanes_below_plus(m[e][hh], pos);
-#pragma unroll
-                for (int hh = 0; hh < EPD; ++hh) {
-                    if (keep[e][hh] && pos < cap) {
-                        Li[pos] = static_cast<int32_t>(i_lane + e * 64 * EPD + hh);
-                        Lv[pos] = static_cast<R>(elem_of<VEC>(dw[e], hh));
-                    }
-                    pos += keep[e][hh] ? 1u : 0u;
-                    slot_base += __popcll(m[e][hh]);
-                }
-            }
-        }
+        // room for it: the window bins by runs.  Nothing is stored, the list is given up.
+        cap = 0;
         // A wavefront whose whole share of the tile is kept and sits in one bin (a constant tensor) adds once.
         const uint32_t bin0 = __builtin_amdgcn_readfirstlane(window_bin(key_of<VEC>(elem_of<VEC>(dw[0], 0)), lo, shw));
         uint32_t other = 0;
@@ -935,6 +923,8 @@ __device__ __forceinline__ void scan_tile(const uint32_t (&dw)[Stream<VEC>::SLOT
             run.flush(hw);
         }
     } else {
+        // (the variant with two workgroups per compute unit has no register to spare for a list that
+        // ends early: it stores while the list has room)
 #pragma unroll
         for (int e = 0; e < SLOTS; ++e) {
             uint32_t pos = slot_base;
@@ -1165,7 +1155,7 @@ __global__ __launch_bounds__(BLOCK, DEPTH == 2 ? 4 : 2) void k_scan(Launch a) {
             a.state[s].shwB = shw;
         }
     }
-    const uint32_t cap = a.cap;
+    uint32_t cap = a.cap;  // 0 once a dense tile has made the scan give the chunk's list up
     int32_t *Li = a.L_idx + static_cast<size_t>(g) * cap;
     R *Lv = static_cast<R *>(a.L_val) + static_cast<size_t>(g) * cap;
 
@@ -1243,7 +1233,8 @@ __global__ __launch_bounds__(BLOCK, DEPTH == 2 ? 4 : 2) void k_scan(Launch a) {
     const double bsum = block_sum_f64(acc, smd);
     if (threadIdx.x == 0) {
         a.chunk_err[g] = bsum;
-        a.cnt[g] = running;
+        // more than the list holds = "read this chunk from the input", also for a list that was given up
+        a.cnt[g] = (cap == 0 && running <= a.cap) ? a.cap + 1 : running;
     }
     __syncthreads();
     if (SPEC && threadIdx.x == 0) a.cpairA[g] = make_uint2(running, hw[NBW - 1]);
