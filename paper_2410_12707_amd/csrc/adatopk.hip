@@ -1722,6 +1722,10 @@ template <int VEC, bool WIDE> __global__ __launch_bounds__(BLOCK) void k_emit(La
     const ChunkSource<VEC> src = chunk_source<VEC>(a, sg, g, part, sub, lo);
     // the tensor's last chunk is the short one, and the last part of a chunk the shortest
     const bool sums_error = c == sg.nchunks - 1 && part == sub - 1 && a.err_out != nullptr;
+    // 16-bit types: thread t of that workgroup asks for chunk t's sum of squares below the window now, so that it
+    // arrives behind the prologue instead of costing the error sum a memory round trip of its own at the end
+    double below_t = 0.0;
+    if (VEC != TAG_F32 && sums_error && static_cast<int>(threadIdx.x) < sg.nchunks) below_t = a.chunk_err[sg.chunk_begin + threadIdx.x];
 
     uint32_t raw[LU];
     int32_t id[LU];
@@ -1831,10 +1835,17 @@ template <int VEC, bool WIDE> __global__ __launch_bounds__(BLOCK) void k_emit(La
         if (sums_error) {
             // nothing kept means k = 0, for which the window starts above every key: no candidates at all
             const uint32_t ncols = any_kept ? Bw + 2 : 0u;  // S[Bw + 1] is the last one needed (0 past the last bin)
-            for (uint32_t b = threadIdx.x; b < NBW + 1; b += BLOCK) h[b] = 0;
-            __syncthreads();
+            // With the k-th key in the window's first 31 bins (the usual case for bf16, whose window starts
+            // a few patterns below it) the sums S[0 .. Bw + 1] are among those column_pick has just left in h
+            // (behind its NCW coarse sums: the fine sums of the first NBW / NCW bins): nothing to add up.
+            const bool have_sums = any_kept && Bw + 1 < NBW / NCW;  // uniform
+            const uint32_t *S = have_sums ? h + NCW : h;
+            if (!have_sums) {
+                for (uint32_t b = threadIdx.x; b < NBW + 1; b += BLOCK) h[b] = 0;
+                __syncthreads();
+            }
             const uint32_t col = threadIdx.x & 63, rg = threadIdx.x >> 6;
-            for (uint32_t c0 = 0; c0 < ncols && c0 < NBW; c0 += 64) {
+            for (uint32_t c0 = 0; !have_sums && c0 < ncols && c0 < NBW; c0 += 64) {
                 const uint32_t b = c0 + col;
                 if (b < ncols && b < NBW) {
                     const uint32_t *p = a.rowsW + static_cast<size_t>(sg.chunk_begin) * NBW + b;
@@ -1854,10 +1865,10 @@ template <int VEC, bool WIDE> __global__ __launch_bounds__(BLOCK) void k_emit(La
                 }
             }
             __syncthreads();
-            double sum = 0.0;
-            for (int cc = threadIdx.x; cc < sg.nchunks; cc += BLOCK) sum += a.chunk_err[sg.chunk_begin + cc];
+            static_assert(CTARGET <= BLOCK, "thread t has chunk t");
+            double sum = below_t;
             for (uint32_t b = threadIdx.x; any_kept && b <= Bw; b += BLOCK) {
-                uint32_t dropped = h[b] - h[b + 1];
+                uint32_t dropped = S[b] - S[b + 1];
                 if (b == Bw) dropped -= q;
                 if (dropped) {  // the open-ended last bin is never below Bw: a dropped bin is one pattern
                     const double v = static_cast<double>(value_of<VEC>((lo + (b << shw)) >> 16));
