@@ -894,11 +894,21 @@ __device__ __forceinline__ void scan_tile(const uint32_t (&dw)[Stream<VEC>::SLOT
             uint32_t pos = slot_base;
 #pragma unroll
             for (int hh = 0; hh < EPD; ++hh) pos = lanes_below_plus(m[e][hh], pos);
+            if constexpr (EPD == 2) {
+                // (a lane's two halves are neighbours in the list: one address, the second eight bytes on if the first is kept)
+                char *p = reinterpret_cast<char *>(dst + pos);
+                const uint32_t i0 = i_lane + e * 64 * EPD;
+                if (keep[e][0]) *reinterpret_cast<uint2 *>(p) = make_uint2(i0, elem_of<VEC>(dw[e], 0));
+                p += keep[e][0] ? sizeof(uint2) : 0;
+                if (keep[e][1]) *reinterpret_cast<uint2 *>(p) = make_uint2(i0 + 1, elem_of<VEC>(dw[e], 1));
+                slot_base += __popcll(m[e][0]) + __popcll(m[e][1]);
+            } else {
 #pragma unroll
-            for (int hh = 0; hh < EPD; ++hh) {
-                if (keep[e][hh]) dst[pos] = make_uint2(i_lane + e * 64 * EPD + hh, elem_of<VEC>(dw[e], hh));
-                pos += keep[e][hh] ? 1u : 0u;
-                slot_base += __popcll(m[e][hh]);
+                for (int hh = 0; hh < EPD; ++hh) {
+                    if (keep[e][hh]) dst[pos] = make_uint2(i_lane + e * 64 * EPD + hh, elem_of<VEC>(dw[e], hh));
+                    pos += keep[e][hh] ? 1u : 0u;
+                    slot_base += __popcll(m[e][hh]);
+                }
             }
         }
     } else if (RUNS) {
