@@ -103,6 +103,37 @@ def test_chunks_kept_whole_in_a_batch_of_few_chunks(dtype):
         assert H.same_err(ge[s], re, ERR_RTOL), "err %r vs %r, tensor %d %s" % (ge[s], re, s, dtype)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("share,width,kept", [(0.06, 200, range(60, 161, 10)), (0.03, 300, range(60, 221, 10)),
+                                              (0.0046, 400, range(50, 301, 25))])
+def test_error_norm_of_16bit_types_as_the_threshold_moves_through_the_window(dtype, share, width, kept):
+    # A share of the elements is spread evenly over `width` consecutive 16-bit patterns, the rest lie far
+    # below; k keeps a growing number of those patterns.  The window that the sample sets starts a certain
+    # fraction of k below the threshold (the larger k, the smaller the fraction), so the three settings put
+    # the threshold's window bin at 11-24, at 25-37 (29, 30, 31, 32, 33 among them) and at 90-145 (with the
+    # thinnest spread the sample also misses at both ends of the range, and the exact passes run).  Up to
+    # bin 30 the error norm takes the window's column sums from the bucket search, beyond it adds them up
+    # itself.
+    import gpu_harness as H
+
+    n = (1 << 20) + 4099
+    rng = np.random.Generator(np.random.PCG64(23))
+    top = 0x4100 if dtype == "bf16" else 0x4A00  # patterns of 8.0 upwards (bf16) / 12.0 upwards (fp16)
+    low = (0x3000, 0x3400) if dtype == "bf16" else (0x2000, 0x2800)
+    pats = rng.integers(low[0], low[1], size=n, dtype=np.uint32).astype(np.uint16)
+    spread = rng.random(n) < share
+    pats[spread] = (top + rng.integers(0, width, size=int(spread.sum()))).astype(np.uint16)
+    pats[rng.random(n) < 0.5] |= np.uint16(0x8000)
+    x = pats if dtype == "bf16" else pats.view(np.float16)
+    per_pattern = int(spread.sum()) // width
+    for kept_patterns in kept:
+        k = kept_patterns * per_pattern + 17
+        ri, rv, re = orc.compress(x, k)
+        gi, gv, ge = H.gpu_compress(x, k)
+        assert np.array_equal(gi, ri) and np.array_equal(H.bits(gv), H.bits(rv)), (dtype, kept_patterns)
+        assert H.same_err(ge, re, ERR_RTOL), "err %r vs %r with %d patterns kept, %s" % (ge, re, kept_patterns, dtype)
+
+
 def test_ties_straddling_tiles_and_chunks():
     # the tied value sits on both sides of every tile and chunk boundary; the quota ends mid-way
     n = 300_000
